@@ -1,0 +1,154 @@
+/*
+ * flashsketch.h -- C ABI of the MI355X (gfx950) BlockPerm-SJLT sketch library.
+ *
+ * The library applies a sparse sketch S (k x d) to a dense A (d x n) and
+ * returns Y = S A (k x n)  (paper Section 3 "Notation": A in R^{d x n},
+ * S in R^{k x d}, Y := S A).
+ *
+ * S is never stored.  It is a pure function of (d, k, Bc, Br, kappa, s, seed):
+ *   - an M x M grid of Br x Bc blocks, M = d/Bc = k/Br (Section 4, "Block model");
+ *   - block (g, h) is nonzero iff h = f^l(g) for some l in 1..kappa, where
+ *     f(x) = (a x + b) mod M is a full-period affine map whose (a, b) are
+ *     derived from the seed (Section 4, "Block-level wiring"; Appendix E,
+ *     "Full-cycle affine construction");
+ *   - every column of a nonzero block has exactly s entries +-1 at distinct
+ *     rows given by a 32-bit hash of (seed, g, h, local row) (Section 4,
+ *     "Intra-block SJLT mixing"; Appendix E, "Within-block hashing");
+ *   - all entries are scaled by 1/sqrt(kappa*s) (Alg. 1, scaling step).
+ *
+ * Conventions
+ *   Layout     A is row-major d x n: element (u, t) at A[u*lda + t]; lda >= n,
+ *              counted in ELEMENTS.  out is row-major k x n with leading
+ *              dimension ldo >= n (fs_sketch_apply: ldo = n).  The n columns
+ *              are the vectors being sketched.
+ *   Pointers   A, out, rows, signs, S_dense and workspaces are DEVICE pointers
+ *              owned by the caller.  Handles and fs_info are HOST objects.
+ *   Alignment  A and out must be aligned to their element size.  The fast
+ *              kernels additionally want 16-byte aligned bases and
+ *              lda*sizeof(elt) a multiple of 16; otherwise a slower generic
+ *              kernel is used (never an error).
+ *   Streams    `stream` is a hipStream_t passed as void* (NULL = default
+ *              stream).  Calls enqueue work and return; they never synchronise.
+ *              A handle must not be used from two streams at the same time
+ *              (its workspace is shared).
+ *   Precision  accumulation is always fp32; one fp32 multiply by
+ *              (float)(1/sqrt(kappa*s)) follows; bf16 outputs are rounded to
+ *              nearest-even.
+ *   Errors     every call returns fs_status; nothing throws, aborts or prints.
+ *              Argument errors are detected before any HIP call is made.
+ *   Determinism FS_KIND_BLOCKPERM uses no atomics on data: the same inputs give
+ *              bit-identical outputs.  FS_KIND_SJLT_SCATTER sums with global
+ *              float atomics and is order-nondeterministic by construction.
+ */
+#ifndef FLASHSKETCH_H
+#define FLASHSKETCH_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct fs_sketch_s* fs_sketch_t; /* opaque host handle */
+
+typedef enum {
+  FS_OK = 0,
+  FS_ERR_INVALID_ARG = 1, /* bad pointer, size, divisibility, range        */
+  FS_ERR_UNSUPPORTED = 2, /* valid request this build has no kernel for    */
+  FS_ERR_ALLOC = 3,       /* host or device allocation failed              */
+  FS_ERR_HIP = 4          /* a HIP runtime call failed (see fs_info)       */
+} fs_status;
+
+typedef enum { FS_F32 = 0, FS_BF16 = 1 } fs_dtype; /* dtype of A and of out */
+
+typedef enum {
+  FS_KIND_BLOCKPERM = 0,    /* the paper's sketch (Section 4)                              */
+  FS_KIND_SJLT_SCATTER = 1, /* prior-art baseline: plain SJLT, global scatter-add
+                               (Section 3 "GPU bottlenecks for Sparse Sketching").
+                               Same S as BLOCKPERM with M = 1: needs Bc = d, Br = k,
+                               kappa = 1.                                                  */
+  FS_KIND_GAUSS_DENSE = 2   /* dense Gaussian sketch S_ij ~ N(0, 1/k) (Section 1) applied
+                               by an MFMA GEMM; Bc, Br, kappa, s are ignored.              */
+} fs_kind;
+
+/* Kernel variants of the BLOCKPERM apply (fs_sketch_set_variant). */
+typedef enum {
+  FS_VARIANT_AUTO = 0,    /* pick by shape/dtype/alignment                          */
+  FS_VARIANT_GENERIC = 1, /* one lane per column, LDS-private output tile, any Br   */
+  FS_VARIANT_MFMA = 2     /* +-1 operand on the matrix cores, power-of-two Br       */
+} fs_variant;
+
+typedef struct {
+  int64_t d, k;
+  int32_t Bc, Br, kappa, s;
+  int32_t M;           /* blocks per side                                   */
+  int32_t a, b;        /* wiring f(x) = (a x + b) mod M                     */
+  int32_t a_inv;       /* inverse of a modulo M (0 when M = 1)              */
+  uint32_t key0, key1; /* seed-derived hash keys                            */
+  float scale;         /* (float)(1/sqrt(kappa*s)); 1/sqrt(k) for GAUSS     */
+  int32_t kind;        /* fs_kind                                           */
+  int32_t variant;     /* fs_variant requested                              */
+  int32_t last_variant;/* variant the most recent apply actually launched   */
+  int32_t last_hip_error; /* hipError_t of the last failed HIP call, else 0 */
+  uint64_t workspace_bytes; /* size of the workspace currently attached     */
+} fs_info;
+
+/* Create a BLOCKPERM handle.  Pure host work (no HIP call, usable without a GPU).
+ * Errors (FS_ERR_INVALID_ARG): out == NULL; d, k, Bc, Br, kappa, s < 1;
+ * Bc does not divide d, Br does not divide k, d/Bc != k/Br; kappa > M
+ * (Appendix E: the kappa neighbours are distinct only for kappa <= M);
+ * s > Br (rows must be distinct, Alg. 1) or s > 32; Br > 65536; M > 2^24. */
+fs_status fs_sketch_create(fs_sketch_t* out, int64_t d, int64_t k, int32_t Bc, int32_t Br,
+                           int32_t kappa, int32_t s, uint64_t seed);
+
+/* As above for any kind.  SJLT_SCATTER requires Bc == d, Br == k, kappa == 1.
+ * GAUSS_DENSE allocates and fills the k x d matrix on the current device
+ * (FS_ERR_HIP / FS_ERR_ALLOC without a device); it ignores Bc, Br, kappa, s. */
+fs_status fs_sketch_create_kind(fs_sketch_t* out, fs_kind kind, int64_t d, int64_t k, int32_t Bc,
+                                int32_t Br, int32_t kappa, int32_t s, uint64_t seed);
+
+/* out (k x n, ld = n) = S * A (d x n, ld = lda), both of type `dtype`.
+ * n == 0 is FS_OK and launches nothing.  Errors: NULL handle/A/out, n < 0,
+ * lda < n, unknown dtype.  May grow the handle's workspace with hipMalloc on
+ * first use unless one was attached with fs_sketch_set_workspace. */
+fs_status fs_sketch_apply(fs_sketch_t h, const void* A, int64_t lda, int64_t n, void* out,
+                          fs_dtype dtype, void* stream);
+
+/* Same with an explicit output leading dimension (column-chunk views). */
+fs_status fs_sketch_apply_ld(fs_sketch_t h, const void* A, int64_t lda, int64_t n, void* out,
+                             int64_t ldo, fs_dtype dtype, void* stream);
+
+/* Materialise the nonzeros of S on the device (BLOCKPERM / SJLT_SCATTER):
+ * rows[c*kappa*s + (l-1)*s + i] = global output row, signs[...] = +1/-1, for
+ * column c of S, wiring slot l (the l with f^l(g) = c / Bc) and update i.
+ * Both buffers hold d*kappa*s entries. */
+fs_status fs_sketch_export(fs_sketch_t h, int32_t* rows, int8_t* signs, void* stream);
+
+/* GAUSS_DENSE only: copy the k x d fp32 matrix (row-major, ld = d) to S_dense. */
+fs_status fs_sketch_export_dense(fs_sketch_t h, float* S_dense, void* stream);
+
+fs_status fs_sketch_info(fs_sketch_t h, fs_info* out);
+
+/* Bytes of device workspace an apply of n columns of `dtype` needs with the
+ * handle's current variant setting (0 if none). */
+fs_status fs_sketch_workspace_bytes(fs_sketch_t h, int64_t n, fs_dtype dtype, size_t* bytes);
+
+/* Attach a caller-owned device workspace (256-byte aligned); the handle then
+ * never allocates in apply and fails with FS_ERR_ALLOC if it is too small.
+ * (NULL, 0) detaches it and returns to the internal, lazily grown one. */
+fs_status fs_sketch_set_workspace(fs_sketch_t h, void* dev_ptr, size_t bytes);
+
+/* Force a kernel variant for BLOCKPERM applies (tests, benchmarks).
+ * FS_ERR_UNSUPPORTED at apply time if the forced variant cannot run the shape. */
+fs_status fs_sketch_set_variant(fs_sketch_t h, fs_variant v);
+
+/* Frees the handle and any device memory it owns (not caller workspaces). */
+fs_status fs_sketch_destroy(fs_sketch_t h);
+
+const char* fs_status_string(fs_status st);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLASHSKETCH_H */

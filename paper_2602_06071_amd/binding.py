@@ -1,0 +1,159 @@
+"""ctypes binding of include/flashsketch.h: same names, argument marshalling only.
+
+PyTorch supplies device memory (``tensor.data_ptr()``) and the HIP stream
+(``torch.cuda.current_stream().cuda_stream``); nothing is computed here.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch  # must precede the CDLL: the library binds to the HIP runtime torch has loaded
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+lib_path = os.path.join(_HERE, "libflashsketch.so")
+
+FS_F32, FS_BF16 = 0, 1
+KIND_BLOCKPERM, KIND_SJLT_SCATTER, KIND_GAUSS_DENSE = 0, 1, 2
+VARIANT_AUTO, VARIANT_GENERIC, VARIANT_MFMA = 0, 1, 2
+
+SYMBOLS = [
+    "fs_sketch_create", "fs_sketch_create_kind", "fs_sketch_apply", "fs_sketch_apply_ld",
+    "fs_sketch_export", "fs_sketch_export_dense", "fs_sketch_info", "fs_sketch_workspace_bytes",
+    "fs_sketch_set_workspace", "fs_sketch_set_variant", "fs_sketch_destroy", "fs_status_string",
+]
+
+
+class FlashSketchError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(f"{what}: {lib.fs_status_string(status).decode()} (fs_status {status})")
+
+
+class fs_info(C.Structure):
+    _fields_ = [
+        ("d", C.c_int64), ("k", C.c_int64),
+        ("Bc", C.c_int32), ("Br", C.c_int32), ("kappa", C.c_int32), ("s", C.c_int32),
+        ("M", C.c_int32), ("a", C.c_int32), ("b", C.c_int32), ("a_inv", C.c_int32),
+        ("key0", C.c_uint32), ("key1", C.c_uint32),
+        ("scale", C.c_float),
+        ("kind", C.c_int32), ("variant", C.c_int32), ("last_variant", C.c_int32),
+        ("last_hip_error", C.c_int32),
+        ("workspace_bytes", C.c_uint64),
+    ]
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(lib_path):
+        raise ImportError(
+            f"{lib_path} is missing: build it with `python -m paper_2602_06071_amd.build` "
+            "(there is no CPU fallback)")
+    L = C.CDLL(lib_path)
+    vp, i64, i32, u64 = C.c_void_p, C.c_int64, C.c_int32, C.c_uint64
+    L.fs_sketch_create.argtypes = [C.POINTER(vp), i64, i64, i32, i32, i32, i32, u64]
+    L.fs_sketch_create_kind.argtypes = [C.POINTER(vp), C.c_int, i64, i64, i32, i32, i32, i32, u64]
+    L.fs_sketch_apply.argtypes = [vp, vp, i64, i64, vp, C.c_int, vp]
+    L.fs_sketch_apply_ld.argtypes = [vp, vp, i64, i64, vp, i64, C.c_int, vp]
+    L.fs_sketch_export.argtypes = [vp, vp, vp, vp]
+    L.fs_sketch_export_dense.argtypes = [vp, vp, vp]
+    L.fs_sketch_info.argtypes = [vp, C.POINTER(fs_info)]
+    L.fs_sketch_workspace_bytes.argtypes = [vp, i64, C.c_int, C.POINTER(C.c_size_t)]
+    L.fs_sketch_set_workspace.argtypes = [vp, vp, C.c_size_t]
+    L.fs_sketch_set_variant.argtypes = [vp, C.c_int]
+    L.fs_sketch_destroy.argtypes = [vp]
+    for name in SYMBOLS:
+        getattr(L, name).restype = C.c_int
+    L.fs_status_string.argtypes = [C.c_int]
+    L.fs_status_string.restype = C.c_char_p
+    return L
+
+
+lib = _load()
+
+
+def _check(st: int, what: str) -> None:
+    if st != 0:
+        raise FlashSketchError(st, what)
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return FS_F32
+    if t.dtype == torch.bfloat16:
+        return FS_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _stream_ptr(stream) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return int(stream.cuda_stream)
+
+
+class Sketch:
+    """Owns one fs_sketch_t.  Methods map one-to-one onto the C entry points."""
+
+    def __init__(self, d, k, Bc, Br, kappa, s, seed=0, kind=KIND_BLOCKPERM):
+        self._h = C.c_void_p()
+        _check(lib.fs_sketch_create_kind(C.byref(self._h), kind, d, k, Bc, Br, kappa, s, seed),
+               "fs_sketch_create_kind")
+        self.d, self.k = d, k
+        self._ws_keepalive = None
+
+    def close(self) -> None:
+        if self._h:
+            lib.fs_sketch_destroy(self._h)
+            self._h = C.c_void_p()
+
+    __del__ = close
+
+    def info(self) -> fs_info:
+        out = fs_info()
+        _check(lib.fs_sketch_info(self._h, C.byref(out)), "fs_sketch_info")
+        return out
+
+    def set_variant(self, v: int) -> None:
+        _check(lib.fs_sketch_set_variant(self._h, v), "fs_sketch_set_variant")
+
+    def workspace_bytes(self, n: int, dtype: torch.dtype) -> int:
+        out = C.c_size_t()
+        code = FS_F32 if dtype == torch.float32 else FS_BF16
+        _check(lib.fs_sketch_workspace_bytes(self._h, n, code, C.byref(out)), "fs_sketch_workspace_bytes")
+        return out.value
+
+    def set_workspace(self, buf: torch.Tensor | None) -> None:
+        if buf is None:
+            _check(lib.fs_sketch_set_workspace(self._h, None, 0), "fs_sketch_set_workspace")
+        else:
+            _check(lib.fs_sketch_set_workspace(self._h, buf.data_ptr(), buf.numel() * buf.element_size()),
+                   "fs_sketch_set_workspace")
+        self._ws_keepalive = buf
+
+    def apply(self, A: torch.Tensor, out: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+        """out = S @ A for a 2-D row-major view A (unit column stride)."""
+        if A.dim() != 2 or A.shape[0] != self.d or A.stride(1) != 1 and A.shape[1] > 1:
+            raise ValueError("A must be d x n with contiguous rows")
+        n = A.shape[1]
+        if out is None:
+            out = torch.empty((self.k, n), dtype=A.dtype, device=A.device)
+        if out.shape != (self.k, n) or out.dtype != A.dtype or (out.stride(1) != 1 and n > 1):
+            raise ValueError("out must be k x n, same dtype, contiguous rows")
+        _check(lib.fs_sketch_apply_ld(self._h, A.data_ptr(), A.stride(0), n, out.data_ptr(),
+                                      out.stride(0), _dtype_code(A), _stream_ptr(stream)),
+               "fs_sketch_apply_ld")
+        return out
+
+    def export(self, device="cuda", stream=None):
+        i = self.info()
+        nnz = i.d * i.kappa * i.s
+        rows = torch.empty(nnz, dtype=torch.int32, device=device)
+        signs = torch.empty(nnz, dtype=torch.int8, device=device)
+        _check(lib.fs_sketch_export(self._h, rows.data_ptr(), signs.data_ptr(), _stream_ptr(stream)),
+               "fs_sketch_export")
+        return rows.view(i.d, i.kappa * i.s), signs.view(i.d, i.kappa * i.s)
+
+    def export_dense(self, device="cuda", stream=None) -> torch.Tensor:
+        S = torch.empty((self.k, self.d), dtype=torch.float32, device=device)
+        _check(lib.fs_sketch_export_dense(self._h, S.data_ptr(), _stream_ptr(stream)),
+               "fs_sketch_export_dense")
+        return S

@@ -1,0 +1,65 @@
+// Host-side handle and the launchers each kernel file provides.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/flashsketch.h"
+
+// Plain-old-data view of a sketch that kernels take by value.
+struct SketchParams {
+  int64_t d, k;
+  uint32_t Bc, Br, kappa, s, M;
+  uint32_t a, b, a_inv;
+  uint32_t key1;
+  uint32_t br_pow2;  // 1 when Br is a power of two
+  float scale;
+};
+
+struct fs_sketch_s {
+  SketchParams p;
+  uint32_t key0;
+  int kind;
+  int variant;
+  int last_variant;
+  int last_hip_error;
+  int device;  // device that owns ws / dense (-1: none yet)
+  // internal or caller-owned workspace
+  void* ws;
+  size_t ws_bytes;
+  bool ws_owned;
+  // GAUSS_DENSE: k x d matrix, fp32 and bf16 copies
+  float* dense_f32;
+  void* dense_bf16;
+};
+
+namespace fs {
+
+// Each launcher validates nothing: api.hip has already checked every argument
+// and that the shape fits the kernel.  They return the launch's hipError_t.
+
+hipError_t launch_export(const SketchParams& p, int32_t* rows, int8_t* signs, hipStream_t st);
+
+// One lane per column, LDS-private output tile.
+hipError_t launch_generic(const SketchParams& p, const void* A, int64_t lda, int64_t n, void* out,
+                          int64_t ldo, fs_dtype dt, hipStream_t st);
+
+// Matrix-core path.  ws holds the per-slot partial tiles.
+bool mfma_supported(const SketchParams& p, const void* A, int64_t lda, int64_t n, const void* out,
+                    int64_t ldo, fs_dtype dt);
+size_t mfma_workspace_bytes(const SketchParams& p, int64_t n, fs_dtype dt);
+hipError_t launch_mfma(const SketchParams& p, const void* A, int64_t lda, int64_t n, void* out,
+                       int64_t ldo, fs_dtype dt, void* ws, hipStream_t st);
+
+// Plain SJLT, global float atomics.  ws: k*n floats for bf16 output, unused for fp32.
+size_t scatter_workspace_bytes(const SketchParams& p, int64_t n, fs_dtype dt);
+hipError_t launch_scatter(const SketchParams& p, const void* A, int64_t lda, int64_t n, void* out,
+                          int64_t ldo, fs_dtype dt, void* ws, hipStream_t st);
+
+// Dense Gaussian sketch.
+hipError_t gauss_fill(float* S_f32, void* S_bf16, int64_t k, int64_t d, uint32_t key1,
+                      hipStream_t st);
+hipError_t launch_gauss(const float* S_f32, const void* S_bf16, int64_t k, int64_t d, const void* A,
+                        int64_t lda, int64_t n, void* out, int64_t ldo, fs_dtype dt,
+                        hipStream_t st);
+
+}  // namespace fs

@@ -1,0 +1,90 @@
+// General BlockPerm-SJLT apply: any Br, any s, any alignment.
+//
+// Work-group (g, j[, pass]) owns the output tile Y[g*Br : (g+1)*Br, j*TN : (j+1)*TN]
+// (Alg. 1: one thread-block per output tile, no global atomics).  Unlike the
+// paper's kernel there are no shared-memory atomics either: each lane owns one
+// column, rows are walked wave-uniformly, so two lanes never touch the same
+// accumulator.  The tile lives in LDS as [row][lane] (bank = lane, conflict
+// free).  A is re-read once per wiring slot (kappa times in total).
+//
+// When Br*TN floats exceed the LDS budget the rows are split over grid.z
+// passes; a pass skips the updates that fall outside its row range.
+#include "convert.h"
+#include "handle.h"
+#include "spec.h"
+
+namespace fs {
+
+constexpr int kGenericLdsBytes = 64 * 1024;
+constexpr int kRowUnroll = 8;
+
+template <typename T, bool POW2>
+__global__ __launch_bounds__(256) void generic_kernel(SketchParams p, const T* __restrict__ A,
+                                                      int64_t lda, int n, T* __restrict__ out,
+                                                      int64_t ldo, int rows_per_pass) {
+  extern __shared__ float sY[];  // [R][TN]
+  const int tn = blockDim.x, tid = threadIdx.x;
+  const uint32_t g = blockIdx.x;
+  const uint32_t r0 = blockIdx.z * (uint32_t)rows_per_pass;
+  const uint32_t R = min((uint32_t)rows_per_pass, p.Br - r0);
+  const int col = blockIdx.y * tn + tid;
+  const bool active = col < n;
+
+  for (uint32_t r = 0; r < R; ++r) sY[r * tn + tid] = 0.f;
+
+  uint32_t h = g;
+  for (uint32_t l = 0; l < p.kappa; ++l) {
+    h = wire_next(h, p.a, p.b, p.M);
+    const uint32_t bk = block_key(p.key1, g, h, p.M);
+    const T* src = A + (int64_t)h * p.Bc * lda + col;
+    for (uint32_t u0 = 0; u0 < p.Bc; u0 += kRowUnroll) {
+      float v[kRowUnroll];
+#pragma unroll
+      for (int q = 0; q < kRowUnroll; ++q)
+        v[q] = (active && u0 + q < p.Bc) ? Elt<T>::load(src + (int64_t)(u0 + q) * lda) : 0.f;
+#pragma unroll
+      for (int q = 0; q < kRowUnroll; ++q) {
+        if (u0 + q >= p.Bc) break;
+        const RowHash rh = POW2 ? row_hash_pow2(bk, u0 + q, p.Br) : row_hash_any(bk, u0 + q, p.Br);
+        uint32_t r = rh.shift;
+        for (uint32_t i = 0; i < p.s; ++i) {
+          const uint32_t rel = r - r0;
+          if (rel < R) {
+            const float x = ((rh.signs >> i) & 1u) ? -v[q] : v[q];
+            sY[rel * tn + tid] += x;
+          }
+          r += rh.stride;
+          if (r >= p.Br) r -= p.Br;
+        }
+      }
+    }
+  }
+
+  if (active) {
+    T* dst = out + ((int64_t)g * p.Br + r0) * ldo + col;
+    for (uint32_t r = 0; r < R; ++r) Elt<T>::store(dst + (int64_t)r * ldo, sY[r * tn + tid] * p.scale);
+  }
+}
+
+hipError_t launch_generic(const SketchParams& p, const void* A, int64_t lda, int64_t n, void* out,
+                          int64_t ldo, fs_dtype dt, hipStream_t st) {
+  int tn = 256;
+  if (n <= 64) tn = 64; else if (n <= 128) tn = 128;
+  while (tn > 64 && (int64_t)p.Br * tn * 4 > kGenericLdsBytes) tn >>= 1;
+  int rows_per_pass = (int)p.Br;
+  const int max_rows = kGenericLdsBytes / (tn * 4);
+  if (rows_per_pass > max_rows) rows_per_pass = max_rows;
+  const unsigned passes = (p.Br + rows_per_pass - 1) / rows_per_pass;
+  const unsigned jt = (unsigned)((n + tn - 1) / tn);
+  if (jt > 65535u || passes > 65535u) return hipErrorInvalidValue;
+  dim3 grid(p.M, jt, passes), block(tn);
+  const size_t lds = (size_t)rows_per_pass * tn * 4;
+#define FS_GO(T, P2) \
+  hipLaunchKernelGGL((generic_kernel<T, P2>), grid, block, lds, st, p, (const T*)A, lda, (int)n, (T*)out, ldo, rows_per_pass)
+  if (dt == FS_F32) { if (p.br_pow2) FS_GO(float, true); else FS_GO(float, false); }
+  else              { if (p.br_pow2) FS_GO(uint16_t, true); else FS_GO(uint16_t, false); }
+#undef FS_GO
+  return hipGetLastError();
+}
+
+}  // namespace fs

@@ -1,0 +1,272 @@
+"""GPU parity: every result of the HIP path, called through the C ABI, against
+the float64 oracle on the same seeded inputs.
+
+Bars: indices and signs bit-exact; relative Frobenius error <= 1e-5 for fp32
+inputs and <= 4e-3 for bf16 inputs/outputs with fp32 accumulation.
+"""
+import functools
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import blockperm as O
+from paper_2602_06071_amd import binding as B
+from paper_2602_06071_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+TOL = {torch.float32: 1e-5, torch.bfloat16: 4e-3}
+VARIANTS = [B.VARIANT_GENERIC, B.VARIANT_MFMA]
+VNAME = {B.VARIANT_GENERIC: "generic", B.VARIANT_MFMA: "mfma", B.VARIANT_AUTO: "auto"}
+
+
+@functools.lru_cache(maxsize=8)
+def oracle_csc(params, seed):
+    return O.build_csc(O.Params(*params), seed)
+
+
+def host64(t: torch.Tensor) -> np.ndarray:
+    return t.detach().to("cpu").to(torch.float64).numpy()
+
+
+def check(out, ref, dtype, what=""):
+    err = O.rel_fro_err(host64(out), ref)
+    assert err <= TOL[dtype], f"{what}: rel. Frobenius error {err:.3e} > {TOL[dtype]:.0e}"
+    return err
+
+
+def make_sketch(params, seed, variant):
+    sk = B.Sketch(*params, seed=seed)
+    sk.set_variant(variant)
+    return sk
+
+
+def apply_or_skip(sk, A, out=None):
+    try:
+        return sk.apply(A, out)
+    except B.FlashSketchError as e:
+        if e.status == 2:
+            pytest.skip("variant does not support this shape")
+        raise
+
+
+# ------------------------------------------------------------ export ------
+@pytest.mark.parametrize("params", [
+    (4096, 256, 512, 32, 2, 4), (2048, 1024, 128, 64, 4, 2), (1152, 72, 96, 6, 5, 3),
+    (1440, 180, 80, 10, 18, 10), (512, 512, 1, 1, 3, 1), (1024, 64, 1024, 64, 1, 8),
+    (16384, 1024, 1024, 64, 8, 8), (262144, 4096, 2048, 32, 4, 4), (65536, 4096, 2048, 128, 4, 8),
+])
+@pytest.mark.parametrize("seed", [0, 0xABCDEF0123456789])
+def test_export_bit_exact(params, seed):
+    print("export", params, seed, flush=True)
+    sk = B.Sketch(*params, seed=seed)
+    rows, signs = sk.export()
+    torch.cuda.synchronize()
+    want_r, want_s = O.build_tables(O.Params(*params), seed)
+    assert np.array_equal(rows.cpu().numpy().astype(np.int64), want_r)
+    assert np.array_equal(signs.cpu().numpy(), want_s)
+
+
+def test_export_bit_exact_gradient_config():
+    cfg = W.CONFIGS["grad"]
+    print("export grad", flush=True)
+    sk = B.Sketch(*cfg.params, seed=cfg.sketch_seed)
+    rows, signs = sk.export()
+    torch.cuda.synchronize()
+    want_r, want_s = O.build_tables(O.Params(*cfg.params), cfg.sketch_seed)
+    assert np.array_equal(rows.cpu().numpy(), want_r.astype(np.int32))
+    assert np.array_equal(signs.cpu().numpy(), want_s)
+
+
+# ------------------------------------------------- element-wise parity ----
+SMALL = [
+    # params (d,k,Bc,Br,kappa,s), n, lda pad, ldo pad
+    ((4096, 256, 512, 32, 2, 4), 512, 0, 0),        # tiny config
+    ((4096, 256, 512, 32, 2, 4), 301, 3, 5),        # ragged tail, odd strides
+    ((2048, 1024, 128, 64, 4, 2), 130, 6, 0),       # Fig. 2 parameters
+    ((8192, 512, 1024, 64, 8, 8), 264, 0, 8),       # mid-config blocks, kappa = M
+    ((16384, 256, 2048, 32, 4, 4), 72, 8, 0),       # tall-config blocks
+    ((16384, 1024, 2048, 128, 4, 8), 200, 0, 0),    # wide-config blocks
+    ((32768, 64, 4096, 8, 8, 2), 256, 768, 0),      # gradient-config blocks, chunk view stride
+    ((32768, 64, 4096, 8, 8, 2), 100, 4, 4),
+    ((1152, 72, 96, 6, 5, 3), 65, 0, 0),            # Br not a power of two
+    ((1440, 180, 80, 10, 18, 10), 33, 1, 1),        # kappa = M, s = Br
+    ((512, 512, 1, 1, 3, 1), 17, 0, 0),             # Br = Bc = 1
+    ((1024, 64, 1024, 64, 1, 8), 1, 0, 0),          # M = 1, single column
+    ((3072, 1536, 1024, 512, 2, 8), 70, 0, 0),      # Br > LDS rows per pass
+]
+
+
+@pytest.mark.parametrize("variant", VARIANTS, ids=lambda v: VNAME[v])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("case", SMALL, ids=lambda c: f"{c[0]}-n{c[1]}")
+def test_apply_matches_oracle(case, dtype, variant):
+    params, n, pa, po = case
+    print("apply", params, n, dtype, VNAME[variant], flush=True)
+    seed = 5
+    d, k = params[0], params[1]
+    g = torch.Generator(device=DEV).manual_seed(n + d)
+    Abuf = torch.randn((d, n + pa), generator=g, device=DEV).to(dtype)
+    A = Abuf[:, :n]
+    obuf = torch.full((k, n + po), float("nan"), device=DEV, dtype=dtype)
+    sk = make_sketch(params, seed, variant)
+    apply_or_skip(sk, A, obuf[:, :n])
+    torch.cuda.synchronize()
+    ref = O.apply(oracle_csc(params, seed), host64(A))
+    check(obuf[:, :n], ref, dtype, "apply")
+    if po:
+        assert torch.isnan(obuf[:, n:].float()).all(), "wrote outside the n output columns"
+    # element-wise, scaled by the typical magnitude of an output entry
+    tol = (2e-5 if dtype == torch.float32 else 8e-3)
+    diff = np.abs(host64(obuf[:, :n]) - ref)
+    assert (diff <= tol * (np.abs(ref) + np.sqrt((ref ** 2).mean()))).all()
+
+
+# ---------------------------------------------------------- one-hot -------
+@pytest.mark.parametrize("variant", VARIANTS, ids=lambda v: VNAME[v])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("params", [(4096, 256, 512, 32, 4, 4), (32768, 64, 4096, 8, 8, 2),
+                                    (8192, 512, 1024, 64, 4, 4), (4096, 256, 512, 32, 2, 2)])
+def test_one_hot_probes_reproduce_columns_exactly(params, dtype, variant):
+    """A = selected unit vectors: each output column is one column of S; with
+    kappa*s a power of four the scale is a power of two, so the match is exact."""
+    print("one-hot", params, dtype, VNAME[variant], flush=True)
+    d = params[0]
+    assert round(np.sqrt(params[4] * params[5])) ** 2 == params[4] * params[5]
+    rng = np.random.default_rng(1)
+    cols = np.unique(np.r_[0, d - 1, params[2] - 1, params[2], rng.integers(0, d, 120)])
+    A = torch.zeros((d, len(cols)), device=DEV, dtype=dtype)
+    A[torch.from_numpy(cols).to(DEV), torch.arange(len(cols), device=DEV)] = 1.0
+    sk = make_sketch(params, 0, variant)
+    out = apply_or_skip(sk, A)
+    torch.cuda.synchronize()
+    want = oracle_csc(params, 0)[:, cols].toarray()
+    assert np.array_equal(host64(out), want)
+
+
+# ------------------------------------ chunking, determinism, linearity ----
+@pytest.mark.parametrize("variant", VARIANTS, ids=lambda v: VNAME[v])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+def test_chunked_equals_monolithic_bitwise(dtype, variant):
+    params, n, chunk = (32768, 64, 4096, 8, 8, 2), 1024, 256
+    print("chunked", dtype, VNAME[variant], flush=True)
+    A = W.laplace_lognormal(params[0], n, 3, DEV, dtype=dtype)
+    sk = make_sketch(params, 0, variant)
+    whole = apply_or_skip(sk, A)
+    again = sk.apply(A)
+    parts = torch.empty_like(whole)
+    for c in range(0, n, chunk):
+        sk.apply(A[:, c:c + chunk], parts[:, c:c + chunk])
+    torch.cuda.synchronize()
+    assert torch.equal(whole.view(torch.int16 if dtype == torch.bfloat16 else torch.int32),
+                       again.view(torch.int16 if dtype == torch.bfloat16 else torch.int32))
+    assert torch.equal(whole, parts)
+
+
+@pytest.mark.parametrize("variant", VARIANTS, ids=lambda v: VNAME[v])
+def test_linearity(variant):
+    params = (8192, 512, 1024, 64, 4, 4)
+    g = torch.Generator(device=DEV).manual_seed(0)
+    X, Y = torch.randn((2, params[0], 96), generator=g, device=DEV)
+    sk = make_sketch(params, 2, variant)
+    lhs = apply_or_skip(sk, 2 * X - 3 * Y)
+    rhs = 2 * sk.apply(X) - 3 * sk.apply(Y)
+    torch.cuda.synchronize()
+    assert O.rel_fro_err(host64(lhs), host64(rhs)) < 1e-5
+
+
+def test_forced_variant_on_unsupported_shape_reports_unsupported():
+    sk = B.Sketch(1152, 72, 96, 6, 5, 3)  # Br not a power of two
+    sk.set_variant(B.VARIANT_MFMA)
+    A = torch.zeros((1152, 8), device=DEV)
+    with pytest.raises(B.FlashSketchError) as e:
+        sk.apply(A)
+    assert e.value.status == 2
+    sk.set_variant(B.VARIANT_AUTO)
+    sk.apply(A)  # falls back to the generic kernel
+    assert sk.info().last_variant == B.VARIANT_GENERIC
+
+
+def test_empty_input_launches_nothing():
+    sk = B.Sketch(4096, 256, 512, 32, 2, 4)
+    A = torch.zeros((4096, 0), device=DEV)
+    out = sk.apply(A)
+    assert out.shape == (256, 0)
+
+
+# ------------------------------------------------ baselines ---------------
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("d,k,s,n", [(4096, 256, 4, 300), (16384, 1024, 8, 520), (1000, 48, 3, 17)])
+def test_plain_sjlt_scatter_matches_oracle(d, k, s, n, dtype):
+    print("scatter", d, k, s, n, dtype, flush=True)
+    params = (d, k, d, k, 1, s)
+    g = torch.Generator(device=DEV).manual_seed(4)
+    A = torch.randn((d, n), generator=g, device=DEV).to(dtype)
+    sk = B.Sketch(*params, seed=1, kind=B.KIND_SJLT_SCATTER)
+    out = sk.apply(A)
+    torch.cuda.synchronize()
+    check(out, O.apply(oracle_csc(params, 1), host64(A)), dtype, "scatter")
+    rows, signs = sk.export()
+    want_r, want_s = O.build_tables(O.Params(*params), 1)
+    assert np.array_equal(rows.cpu().numpy().astype(np.int64), want_r)
+    assert np.array_equal(signs.cpu().numpy(), want_s)
+
+
+# ------------------------------------------------ full-size configs -------
+def _sampled_parity(cfg, A, out, ncols=12, seed=0):
+    """Oracle on a sample of columns of the full-size problem."""
+    rng = np.random.default_rng(seed)
+    cols = np.unique(np.r_[0, cfg.n - 1, rng.integers(0, cfg.n, ncols)])
+    idx = torch.from_numpy(cols).to(A.device)
+    ref = O.apply(oracle_csc(cfg.params, cfg.sketch_seed), host64(A[:, idx]))
+    return check(out[:, idx], ref, cfg.dtype, f"{cfg.name} sampled columns")
+
+
+@pytest.mark.parametrize("name", ["tiny", "tall"])
+def test_full_config_all_columns(name):
+    cfg = W.CONFIGS[name]
+    print("full", name, flush=True)
+    A = W.make_input(cfg, DEV)
+    sk = B.Sketch(*cfg.params, seed=cfg.sketch_seed)
+    out = sk.apply(A)
+    torch.cuda.synchronize()
+    ref = O.apply(oracle_csc(cfg.params, cfg.sketch_seed), host64(A))
+    check(out, ref, cfg.dtype, name)
+
+
+@pytest.mark.parametrize("kappa", W.MID_KAPPAS)
+def test_full_config_mid_sampled(kappa):
+    import dataclasses
+    cfg = dataclasses.replace(W.CONFIGS["mid"], kappa=kappa)
+    print("full mid kappa", kappa, flush=True)
+    A = W.make_input(cfg, DEV)
+    sk = B.Sketch(*cfg.params, seed=cfg.sketch_seed)
+    out = sk.apply(A)
+    torch.cuda.synchronize()
+    _sampled_parity(cfg, A, out)
+
+
+def test_full_config_wide_sampled():
+    cfg = W.CONFIGS["wide"]
+    print("full wide", flush=True)
+    A = W.make_input(cfg, DEV)
+    sk = B.Sketch(*cfg.params, seed=cfg.sketch_seed)
+    out = sk.apply(A)
+    torch.cuda.synchronize()
+    _sampled_parity(cfg, A, out)
+
+
+def test_full_config_grad_chunked_sampled():
+    """8 GiB bf16 input, applied as the benchmark does: four 256-column views of
+    one allocation on one stream."""
+    cfg = W.CONFIGS["grad"]
+    print("full grad", flush=True)
+    A = W.make_input(cfg, DEV)
+    sk = B.Sketch(*cfg.params, seed=cfg.sketch_seed)
+    out = torch.empty((cfg.k, cfg.n), device=DEV, dtype=cfg.dtype)
+    for c in range(0, cfg.n, cfg.chunk):
+        sk.apply(A[:, c:c + cfg.chunk], out[:, c:c + cfg.chunk])
+    torch.cuda.synchronize()
+    print("  applied; oracle on sampled columns", flush=True)
+    _sampled_parity(cfg, A, out, ncols=6)
