@@ -1,0 +1,196 @@
+#!/usr/bin/env python3
+"""Benchmark of the BlockPerm-SJLT sketch apply on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload grad] [--no-extra]
+
+A step is one pass of the whole hot path over one batch of synthetic input: for
+the default workload (the per-example-gradient configuration, 8 GiB bf16) that
+is four fs_sketch_apply_ld calls on 256-column views of one resident matrix,
+back to back on one stream.  Inputs are resident in HBM before the timed region.
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import dataclasses
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="grad", choices=["tiny", "mid", "tall", "wide", "grad"])
+    ap.add_argument("--variant", default="auto", choices=["auto", "generic", "mfma"])
+    ap.add_argument("--no-extra", action="store_true", help="skip the side measurements")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    return ap.parse_args()
+
+
+def chunks_of(cfg):
+    w = cfg.chunk if cfg.chunk else cfg.n
+    return [(c, min(cfg.n, c + w)) for c in range(0, cfg.n, w)]
+
+
+def run_steps(sk, A, out, cfg, steps):
+    for _ in range(steps):
+        for c0, c1 in chunks_of(cfg):
+            sk.apply(A[:, c0:c1], out[:, c0:c1])
+
+
+def time_workload(torch, B, cfg, A, variant, steps, warmup, kind=None, sketch_params=None):
+    """Wall-clock over `steps` steps plus HIP-event durations of the dominant kernel."""
+    params = sketch_params or cfg.params
+    sk = B.Sketch(*params, seed=cfg.sketch_seed, kind=B.KIND_BLOCKPERM if kind is None else kind)
+    if kind is None:
+        sk.set_variant({"auto": B.VARIANT_AUTO, "generic": B.VARIANT_GENERIC, "mfma": B.VARIANT_MFMA}[variant])
+    out = torch.empty((cfg.k, cfg.n), device=A.device, dtype=cfg.dtype)
+    run_steps(sk, A, out, cfg, warmup)
+    torch.cuda.synchronize()
+    launches = steps * len(chunks_of(cfg))
+    sk.profile_begin(launches)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run_steps(sk, A, out, cfg, steps)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    kernel_ms = sk.profile_end()
+    used = sk.info().last_variant
+    sk.close()
+    return (t1 - t0) / steps, kernel_ms, used, out
+
+
+def cpu_baseline(torch, cfg, A, budget_cols=None):
+    """The float64 oracle, as it stands, on a bounded sample of the same workload."""
+    from oracle import blockperm as O
+    t0 = time.perf_counter()
+    S = O.build_csc(O.Params(*cfg.params), cfg.sketch_seed)
+    t_build = time.perf_counter() - t0
+    # size the sample for roughly 10 s of sparse-times-dense work (~1.5e9 f64 MAC/s/core)
+    nnz = cfg.d * cfg.kappa * cfg.s
+    cols = budget_cols or int(max(1, min(cfg.n, 1.5e10 // nnz)))
+    A_host = A[:, :cols].to("cpu").to(torch.float64).numpy()
+    t0 = time.perf_counter()
+    Y = O.apply(S, A_host)
+    t_apply = time.perf_counter() - t0
+    gbps = cfg.d * cols * cfg.elt / t_apply / 1e9
+    return {
+        "value": gbps, "unit": "GB/s", "cores": 1, "kind": "oracle",
+        "sample": f"first {cols} of {cfg.n} columns of the same A (all {cfg.d} rows), float64 CSC product "
+                  f"{t_apply:.2f} s; building S as CSC took {t_build:.2f} s more and is not counted",
+        "cols_per_s": cols / t_apply,
+    }, Y, cols
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the sketch apply shards over columns with no exchange step, "
+              "so this build has no multi-GPU path; run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from oracle import blockperm as O  # cpu_baseline leg and the sanity check only
+    from paper_2602_06071_amd import binding as B
+    from paper_2602_06071_amd import workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = "cuda:0"
+    cfg = W.CONFIGS[args.workload]
+    A = W.make_input(cfg, dev)
+    torch.cuda.synchronize()
+
+    sec_per_step, kernel_ms, used, out = time_workload(torch, B, cfg, A, args.variant, args.steps, args.warmup)
+    n_launch = len(chunks_of(cfg))
+    cols_per_launch = cfg.n // n_launch
+    # algorithmic bytes of one launch: read its columns of A once, write its columns of SA once
+    alg_bytes = cols_per_launch * (cfg.d * cfg.elt + cfg.k * cfg.elt)
+    avg_kernel_s = sum(kernel_ms) / len(kernel_ms) / 1e3
+    achieved = alg_bytes / avg_kernel_s / 1e9
+    value = cfg.a_bytes / sec_per_step / 1e9
+
+    rec = {
+        "metric": "sketch-apply GB/s of A streamed",
+        "value": value, "unit": "GB/s",
+        "pct_hbm_peak": 100.0 * value / HBM_PEAK_GBPS,
+        "cols_per_s": cfg.n / sec_per_step,
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": sec_per_step * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.elt == 2 else "f32", "data": "synthetic",
+        "config": {
+            "workload": f"{cfg.name}: A {cfg.d}x{cfg.n} {'bf16' if cfg.elt == 2 else 'fp32'}, k={cfg.k}, "
+                        f"Bc={cfg.Bc}, Br={cfg.Br}, s={cfg.s}, kappa={cfg.kappa}, "
+                        f"{n_launch} launch(es) of {cols_per_launch} columns per step",
+            "variant": {1: "generic", 2: "mfma"}.get(used, str(used)),
+            "accumulate": "fp32",
+        },
+        "roofline": {
+            "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+            "kernel_ms_avg": avg_kernel_s * 1e3, "launches_timed": len(kernel_ms),
+            "algorithmic_bytes_per_launch": alg_bytes,
+        },
+    }
+
+    if not args.no_cpu:
+        base, Y, cols = cpu_baseline(torch, cfg, A)
+        err = O.rel_fro_err(out[:, :cols].to("cpu").to(torch.float64).numpy(), Y)
+        rec["cpu_baseline"] = base
+        rec["rel_fro_err_vs_oracle_on_sample"] = err
+
+    if not args.no_extra:
+        rec["extra"] = extra_measurements(torch, B, W, dev, cfg.name)
+    print(json.dumps(rec))
+
+
+def extra_measurements(torch, B, W, dev, skip):
+    """Short side measurements on the other configurations (kernel time by HIP
+    events, 5 launches each): the kappa sweep with the plain-SJLT scatter and
+    dense-Gaussian reference points, the tall matrix, and the bf16 width sweep."""
+    res = {}
+
+    def one(cfg, A, **kw):
+        try:
+            _, ms, used, _ = time_workload(torch, B, cfg, A, "auto", 5, 2, **kw)
+        except B.FlashSketchError as e:
+            return {"error": str(e)}
+        t = sum(ms) / len(ms) / 1e3
+        return {"kernel_ms": t * 1e3, "GBps_A": cfg.a_bytes / len(chunks_of(cfg)) / t / 1e9,
+                "variant": used}
+
+    for name in ("tiny", "tall"):
+        if name != skip:
+            cfg = W.CONFIGS[name]
+            res[name] = one(cfg, W.make_input(cfg, dev))
+    if skip != "mid":
+        base = W.CONFIGS["mid"]
+        A = W.make_input(base, dev)
+        for kappa in W.MID_KAPPAS:
+            res[f"mid_kappa{kappa}"] = one(dataclasses.replace(base, kappa=kappa), A)
+        for s in (8, 32):
+            res[f"mid_plain_sjlt_scatter_s{s}"] = one(
+                base, A, kind=B.KIND_SJLT_SCATTER, sketch_params=(base.d, base.k, base.d, base.k, 1, s))
+        res["mid_dense_gaussian"] = one(base, A, kind=B.KIND_GAUSS_DENSE)
+        del A
+    if skip != "wide":
+        base = W.CONFIGS["wide"]
+        A = W.make_input(base, dev)
+        for n in W.WIDE_NS:
+            res[f"wide_n{n}"] = one(dataclasses.replace(base, n=n), A[:, :n].contiguous())
+        del A
+    return res
+
+
+if __name__ == "__main__":
+    main()

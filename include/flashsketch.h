@@ -143,6 +143,16 @@ fs_status fs_sketch_set_workspace(fs_sketch_t h, void* dev_ptr, size_t bytes);
  * FS_ERR_UNSUPPORTED at apply time if the forced variant cannot run the shape. */
 fs_status fs_sketch_set_variant(fs_sketch_t h, fs_variant v);
 
+/* Kernel timing for benchmarks.  After profile_begin, each apply brackets its
+ * dominant kernel (the one that streams A) with a HIP event pair recorded on the
+ * apply's stream, up to max_launches pairs.  profile_end synchronises those
+ * events, writes the elapsed milliseconds of each bracketed launch to the HOST
+ * array ms (capacity max_launches), the number of launches to *count, and
+ * releases the events.  Errors: NULL arguments, max_launches < 1, begin while
+ * already profiling, end without begin. */
+fs_status fs_sketch_profile_begin(fs_sketch_t h, int32_t max_launches);
+fs_status fs_sketch_profile_end(fs_sketch_t h, float* ms, int32_t* count);
+
 /* Frees the handle and any device memory it owns (not caller workspaces). */
 fs_status fs_sketch_destroy(fs_sketch_t h);
 

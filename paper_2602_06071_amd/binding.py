@@ -21,6 +21,7 @@ SYMBOLS = [
     "fs_sketch_create", "fs_sketch_create_kind", "fs_sketch_apply", "fs_sketch_apply_ld",
     "fs_sketch_export", "fs_sketch_export_dense", "fs_sketch_info", "fs_sketch_workspace_bytes",
     "fs_sketch_set_workspace", "fs_sketch_set_variant", "fs_sketch_destroy", "fs_status_string",
+    "fs_sketch_profile_begin", "fs_sketch_profile_end",
 ]
 
 
@@ -61,6 +62,8 @@ def _load() -> C.CDLL:
     L.fs_sketch_set_workspace.argtypes = [vp, vp, C.c_size_t]
     L.fs_sketch_set_variant.argtypes = [vp, C.c_int]
     L.fs_sketch_destroy.argtypes = [vp]
+    L.fs_sketch_profile_begin.argtypes = [vp, i32]
+    L.fs_sketch_profile_end.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(i32)]
     for name in SYMBOLS:
         getattr(L, name).restype = C.c_int
     L.fs_status_string.argtypes = [C.c_int]
@@ -128,6 +131,17 @@ class Sketch:
             _check(lib.fs_sketch_set_workspace(self._h, buf.data_ptr(), buf.numel() * buf.element_size()),
                    "fs_sketch_set_workspace")
         self._ws_keepalive = buf
+
+    def profile_begin(self, max_launches: int) -> None:
+        self._prof_cap = max_launches
+        _check(lib.fs_sketch_profile_begin(self._h, max_launches), "fs_sketch_profile_begin")
+
+    def profile_end(self) -> list[float]:
+        """Milliseconds of each bracketed dominant-kernel launch since profile_begin."""
+        ms = (C.c_float * self._prof_cap)()
+        cnt = C.c_int32()
+        _check(lib.fs_sketch_profile_end(self._h, ms, C.byref(cnt)), "fs_sketch_profile_end")
+        return [float(ms[i]) for i in range(cnt.value)]
 
     def apply(self, A: torch.Tensor, out: torch.Tensor | None = None, stream=None) -> torch.Tensor:
         """out = S @ A for a 2-D row-major view A (unit column stride)."""

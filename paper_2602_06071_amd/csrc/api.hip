@@ -142,6 +142,7 @@ fs_status fs_sketch_create_kind(fs_sketch_t* out, fs_kind kind, int64_t d, int64
   h->device = -1;
   h->ws = nullptr; h->ws_bytes = 0; h->ws_owned = true;
   h->dense_f32 = nullptr; h->dense_bf16 = nullptr;
+  h->profiling = false; h->prof_used = 0;
 
   if (kind == FS_KIND_GAUSS_DENSE) {
     if ((double)k * (double)d > 4.0e9) { delete h; return FS_ERR_UNSUPPORTED; }
@@ -167,9 +168,47 @@ fs_status fs_sketch_create(fs_sketch_t* out, int64_t d, int64_t k, int32_t Bc, i
   return fs_sketch_create_kind(out, FS_KIND_BLOCKPERM, d, k, Bc, Br, kappa, s, seed);
 }
 
+static void release_events(fs_sketch_t h) {
+  for (hipEvent_t e : h->prof_start) (void)hipEventDestroy(e);
+  for (hipEvent_t e : h->prof_stop) (void)hipEventDestroy(e);
+  h->prof_start.clear(); h->prof_stop.clear();
+  h->profiling = false; h->prof_used = 0;
+}
+
+fs_status fs_sketch_profile_begin(fs_sketch_t h, int32_t max_launches) {
+  if (!h || max_launches < 1 || max_launches > (1 << 20) || h->profiling) return FS_ERR_INVALID_ARG;
+  for (int i = 0; i < max_launches; ++i) {
+    hipEvent_t a = nullptr, b = nullptr;
+    hipError_t e = hipEventCreate(&a);
+    if (e == hipSuccess) e = hipEventCreate(&b);
+    if (e != hipSuccess) {
+      if (a) (void)hipEventDestroy(a);
+      release_events(h);
+      return hip_fail(h, e);
+    }
+    h->prof_start.push_back(a); h->prof_stop.push_back(b);
+  }
+  h->profiling = true; h->prof_used = 0;
+  return FS_OK;
+}
+
+fs_status fs_sketch_profile_end(fs_sketch_t h, float* ms, int32_t* count) {
+  if (!h || !ms || !count || !h->profiling) return FS_ERR_INVALID_ARG;
+  fs_status rc = FS_OK;
+  *count = h->prof_used;
+  for (int i = 0; i < h->prof_used; ++i) {
+    hipError_t e = hipEventSynchronize(h->prof_stop[i]);
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms[i], h->prof_start[i], h->prof_stop[i]);
+    if (e != hipSuccess) { rc = hip_fail(h, e); *count = i; break; }
+  }
+  release_events(h);
+  return rc;
+}
+
 fs_status fs_sketch_destroy(fs_sketch_t h) {
   if (!h) return FS_ERR_INVALID_ARG;
   fs_status st = FS_OK;
+  release_events(h);
   if (h->ws && h->ws_owned && hipFree(h->ws) != hipSuccess) st = FS_ERR_HIP;
   if (h->dense_f32 && hipFree(h->dense_f32) != hipSuccess) st = FS_ERR_HIP;
   if (h->dense_bf16 && hipFree(h->dense_bf16) != hipSuccess) st = FS_ERR_HIP;
@@ -244,15 +283,21 @@ fs_status fs_sketch_apply_ld(fs_sketch_t h, const void* A, int64_t lda, int64_t 
   rc = ensure_workspace(h, need);
   if (rc != FS_OK) return rc;
 
+  fs::EventPair ev;
+  if (h->profiling && h->prof_used < (int)h->prof_start.size()) {
+    ev.start = h->prof_start[h->prof_used];
+    ev.stop = h->prof_stop[h->prof_used];
+    ++h->prof_used;
+  }
   hipError_t e;
   if (h->kind == FS_KIND_SJLT_SCATTER) {
-    e = fs::launch_scatter(h->p, A, lda, n, out, ldo, dt, h->ws, st);
+    e = fs::launch_scatter(h->p, A, lda, n, out, ldo, dt, h->ws, st, ev);
   } else if (h->kind == FS_KIND_GAUSS_DENSE) {
-    e = fs::launch_gauss(h->dense_f32, h->dense_bf16, h->p.k, h->p.d, A, lda, n, out, ldo, dt, st);
+    e = fs::launch_gauss(h->dense_f32, h->dense_bf16, h->p.k, h->p.d, A, lda, n, out, ldo, dt, st, ev);
   } else if (variant == FS_VARIANT_MFMA) {
-    e = fs::launch_mfma(h->p, A, lda, n, out, ldo, dt, h->ws, st);
+    e = fs::launch_mfma(h->p, A, lda, n, out, ldo, dt, h->ws, st, ev);
   } else {
-    e = fs::launch_generic(h->p, A, lda, n, out, ldo, dt, st);
+    e = fs::launch_generic(h->p, A, lda, n, out, ldo, dt, st, ev);
   }
   h->last_variant = variant;
   if (e != hipSuccess) return hip_fail(h, e);

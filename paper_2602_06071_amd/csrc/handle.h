@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <vector>
+
 #include "../../include/flashsketch.h"
 
 // Plain-old-data view of a sketch that kernels take by value.
@@ -27,12 +29,21 @@ struct fs_sketch_s {
   void* ws;
   size_t ws_bytes;
   bool ws_owned;
+  // optional event pairs around the dominant kernel of each apply
+  bool profiling;
+  int prof_used;
+  std::vector<hipEvent_t> prof_start, prof_stop;
   // GAUSS_DENSE: k x d matrix, fp32 and bf16 copies
   float* dense_f32;
   void* dense_bf16;
 };
 
 namespace fs {
+
+// Optional event pair recorded immediately before / after the dominant kernel.
+struct EventPair {
+  hipEvent_t start = nullptr, stop = nullptr;
+};
 
 // Each launcher validates nothing: api.hip has already checked every argument
 // and that the shape fits the kernel.  They return the launch's hipError_t.
@@ -41,25 +52,25 @@ hipError_t launch_export(const SketchParams& p, int32_t* rows, int8_t* signs, hi
 
 // One lane per column, LDS-private output tile.
 hipError_t launch_generic(const SketchParams& p, const void* A, int64_t lda, int64_t n, void* out,
-                          int64_t ldo, fs_dtype dt, hipStream_t st);
+                          int64_t ldo, fs_dtype dt, hipStream_t st, EventPair ev);
 
 // Matrix-core path.  ws holds the per-slot partial tiles.
 bool mfma_supported(const SketchParams& p, const void* A, int64_t lda, int64_t n, const void* out,
                     int64_t ldo, fs_dtype dt);
 size_t mfma_workspace_bytes(const SketchParams& p, int64_t n, fs_dtype dt);
 hipError_t launch_mfma(const SketchParams& p, const void* A, int64_t lda, int64_t n, void* out,
-                       int64_t ldo, fs_dtype dt, void* ws, hipStream_t st);
+                       int64_t ldo, fs_dtype dt, void* ws, hipStream_t st, EventPair ev);
 
 // Plain SJLT, global float atomics.  ws: k*n floats for bf16 output, unused for fp32.
 size_t scatter_workspace_bytes(const SketchParams& p, int64_t n, fs_dtype dt);
 hipError_t launch_scatter(const SketchParams& p, const void* A, int64_t lda, int64_t n, void* out,
-                          int64_t ldo, fs_dtype dt, void* ws, hipStream_t st);
+                          int64_t ldo, fs_dtype dt, void* ws, hipStream_t st, EventPair ev);
 
 // Dense Gaussian sketch.
 hipError_t gauss_fill(float* S_f32, void* S_bf16, int64_t k, int64_t d, uint32_t key1,
                       hipStream_t st);
 hipError_t launch_gauss(const float* S_f32, const void* S_bf16, int64_t k, int64_t d, const void* A,
                         int64_t lda, int64_t n, void* out, int64_t ldo, fs_dtype dt,
-                        hipStream_t st);
+                        hipStream_t st, EventPair ev);
 
 }  // namespace fs

@@ -2,5 +2,5 @@
 #include "handle.h"
 namespace fs {
 hipError_t gauss_fill(float*, void*, int64_t, int64_t, uint32_t, hipStream_t) { return hipErrorNotSupported; }
-hipError_t launch_gauss(const float*, const void*, int64_t, int64_t, const void*, int64_t, int64_t, void*, int64_t, fs_dtype, hipStream_t) { return hipErrorNotSupported; }
+hipError_t launch_gauss(const float*, const void*, int64_t, int64_t, const void*, int64_t, int64_t, void*, int64_t, fs_dtype, hipStream_t, EventPair) { return hipErrorNotSupported; }
 }

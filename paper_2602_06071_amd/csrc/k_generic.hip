@@ -67,7 +67,7 @@ __global__ __launch_bounds__(256) void generic_kernel(SketchParams p, const T* _
 }
 
 hipError_t launch_generic(const SketchParams& p, const void* A, int64_t lda, int64_t n, void* out,
-                          int64_t ldo, fs_dtype dt, hipStream_t st) {
+                          int64_t ldo, fs_dtype dt, hipStream_t st, EventPair ev) {
   int tn = 256;
   if (n <= 64) tn = 64; else if (n <= 128) tn = 128;
   while (tn > 64 && (int64_t)p.Br * tn * 4 > kGenericLdsBytes) tn >>= 1;
@@ -81,9 +81,11 @@ hipError_t launch_generic(const SketchParams& p, const void* A, int64_t lda, int
   const size_t lds = (size_t)rows_per_pass * tn * 4;
 #define FS_GO(T, P2) \
   hipLaunchKernelGGL((generic_kernel<T, P2>), grid, block, lds, st, p, (const T*)A, lda, (int)n, (T*)out, ldo, rows_per_pass)
+  if (ev.start) (void)hipEventRecord(ev.start, st);
   if (dt == FS_F32) { if (p.br_pow2) FS_GO(float, true); else FS_GO(float, false); }
   else              { if (p.br_pow2) FS_GO(uint16_t, true); else FS_GO(uint16_t, false); }
 #undef FS_GO
+  if (ev.stop) (void)hipEventRecord(ev.stop, st);
   return hipGetLastError();
 }
 

@@ -53,7 +53,7 @@ size_t scatter_workspace_bytes(const SketchParams& p, int64_t n, fs_dtype dt) {
 }
 
 hipError_t launch_scatter(const SketchParams& p, const void* A, int64_t lda, int64_t n, void* out,
-                          int64_t ldo, fs_dtype dt, void* ws, hipStream_t st) {
+                          int64_t ldo, fs_dtype dt, void* ws, hipStream_t st, EventPair ev) {
   const unsigned jt = (unsigned)((n + 255) / 256);
   const unsigned slabs = (p.Bc + kScatterRows - 1) / kScatterRows;
   if (jt > 65535u) return hipErrorInvalidValue;
@@ -64,9 +64,11 @@ hipError_t launch_scatter(const SketchParams& p, const void* A, int64_t lda, int
   dim3 grid(slabs, jt), block(256);
 #define FS_GO(T, P2) \
   hipLaunchKernelGGL((scatter_kernel<T, P2>), grid, block, 0, st, p, (const T*)A, lda, (int)n, acc, ldacc)
+  if (ev.start) (void)hipEventRecord(ev.start, st);
   if (dt == FS_F32) { if (p.br_pow2) FS_GO(float, true); else FS_GO(float, false); }
   else              { if (p.br_pow2) FS_GO(uint16_t, true); else FS_GO(uint16_t, false); }
 #undef FS_GO
+  if (ev.stop) (void)hipEventRecord(ev.stop, st);
   if (dt == FS_BF16)
     hipLaunchKernelGGL(scatter_finalize_bf16, dim3(jt, zrows), dim3(256), 0, st, acc, p.k, (int)n,
                        (uint16_t*)out, ldo);
