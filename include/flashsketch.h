@@ -90,6 +90,9 @@ typedef struct {
   int32_t kind;        /* fs_kind                                           */
   int32_t variant;     /* fs_variant requested                              */
   int32_t last_variant;/* variant the most recent apply actually launched   */
+  int32_t last_mode;   /* its work decomposition: 0 one tile per work-group (generic),
+                          1 MFMA output-stationary, 2 MFMA input-stationary with
+                          partial planes, 3 the same with orbit runs merged in LDS */
   int32_t last_hip_error; /* hipError_t of the last failed HIP call, else 0 */
   uint64_t workspace_bytes; /* size of the workspace currently attached     */
 } fs_info;

@@ -11,7 +11,7 @@ import os
 import torch  # must precede the CDLL: the library binds to the HIP runtime torch has loaded
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-lib_path = os.path.join(_HERE, "libflashsketch.so")
+lib_path = os.environ.get("FLASHSKETCH_LIB") or os.path.join(_HERE, "libflashsketch.so")
 
 FS_F32, FS_BF16 = 0, 1
 KIND_BLOCKPERM, KIND_SJLT_SCATTER, KIND_GAUSS_DENSE = 0, 1, 2
@@ -38,7 +38,7 @@ class fs_info(C.Structure):
         ("M", C.c_int32), ("a", C.c_int32), ("b", C.c_int32), ("a_inv", C.c_int32),
         ("key0", C.c_uint32), ("key1", C.c_uint32),
         ("scale", C.c_float),
-        ("kind", C.c_int32), ("variant", C.c_int32), ("last_variant", C.c_int32),
+        ("kind", C.c_int32), ("variant", C.c_int32), ("last_variant", C.c_int32), ("last_mode", C.c_int32),
         ("last_hip_error", C.c_int32),
         ("workspace_bytes", C.c_uint64),
     ]

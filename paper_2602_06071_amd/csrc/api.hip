@@ -92,6 +92,26 @@ fs_status ensure_workspace(fs_sketch_t h, size_t need) {
   return FS_OK;
 }
 
+// pos2blk[q] = f^q(0), blk2pos = its inverse; uploaded once per handle.
+fs_status ensure_orbit(fs_sketch_t h) {
+  if (h->orbit || !fs::mfma_wants_orbit(h->p)) return FS_OK;
+  const uint32_t M = h->p.M;
+  std::vector<uint32_t> tab(2 * (size_t)M);
+  uint32_t x = 0;
+  for (uint32_t q = 0; q < M; ++q) {
+    tab[q] = x;
+    tab[M + x] = q;
+    x = fs::wire_next(x, h->p.a, h->p.b, M);
+  }
+  void* dev = nullptr;
+  hipError_t e = hipMalloc(&dev, tab.size() * sizeof(uint32_t));
+  if (e != hipSuccess) { hip_fail(h, e); return FS_ERR_ALLOC; }
+  e = hipMemcpy(dev, tab.data(), tab.size() * sizeof(uint32_t), hipMemcpyHostToDevice);
+  if (e != hipSuccess) { (void)hipFree(dev); return hip_fail(h, e); }
+  h->orbit = (uint32_t*)dev;
+  return FS_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -138,11 +158,13 @@ fs_status fs_sketch_create_kind(fs_sketch_t* out, fs_kind kind, int64_t d, int64
   h->kind = (int)kind;
   h->variant = FS_VARIANT_AUTO;
   h->last_variant = 0;
+  h->last_mode = 0;
   h->last_hip_error = 0;
   h->device = -1;
   h->ws = nullptr; h->ws_bytes = 0; h->ws_owned = true;
   h->dense_f32 = nullptr; h->dense_bf16 = nullptr;
   h->profiling = false; h->prof_used = 0;
+  h->orbit = nullptr;
 
   if (kind == FS_KIND_GAUSS_DENSE) {
     if ((double)k * (double)d > 4.0e9) { delete h; return FS_ERR_UNSUPPORTED; }
@@ -210,6 +232,7 @@ fs_status fs_sketch_destroy(fs_sketch_t h) {
   fs_status st = FS_OK;
   release_events(h);
   if (h->ws && h->ws_owned && hipFree(h->ws) != hipSuccess) st = FS_ERR_HIP;
+  if (h->orbit && hipFree(h->orbit) != hipSuccess) st = FS_ERR_HIP;
   if (h->dense_f32 && hipFree(h->dense_f32) != hipSuccess) st = FS_ERR_HIP;
   if (h->dense_bf16 && hipFree(h->dense_bf16) != hipSuccess) st = FS_ERR_HIP;
   if (st != FS_OK) (void)hipGetLastError();
@@ -225,7 +248,7 @@ fs_status fs_sketch_info(fs_sketch_t h, fs_info* o) {
   o->M = (int32_t)p.M; o->a = (int32_t)p.a; o->b = (int32_t)p.b; o->a_inv = (int32_t)p.a_inv;
   o->key0 = h->key0; o->key1 = p.key1;
   o->scale = p.scale;
-  o->kind = h->kind; o->variant = h->variant; o->last_variant = h->last_variant;
+  o->kind = h->kind; o->variant = h->variant; o->last_variant = h->last_variant; o->last_mode = h->last_mode;
   o->last_hip_error = h->last_hip_error;
   o->workspace_bytes = h->ws_bytes;
   return FS_OK;
@@ -282,6 +305,10 @@ fs_status fs_sketch_apply_ld(fs_sketch_t h, const void* A, int64_t lda, int64_t 
   if (rc != FS_OK) return rc;
   rc = ensure_workspace(h, need);
   if (rc != FS_OK) return rc;
+  if (variant == FS_VARIANT_MFMA) {
+    rc = ensure_orbit(h);
+    if (rc != FS_OK) return rc;
+  }
 
   fs::EventPair ev;
   if (h->profiling && h->prof_used < (int)h->prof_start.size()) {
@@ -290,16 +317,18 @@ fs_status fs_sketch_apply_ld(fs_sketch_t h, const void* A, int64_t lda, int64_t 
     ++h->prof_used;
   }
   hipError_t e;
+  int mode = 0;
   if (h->kind == FS_KIND_SJLT_SCATTER) {
     e = fs::launch_scatter(h->p, A, lda, n, out, ldo, dt, h->ws, st, ev);
   } else if (h->kind == FS_KIND_GAUSS_DENSE) {
     e = fs::launch_gauss(h->dense_f32, h->dense_bf16, h->p.k, h->p.d, A, lda, n, out, ldo, dt, st, ev);
   } else if (variant == FS_VARIANT_MFMA) {
-    e = fs::launch_mfma(h->p, A, lda, n, out, ldo, dt, h->ws, st, ev);
+    e = fs::launch_mfma(h->p, A, lda, n, out, ldo, dt, h->ws, h->orbit, st, ev, &mode);
   } else {
     e = fs::launch_generic(h->p, A, lda, n, out, ldo, dt, st, ev);
   }
   h->last_variant = variant;
+  h->last_mode = mode;
   if (e != hipSuccess) return hip_fail(h, e);
   return FS_OK;
 }

@@ -23,6 +23,7 @@ struct fs_sketch_s {
   int kind;
   int variant;
   int last_variant;
+  int last_mode;
   int last_hip_error;
   int device;  // device that owns ws / dense (-1: none yet)
   // internal or caller-owned workspace
@@ -33,6 +34,8 @@ struct fs_sketch_s {
   bool profiling;
   int prof_used;
   std::vector<hipEvent_t> prof_start, prof_stop;
+  // orbit order of the blocks under the wiring map (2*M words, device), built on first use
+  uint32_t* orbit;
   // GAUSS_DENSE: k x d matrix, fp32 and bf16 copies
   float* dense_f32;
   void* dense_bf16;
@@ -58,8 +61,12 @@ hipError_t launch_generic(const SketchParams& p, const void* A, int64_t lda, int
 bool mfma_supported(const SketchParams& p, const void* A, int64_t lda, int64_t n, const void* out,
                     int64_t ldo, fs_dtype dt);
 size_t mfma_workspace_bytes(const SketchParams& p, int64_t n, fs_dtype dt);
+// orbit: device array of 2*M words (block at each orbit position of the wiring map
+// starting from block 0, then the inverse), or NULL.
+bool mfma_wants_orbit(const SketchParams& p);
 hipError_t launch_mfma(const SketchParams& p, const void* A, int64_t lda, int64_t n, void* out,
-                       int64_t ldo, fs_dtype dt, void* ws, hipStream_t st, EventPair ev);
+                       int64_t ldo, fs_dtype dt, void* ws, const uint32_t* orbit, hipStream_t st,
+                       EventPair ev, int* mode);
 
 // Plain SJLT, global float atomics.  ws: k*n floats for bf16 output, unused for fp32.
 size_t scatter_workspace_bytes(const SketchParams& p, int64_t n, fs_dtype dt);

@@ -29,8 +29,19 @@
 //                      them as fp32 partial planes; a second kernel adds the planes
 //                      in fixed order, scales and stores (deterministic).
 //
+//      IN-stationary, orbit runs (RUN = 4)  all kappa permutations are powers of one
+//                      full-cycle map f (Appendix E), so in the order of f's orbit the
+//                      input block at position q feeds the outputs at positions
+//                      q-1..q-kappa.  A work-group takes RUN consecutive orbit
+//                      positions (one pair of waves each), and before anything leaves
+//                      the CU adds up, in LDS, the tiles that go to the same output:
+//                      kappa+RUN-1 tiles leave instead of kappa*RUN, which cuts the
+//                      partial-plane traffic by kappa*RUN/(kappa+RUN-1).
+//
 // Inputs must be finite: a dense product multiplies every element by the zeros of
 // Phi as well, so an Inf/NaN in A spreads to all rows of the blocks that read it.
+#include <type_traits>
+
 #include "convert.h"
 #include "handle.h"
 #include "spec.h"
@@ -54,6 +65,7 @@ struct MfmaArgs {
   const void* A;
   void* out;
   float* ws;
+  const uint32_t* pos2blk;  // orbit order of the blocks (RUN > 1 only)
   int64_t lda, ldo, ldw;
   int n;
   int zsplit;       // IN: row splits of an input block
@@ -69,20 +81,14 @@ __device__ __forceinline__ uint32_t perm(uint32_t hi_src, uint32_t lo_src, uint3
   return __builtin_amdgcn_perm(hi_src, lo_src, sel);
 }
 
-// 4 consecutive columns of one row; lanes beyond n read nothing.
+// 4 consecutive columns of one row, element by element; columns >= n read as 0.
 template <typename T>
-__device__ __forceinline__ typename Ld<T>::V load4(const T* rowp, int col0, int n) {
+__device__ __forceinline__ typename Ld<T>::V load4_guarded(const T* p4, int col0, int n) {
   using V = typename Ld<T>::V;
-  V v;
-  if (col0 + 3 < n) {
-    v = *reinterpret_cast<const V*>(rowp + col0);
-  } else {
-    T e[4];
+  T e[4];
 #pragma unroll
-    for (int c = 0; c < 4; ++c) e[c] = (col0 + c < n) ? rowp[col0 + c] : (T)0;
-    v = *reinterpret_cast<V*>(e);
-  }
-  return v;
+  for (int c = 0; c < 4; ++c) e[c] = (col0 + c < n) ? p4[c] : (T)0;
+  return *reinterpret_cast<V*>(e);
 }
 
 // MFMA B operands of the four column residues from 8 rows x 4 columns (bf16).
@@ -128,25 +134,35 @@ __device__ __forceinline__ f32x16 mfma(uint4 a, uint4 b, f32x16 c) {
                                                  __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
 }
 
-template <typename T, int MT, int NRG, int NCG, bool IN_STAT>
-__global__ __launch_bounds__(64 * NRG * NCG) __attribute__((amdgpu_waves_per_eu(2)))
+template <typename T, int MT, int NRG, int NCG, bool IN_STAT, int RUN>
+__global__ __launch_bounds__(64 * NRG * NCG * RUN) __attribute__((amdgpu_waves_per_eu(2)))
 void mfma_kernel(MfmaArgs a) {
   using V = typename Ld<T>::V;
   constexpr int PFD = Ld<T>::PFD;
-  constexpr int NW = NRG * NCG, NT = 64 * NW;
-  constexpr int RW = 32 * MT * NRG;  // stacked Phi rows per work-group
+  constexpr int NW = NRG * NCG, NT = 64 * NW;  // waves / threads of one sub-group
+  constexpr int RW = 32 * MT * NRG;            // stacked Phi rows per sub-group
   constexpr int PHI_ELEMS = RW * PHI_LD;
+  static_assert(RUN == 1 || IN_STAT, "orbit runs are an IN-stationary mode");
 
-  __shared__ __attribute__((aligned(16))) uint16_t s_phi[3][PHI_ELEMS];
-  __shared__ uint32_t s_bk[MAX_KAPPA];   // block keys per slot
-  __shared__ uint32_t s_blk[MAX_KAPPA];  // IN: destination block g_l;  OUT: source block h_l
-
+  // dynamic LDS: [RUN][3][PHI_ELEMS] bf16 tiles, then [RUN][MAX_KAPPA] keys and blocks;
+  // the tile region is reused as the merge buffer of the RUN > 1 epilogue
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const SketchParams& p = a.p;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int sg = RUN > 1 ? (int)threadIdx.x / NT : 0;  // sub-group: one input block each
+  const int tid = RUN > 1 ? (int)threadIdx.x % NT : (int)threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  uint16_t(*s_phi)[PHI_ELEMS] =
+      reinterpret_cast<uint16_t(*)[PHI_ELEMS]>(smem + (size_t)sg * 3 * PHI_ELEMS * 2);
+  uint32_t* s_bk = reinterpret_cast<uint32_t*>(smem + (size_t)RUN * 3 * PHI_ELEMS * 2) +
+                   sg * 2 * MAX_KAPPA;   // block keys per slot
+  uint32_t* s_blk = s_bk + MAX_KAPPA;    // IN: destination block g_l;  OUT: source block h_l
+
   const int rg = wave / NCG, cg = wave % NCG;
   const int kg = lane >> 5;
   const int col0 = (int)blockIdx.y * (WCOLS * NCG) + cg * WCOLS + 4 * (lane & 31);
-  const uint32_t blk = blockIdx.x;  // IN: h, OUT: g
+  // IN: input block h (RUN > 1: the block at orbit position blockIdx.x*RUN + sg); OUT: g
+  uint32_t blk = blockIdx.x;
+  if (RUN > 1) blk = __builtin_amdgcn_readfirstlane(a.pos2blk[blockIdx.x * RUN + sg]);
   const int z = IN_STAT ? (int)blockIdx.z : 0;
   const int T_stages = a.stages;
   const uint32_t rows_per_blk_stage = p.Bc / KC;  // stages per input block (OUT)
@@ -165,34 +181,38 @@ void mfma_kernel(MfmaArgs a) {
   }
   __syncthreads();
 
-  // first row of A of global k-step kk (16 rows each) of this work-group
+  // first row of A of global k-step kk (16 rows each) of this work-group; wave-uniform
   auto row_of = [&](int kk) -> int64_t {
     if (IN_STAT) {
       return (int64_t)blk * p.Bc + (int64_t)z * T_stages * KC + (int64_t)kk * 16;
     } else {
       const uint32_t per_blk = p.Bc / 16;
       const uint32_t l = (uint32_t)kk / per_blk, kr = (uint32_t)kk % per_blk;
-      return (int64_t)s_blk[l] * p.Bc + (int64_t)kr * 16;
+      const uint32_t hb = __builtin_amdgcn_readfirstlane(s_blk[l]);
+      return (int64_t)hb * p.Bc + (int64_t)kr * 16;
     }
   };
-  const T* Abase = reinterpret_cast<const T*>(a.A);
-  const int total_ksteps = T_stages * KSTEPS;
+  const char* Abase = reinterpret_cast<const char*>(a.A);
+  // per-lane byte offset of its first row inside a 16-row k-step (fits 32 bits: checked on
+  // the host); the other 7 rows are reached through the scalar base
+  const uint32_t voff = (uint32_t)(((int64_t)(kg * 8) * a.lda + col0) * (int64_t)sizeof(T));
+  const int64_t row_bytes = a.lda * (int64_t)sizeof(T);
 
-  V ld[PFD][8];
-  auto issue = [&](int kk, V (&dst)[8]) {
-    if (kk < total_ksteps) {
-      const T* rp = Abase + (row_of(kk) + kg * 8) * a.lda;
+  f32x16 acc[MT][4];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) dst[j] = load4<T>(rp + (int64_t)j * a.lda, col0, a.n);
-    }
-  };
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[mt][c][i] = 0.f;
 
-  // Scatter the nonzeros of stage t into tile `buf` (one lane per (slot, row) pair).
-  auto produce = [&](int t, int buf) {
+  // Scatter the nonzeros of part `part` (of KSTEPS) of stage t into tile `buf`:
+  // one lane per (slot, row) pair.
+  auto produce = [&](int t, int buf, int part) {
     uint16_t* phi = &s_phi[buf][0];
     if (IN_STAT) {
       const uint32_t u = (uint32_t)(z * T_stages + t) * KC + lane;
-      for (uint32_t slot = wave; slot < p.kappa; slot += NW) {
+      for (uint32_t slot = wave + part * NW; slot < p.kappa; slot += NW * KSTEPS) {
         const RowHash rh = row_hash_pow2(s_bk[slot], u, p.Br);
         uint32_t r = rh.shift;
         for (uint32_t i = 0; i < p.s; ++i) {
@@ -200,7 +220,7 @@ void mfma_kernel(MfmaArgs a) {
           r = (r + rh.stride) & (p.Br - 1);
         }
       }
-    } else if (wave == 0) {
+    } else if (wave == 0 && part == 0) {
       const uint32_t l = (uint32_t)t / rows_per_blk_stage;
       const uint32_t u = ((uint32_t)t % rows_per_blk_stage) * KC + lane;
       const RowHash rh = row_hash_pow2(s_bk[l], u, p.Br);
@@ -212,64 +232,162 @@ void mfma_kernel(MfmaArgs a) {
     }
   };
 
-  f32x16 acc[MT][4];
+  // The main loop, once for full column tiles (unguarded vector loads) and once
+  // for the ragged last tile (guarded element loads); the choice is uniform per
+  // work-group.
+  auto body = [&](auto ragged_tag) {
+    constexpr bool RAGGED = decltype(ragged_tag)::value;
+    V ld[PFD][8];
+    // Buffer descriptor over the rows this work-group reads from one input block
+    // (dword 3 = 32-bit data format for gfx9-family raw buffers).  The scalar offset
+    // walks the rows, the lane offset (voff) selects row-in-k-step and column.
+    auto make_rsrc = [&](int64_t first_row, int64_t nrows) {
+      const int64_t bytes = (nrows - 1) * row_bytes + (int64_t)a.n * (int64_t)sizeof(T);
+      return __builtin_amdgcn_make_buffer_rsrc(
+          const_cast<char*>(Abase + first_row * row_bytes), 0, (int)bytes, 0x00020000);
+    };
+    auto issue = [&](int kk, V (&dst)[8]) {
+      if constexpr (RAGGED) {
+        const char* sb = Abase + row_of(kk) * row_bytes;
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-    for (int c = 0; c < 4; ++c)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) acc[mt][c][i] = 0.f;
-
-  produce(0, 0);
-#pragma unroll
-  for (int i = 0; i < PFD; ++i) issue(i, ld[i]);
-
-  for (int t = 0; t < T_stages; ++t) {
-    __syncthreads();
-    {  // clear the tile consumed in the previous stage, fill the next one
-      uint4* z4 = reinterpret_cast<uint4*>(&s_phi[(t + 2) % 3][0]);
-      for (int i = tid; i < PHI_ELEMS / 8; i += NT) z4[i] = make_uint4(0, 0, 0, 0);
-      if (t + 1 < T_stages) produce(t + 1, (t + 1) % 3);
-    }
-    const uint16_t* phi = &s_phi[t % 3][0];
-#pragma unroll
-    for (int ks = 0; ks < KSTEPS; ++ks) {
-      uint4 pa[MT];
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
-        pa[mt] = *reinterpret_cast<const uint4*>(
-            phi + ((rg * MT + mt) * 32 + (lane & 31)) * PHI_LD + ks * 16 + kg * 8);
-      V(&cur)[8] = ld[ks % PFD];
-      if constexpr (sizeof(T) == 2) {
-        uint4 op[4];
-        make_ops(cur, op);
-        issue(t * KSTEPS + ks + PFD, cur);
-#pragma unroll
-        for (int c = 0; c < 4; ++c)
-#pragma unroll
-          for (int mt = 0; mt < MT; ++mt) acc[mt][c] = mfma(pa[mt], op[c], acc[mt][c]);
+        for (int j = 0; j < 8; ++j)
+          dst[j] = load4_guarded<T>(reinterpret_cast<const T*>(sb + j * row_bytes + voff), col0, a.n);
       } else {
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-          uint32_t xs[8];
-#pragma unroll
-          for (int j = 0; j < 8; ++j)
-            xs[j] = c == 0 ? cur[j].x : c == 1 ? cur[j].y : c == 2 ? cur[j].z : cur[j].w;
-          uint4 hi, mid, lo;
-          split_ops(xs, hi, mid, lo);
-#pragma unroll
-          for (int mt = 0; mt < MT; ++mt) {
-            acc[mt][c] = mfma(pa[mt], hi, acc[mt][c]);
-            acc[mt][c] = mfma(pa[mt], mid, acc[mt][c]);
-            acc[mt][c] = mfma(pa[mt], lo, acc[mt][c]);
-          }
+        __amdgpu_buffer_rsrc_t rs;
+        uint32_t so;
+        if (IN_STAT) {
+          rs = make_rsrc((int64_t)blk * p.Bc + (int64_t)z * T_stages * KC, (int64_t)T_stages * KC);
+          so = (uint32_t)kk * 16u * (uint32_t)row_bytes;
+        } else {
+          const uint32_t per_blk = p.Bc / 16;
+          const uint32_t l = (uint32_t)kk / per_blk, kr = (uint32_t)kk % per_blk;
+          const uint32_t hb = __builtin_amdgcn_readfirstlane(s_blk[l]);
+          rs = make_rsrc((int64_t)hb * p.Bc, p.Bc);
+          so = kr * 16u * (uint32_t)row_bytes;
         }
-        issue(t * KSTEPS + ks + PFD, cur);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const uint32_t soj = so + (uint32_t)j * (uint32_t)row_bytes;
+          if constexpr (sizeof(T) == 2)
+            dst[j] = __builtin_bit_cast(V, __builtin_amdgcn_raw_buffer_load_b64(rs, voff, soj, 0));
+          else
+            dst[j] = __builtin_bit_cast(V, __builtin_amdgcn_raw_buffer_load_b128(rs, voff, soj, 0));
+        }
       }
-    }
-  }
+    };
+
+    // One stage: 4 MFMA k-steps on tile t%3 while the next stage is loaded and hashed.
+    // LAST stages issue no loads and fill no tile, so that the steady-state loop body has
+    // no conditional memory operations.
+    auto stage = [&](int t, auto last_tag) {
+      constexpr bool LAST = decltype(last_tag)::value;
+      __syncthreads();
+      const uint16_t* phi = &s_phi[t % 3][0];
+      uint4* zero4 = reinterpret_cast<uint4*>(&s_phi[(t + 2) % 3][0]);
+      const int fill_buf = (t + 1) % 3;
+#pragma unroll
+      for (int ks = 0; ks < KSTEPS; ++ks) {
+        uint4 pa[MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+          pa[mt] = *reinterpret_cast<const uint4*>(
+              phi + ((rg * MT + mt) * 32 + (lane & 31)) * PHI_LD + ks * 16 + kg * 8);
+        if constexpr (!LAST) {
+          // a quarter of: clear the tile consumed in the previous stage, fill the next one
+          for (int i = ks * (PHI_ELEMS / 32) + tid; i < (ks + 1) * (PHI_ELEMS / 32); i += NT)
+            zero4[i] = make_uint4(0, 0, 0, 0);
+          produce(t + 1, fill_buf, ks);
+        }
+        V(&cur)[8] = ld[ks % PFD];
+        const bool fetch = !LAST || ks + PFD < KSTEPS;  // compile-time after unrolling
+        if constexpr (sizeof(T) == 2) {
+          uint4 op[4];
+          make_ops(cur, op);
+          if (fetch) issue(t * KSTEPS + ks + PFD, cur);
+#pragma unroll
+          for (int c = 0; c < 4; ++c)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) acc[mt][c] = mfma(pa[mt], op[c], acc[mt][c]);
+        } else {
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            uint32_t xs[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+              xs[j] = c == 0 ? cur[j].x : c == 1 ? cur[j].y : c == 2 ? cur[j].z : cur[j].w;
+            uint4 hi, mid, lo;
+            split_ops(xs, hi, mid, lo);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+              acc[mt][c] = mfma(pa[mt], hi, acc[mt][c]);
+              acc[mt][c] = mfma(pa[mt], mid, acc[mt][c]);
+              acc[mt][c] = mfma(pa[mt], lo, acc[mt][c]);
+            }
+          }
+          if (fetch) issue(t * KSTEPS + ks + PFD, cur);
+        }
+        __builtin_amdgcn_sched_barrier(0);  // keep k-steps apart: bounds register pressure
+      }
+    };
+
+#pragma unroll
+    for (int part = 0; part < KSTEPS; ++part) produce(0, 0, part);
+#pragma unroll
+    for (int i = 0; i < PFD; ++i) issue(i, ld[i]);
+    for (int t = 0; t + 1 < T_stages; ++t) stage(t, std::false_type{});
+    stage(T_stages - 1, std::true_type{});
+  };
+  const bool full_tile = ((int)blockIdx.y + 1) * (WCOLS * NCG) <= a.n;
+  if (full_tile) body(std::false_type{}); else body(std::true_type{});
 
   // ---- epilogue ------------------------------------------------------------
+  if constexpr (RUN > 1) {
+    // Merge in LDS the tiles of the RUN sub-groups that go to the same output block:
+    // sub-group j, slot l-1 lands on relative output position idx = j - l + kappa
+    // (0 .. kappa+RUN-2).  Sub-groups take turns in index order, so the sum order is fixed.
+    constexpr int TNW = WCOLS * NCG;
+    float* mbuf = reinterpret_cast<float*>(smem);  // [kappa+RUN-1][Br][TNW]
+    const int colw = cg * WCOLS + 4 * (lane & 31);
+    __syncthreads();  // every wave is done with the Phi tiles
+    for (int j = 0; j < RUN; ++j) {
+      if (sg == j) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const uint32_t row_s = (uint32_t)((rg * MT + mt) * 32 + 8 * (i >> 2) + 4 * kg + (i & 3));
+            const uint32_t slot = row_s / p.Br, r = row_s & (p.Br - 1);
+            const uint32_t idx = (uint32_t)j + p.kappa - 1u - slot;
+            float4* d = reinterpret_cast<float4*>(mbuf + ((size_t)(idx * p.Br + r)) * TNW + colw);
+            float4 v = make_float4(acc[mt][0][i], acc[mt][1][i], acc[mt][2][i], acc[mt][3][i]);
+            if (!(slot == 0 || j == 0)) {  // not the first sub-group to reach this tile
+              const float4 o = *d;
+              v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
+            }
+            *d = v;
+          }
+        }
+      }
+      __syncthreads();
+    }
+    // cooperative store of the kappa+RUN-1 merged tiles to their partial planes
+    const uint32_t tiles = p.kappa + RUN - 1;
+    const uint32_t per_tile = p.Br * (TNW / 4);
+    const uint32_t q0 = blockIdx.x * RUN;
+    for (uint32_t e = threadIdx.x; e < tiles * per_tile; e += NT * RUN) {
+      const uint32_t idx = e / per_tile, rem = e % per_tile;
+      const uint32_t r = rem / (TNW / 4), c4 = rem % (TNW / 4);
+      const int col = (int)blockIdx.y * TNW + (int)c4 * 4;
+      if (col >= a.n) continue;
+      const uint32_t pos = (q0 + idx + p.M - p.kappa) % p.M;
+      const uint32_t g = a.pos2blk[pos];
+      const int64_t plane = idx / RUN;
+      float* dst = a.ws + (plane * p.k + (int64_t)g * p.Br + r) * a.ldw + col;
+      *reinterpret_cast<float4*>(dst) =
+          *reinterpret_cast<const float4*>(mbuf + ((size_t)(idx * p.Br + r)) * TNW + c4 * 4);
+    }
+    return;
+  }
   if (col0 >= a.n) return;
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
@@ -306,20 +424,27 @@ void mfma_kernel(MfmaArgs a) {
 }
 
 // out[row][col] = scale * sum_p ws[p][row][col], planes added in index order.
+// RUN > 1: plane c of the output block at orbit position pos holds a tile only when
+// delta = c*RUN + (pos%RUN + kappa)%RUN - kappa <= RUN-2 (the writer's relative position).
 template <typename T>
 __global__ __launch_bounds__(256) void reduce_planes_kernel(const float* __restrict__ ws, int planes,
                                                             int64_t k, int64_t ldw, int n,
                                                             T* __restrict__ out, int64_t ldo,
-                                                            float scale, int out_vec) {
+                                                            float scale, int out_vec, int run,
+                                                            const uint32_t* __restrict__ blk2pos,
+                                                            uint32_t Br, uint32_t kappa) {
   const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;  // over k * ldw/4
   const int64_t q = ldw / 4;
   if (idx >= k * q) return;
   const int64_t row = idx / q;
   const int col0 = (int)(idx % q) * 4;
   if (col0 >= n) return;
+  uint32_t rho_k = 0;
+  if (run > 1) rho_k = (blk2pos[row / Br] % (uint32_t)run + kappa) % (uint32_t)run;
   const float* src = ws + row * ldw + col0;
-  float4 s = *reinterpret_cast<const float4*>(src);
-  for (int pl = 1; pl < planes; ++pl) {
+  float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int pl = 0; pl < planes; ++pl) {
+    if (run > 1 && (int)(pl * run + rho_k) - (int)kappa > run - 2) break;  // later planes: empty too
     const float4 v = *reinterpret_cast<const float4*>(src + (int64_t)pl * k * ldw);
     s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
   }
@@ -345,10 +470,13 @@ __global__ __launch_bounds__(256) void reduce_planes_kernel(const float* __restr
 struct Plan {
   bool ok = false;
   bool in_stat = false;
-  int mt = 0, nrg = 0, ncg = 0, zsplit = 1, stages = 0;
+  int mt = 0, nrg = 0, ncg = 0, zsplit = 1, stages = 0, run = 1;
   int64_t ldw = 0;
   int planes = 0;
+  size_t lds = 0;
 };
+
+constexpr size_t kLdsBudget = 160 * 1024;
 
 bool tile_shape(uint32_t rw, int* mt, int* nrg) {
   if (rw == 32) { *mt = 1; *nrg = 1; return true; }
@@ -357,16 +485,23 @@ bool tile_shape(uint32_t rw, int* mt, int* nrg) {
   return false;
 }
 
-Plan make_plan(const SketchParams& p, const void* A, int64_t lda, int64_t n, fs_dtype dt) {
+size_t lds_bytes(int mt, int nrg, int run) {
+  return (size_t)run * (3 * (size_t)(32 * mt * nrg) * PHI_LD * 2 + 2 * MAX_KAPPA * 4);
+}
+
+Plan make_plan(const SketchParams& p, const void* A, int64_t lda, int64_t n, fs_dtype dt,
+               bool have_orbit) {
   Plan pl;
   const size_t esz = dt == FS_F32 ? 4 : 2;
   if (!p.br_pow2 || p.Bc % KC || p.kappa > (uint32_t)MAX_KAPPA || n < 1) return pl;
   if ((uintptr_t)A % (4 * esz) || (lda * esz) % (4 * esz)) return pl;  // 4-column vector loads
+  if ((16 * lda + n) * (int64_t)esz >= ((int64_t)1 << 31)) return pl;     // 32-bit lane offsets
+  if ((int64_t)p.Bc * lda * (int64_t)esz >= ((int64_t)1 << 31)) return pl;  // 32-bit row offsets in a block
   pl.ncg = n > WCOLS ? 2 : 1;
   const int64_t col_tiles = (n + WCOLS * pl.ncg - 1) / (WCOLS * pl.ncg);
   if (col_tiles > 65535) return pl;
 
-  int mt_i, nrg_i, mt_o, nrg_o;
+  int mt_i = 0, nrg_i = 0, mt_o = 0, nrg_o = 0;
   const bool can_in = (uint64_t)p.kappa * p.Br <= 128 && tile_shape(p.kappa * p.Br, &mt_i, &nrg_i);
   const bool can_out = tile_shape(p.Br, &mt_o, &nrg_o);
   if (!can_in && !can_out) return pl;
@@ -386,25 +521,48 @@ Plan make_plan(const SketchParams& p, const void* A, int64_t lda, int64_t n, fs_
     pl.ldw = (n + 3) & ~(int64_t)3;
     pl.planes = zs * (int)p.kappa;
     if (zs > 65535) return pl;
+    // orbit runs of 4: the 64-row / 256-column shape, enough blocks for one work-group
+    // per CU, and a merge buffer that fits beside nothing else in LDS
+    constexpr int R = 4;
+    const size_t merge = (size_t)(p.kappa + R - 1) * p.Br * (WCOLS * 2) * 4;
+    if (have_orbit && zs == 1 && pl.mt == 2 && pl.nrg == 1 && pl.ncg == 2 && p.kappa > 1 &&
+        p.M % R == 0 && (int64_t)(p.M / R) * col_tiles >= 256 && merge <= lds_bytes(2, 1, R)) {
+      pl.run = R;
+      pl.planes = (int)((p.kappa + R - 2) / R) + 1;
+    }
   } else {
     pl.mt = mt_o; pl.nrg = nrg_o; pl.zsplit = 1;
     pl.stages = (int)((uint64_t)p.kappa * p.Bc / KC);
   }
-  pl.ok = true;
+  pl.lds = lds_bytes(pl.mt, pl.nrg, pl.run);
+  pl.ok = pl.lds <= kLdsBudget;
   return pl;
+}
+
+template <typename K>
+hipError_t go(K kernel, dim3 grid, unsigned threads, size_t lds, hipStream_t st, const MfmaArgs& a) {
+  if (lds > 64 * 1024) {  // above the default dynamic-LDS limit: raise it for this kernel
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+  }
+  hipLaunchKernelGGL(kernel, grid, dim3(threads), lds, st, a);
+  return hipGetLastError();
 }
 
 template <typename T, bool IN_STAT>
 hipError_t launch_shape(const Plan& pl, const MfmaArgs& a, dim3 grid, hipStream_t st) {
-#define FS_GO(MT, NRG, NCG) \
-  hipLaunchKernelGGL((mfma_kernel<T, MT, NRG, NCG, IN_STAT>), grid, dim3(64 * NRG * NCG), 0, st, a)
+#define FS_GO(MT, NRG, NCG, RUN) \
+  return go(mfma_kernel<T, MT, NRG, NCG, IN_STAT, RUN>, grid, 64 * NRG * NCG * RUN, pl.lds, st, a)
+  if constexpr (IN_STAT) {
+    if (pl.run == 4) FS_GO(2, 1, 2, 4);
+  }
   if (pl.ncg == 1) {
-    if (pl.mt == 1) FS_GO(1, 1, 1); else if (pl.nrg == 1) FS_GO(2, 1, 1); else FS_GO(2, 2, 1);
+    if (pl.mt == 1) FS_GO(1, 1, 1, 1); else if (pl.nrg == 1) FS_GO(2, 1, 1, 1); else FS_GO(2, 2, 1, 1);
   } else {
-    if (pl.mt == 1) FS_GO(1, 1, 2); else if (pl.nrg == 1) FS_GO(2, 1, 2); else FS_GO(2, 2, 2);
+    if (pl.mt == 1) FS_GO(1, 1, 2, 1); else if (pl.nrg == 1) FS_GO(2, 1, 2, 1); else FS_GO(2, 2, 2, 1);
   }
 #undef FS_GO
-  return hipGetLastError();
 }
 
 }  // namespace
@@ -412,28 +570,36 @@ hipError_t launch_shape(const Plan& pl, const MfmaArgs& a, dim3 grid, hipStream_
 bool mfma_supported(const SketchParams& p, const void* A, int64_t lda, int64_t n, const void* out,
                     int64_t ldo, fs_dtype dt) {
   (void)out; (void)ldo;
-  return make_plan(p, A, lda, n, dt).ok;
+  return make_plan(p, A, lda, n, dt, false).ok;
+}
+
+bool mfma_wants_orbit(const SketchParams& p) {
+  return p.M >= 4 && p.M <= (1u << 20);
 }
 
 size_t mfma_workspace_bytes(const SketchParams& p, int64_t n, fs_dtype dt) {
+  // sized without the orbit-run saving, so it holds for either mode
   const int64_t ld = (n + 7) & ~(int64_t)7;
-  const Plan pl = make_plan(p, (const void*)(uintptr_t)256, ld, n, dt);
+  const Plan pl = make_plan(p, (const void*)(uintptr_t)256, ld, n, dt, false);
   if (!pl.ok || !pl.in_stat) return 0;
   return (size_t)pl.planes * (size_t)p.k * (size_t)pl.ldw * sizeof(float);
 }
 
 hipError_t launch_mfma(const SketchParams& p, const void* A, int64_t lda, int64_t n, void* out,
-                       int64_t ldo, fs_dtype dt, void* ws, hipStream_t st, EventPair ev) {
-  const Plan pl = make_plan(p, A, lda, n, dt);
+                       int64_t ldo, fs_dtype dt, void* ws, const uint32_t* orbit, hipStream_t st,
+                       EventPair ev, int* mode) {
+  const Plan pl = make_plan(p, A, lda, n, dt, orbit != nullptr);
   if (!pl.ok) return hipErrorInvalidValue;
+  *mode = !pl.in_stat ? 1 : pl.run > 1 ? 3 : 2;
   const size_t esz = dt == FS_F32 ? 4 : 2;
   MfmaArgs a;
   a.p = p; a.A = A; a.out = out; a.ws = (float*)ws;
+  a.pos2blk = orbit;
   a.lda = lda; a.ldo = ldo; a.ldw = pl.ldw; a.n = (int)n;
   a.zsplit = pl.zsplit; a.stages = pl.stages;
   a.out_vec = ((uintptr_t)out % (4 * esz) == 0 && (ldo * esz) % (4 * esz) == 0) ? 1 : 0;
   const unsigned col_tiles = (unsigned)((n + WCOLS * pl.ncg - 1) / (WCOLS * pl.ncg));
-  dim3 grid(p.M, col_tiles, pl.in_stat ? pl.zsplit : 1);
+  dim3 grid(p.M / pl.run, col_tiles, pl.in_stat ? pl.zsplit : 1);
 
   if (ev.start) (void)hipEventRecord(ev.start, st);
   hipError_t e;
@@ -446,12 +612,15 @@ hipError_t launch_mfma(const SketchParams& p, const void* A, int64_t lda, int64_
 
   const int64_t work = p.k * (pl.ldw / 4);
   const unsigned blocks = (unsigned)((work + 255) / 256);
+  const uint32_t* blk2pos = orbit ? orbit + p.M : nullptr;
   if (dt == FS_BF16)
     hipLaunchKernelGGL(reduce_planes_kernel<uint16_t>, dim3(blocks), dim3(256), 0, st, a.ws, pl.planes,
-                       p.k, pl.ldw, (int)n, (uint16_t*)out, ldo, p.scale, a.out_vec);
+                       p.k, pl.ldw, (int)n, (uint16_t*)out, ldo, p.scale, a.out_vec, pl.run, blk2pos,
+                       p.Br, p.kappa);
   else
     hipLaunchKernelGGL(reduce_planes_kernel<float>, dim3(blocks), dim3(256), 0, st, a.ws, pl.planes,
-                       p.k, pl.ldw, (int)n, (float*)out, ldo, p.scale, a.out_vec);
+                       p.k, pl.ldw, (int)n, (float*)out, ldo, p.scale, a.out_vec, pl.run, blk2pos,
+                       p.Br, p.kappa);
   return hipGetLastError();
 }
 

@@ -95,6 +95,10 @@ SMALL = [
     ((512, 512, 1, 1, 3, 1), 17, 0, 0),             # Br = Bc = 1
     ((1024, 64, 1024, 64, 1, 8), 1, 0, 0),          # M = 1, single column
     ((3072, 1536, 1024, 512, 2, 8), 70, 0, 0),      # Br > LDS rows per pass
+    ((65536, 8192, 64, 8, 8, 2), 256, 0, 0),        # M = 1024: orbit-run mode of the MFMA path
+    ((65536, 8192, 64, 8, 8, 2), 300, 4, 4),        # the same with a ragged second column tile
+    ((32768, 4096, 128, 16, 4, 4), 1024, 0, 0),     # M = 256, four column tiles, Br = 16
+    ((16384, 2048, 64, 8, 8, 2), 2500, 0, 0),       # M = 256, ten column tiles, ragged
 ]
 
 
@@ -127,7 +131,8 @@ def test_apply_matches_oracle(case, dtype, variant):
 @pytest.mark.parametrize("variant", VARIANTS, ids=lambda v: VNAME[v])
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
 @pytest.mark.parametrize("params", [(4096, 256, 512, 32, 4, 4), (32768, 64, 4096, 8, 8, 2),
-                                    (8192, 512, 1024, 64, 4, 4), (4096, 256, 512, 32, 2, 2)])
+                                    (8192, 512, 1024, 64, 4, 4), (4096, 256, 512, 32, 2, 2),
+                                    (65536, 8192, 64, 8, 8, 2)])
 def test_one_hot_probes_reproduce_columns_exactly(params, dtype, variant):
     """A = selected unit vectors: each output column is one column of S; with
     kappa*s a power of four the scale is a power of two, so the match is exact."""
@@ -174,6 +179,20 @@ def test_linearity(variant):
     rhs = 2 * sk.apply(X) - 3 * sk.apply(Y)
     torch.cuda.synchronize()
     assert O.rel_fro_err(host64(lhs), host64(rhs)) < 1e-5
+
+
+def test_mfma_modes_are_the_intended_ones():
+    """The dispatcher picks the decomposition each configuration was designed for."""
+    want = {"grad": 3, "wide": 1, "tall": 2, "tiny": 2}
+    for name, mode in want.items():
+        cfg = W.CONFIGS[name]
+        n = 256 if name == "grad" else min(cfg.n, 512)
+        A = torch.zeros((cfg.d, n), device=DEV, dtype=cfg.dtype)
+        sk = B.Sketch(*cfg.params, seed=0)
+        sk.apply(A)
+        i = sk.info()
+        assert (i.last_variant, i.last_mode) == (B.VARIANT_MFMA, mode), (name, i.last_variant, i.last_mode)
+    torch.cuda.synchronize()
 
 
 def test_forced_variant_on_unsupported_shape_reports_unsupported():
