@@ -69,7 +69,10 @@ typedef enum {
                                Same S as BLOCKPERM with M = 1: needs Bc = d, Br = k,
                                kappa = 1.                                                  */
   FS_KIND_GAUSS_DENSE = 2   /* dense Gaussian sketch S_ij ~ N(0, 1/k) (Section 1) applied
-                               by an MFMA GEMM; Bc, Br, kappa, s are ignored.              */
+                               by an MFMA GEMM; Bc, Br, kappa, s are ignored.  Reference
+                               point only: needs 64 | d, 128 | k, 4 | lda, a 16-byte (fp32)
+                               or 8-byte (bf16) aligned A and d*lda*sizeof(elt) < 2^31,
+                               else apply returns FS_ERR_UNSUPPORTED.                      */
 } fs_kind;
 
 /* Kernel variants of the BLOCKPERM apply (fs_sketch_set_variant). */

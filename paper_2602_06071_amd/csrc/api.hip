@@ -65,7 +65,8 @@ fs_status needed_workspace(fs_sketch_t h, const void* A, int64_t lda, int64_t n,
     *bytes = fs::scatter_workspace_bytes(h->p, n, dt);
     return FS_OK;
   }
-  if (h->kind == FS_KIND_GAUSS_DENSE) return FS_OK;
+  if (h->kind == FS_KIND_GAUSS_DENSE)
+    return fs::gauss_supported(h->p.k, h->p.d, A, lda, n, dt) ? FS_OK : FS_ERR_UNSUPPORTED;
   const bool can = fs::mfma_supported(h->p, A, lda, n, out, ldo, dt);
   int v = h->variant;
   if (v == FS_VARIANT_AUTO) v = can ? FS_VARIANT_MFMA : FS_VARIANT_GENERIC;
@@ -162,20 +163,18 @@ fs_status fs_sketch_create_kind(fs_sketch_t* out, fs_kind kind, int64_t d, int64
   h->last_hip_error = 0;
   h->device = -1;
   h->ws = nullptr; h->ws_bytes = 0; h->ws_owned = true;
-  h->dense_f32 = nullptr; h->dense_bf16 = nullptr;
+  h->dense = nullptr;
   h->profiling = false; h->prof_used = 0;
   h->orbit = nullptr;
 
   if (kind == FS_KIND_GAUSS_DENSE) {
-    if ((double)k * (double)d > 4.0e9) { delete h; return FS_ERR_UNSUPPORTED; }
-    hipError_t e = hipMalloc((void**)&h->dense_f32, (size_t)k * d * sizeof(float));
-    if (e == hipSuccess) e = hipMalloc(&h->dense_bf16, (size_t)k * d * 2);
-    if (e == hipSuccess) e = fs::gauss_fill(h->dense_f32, h->dense_bf16, k, d, p.key1, nullptr);
+    if ((double)k * (double)d > 2.0e9) { delete h; return FS_ERR_UNSUPPORTED; }
+    hipError_t e = hipMalloc(&h->dense, fs::gauss_bytes(k, d));
+    if (e == hipSuccess) e = fs::gauss_fill(h->dense, k, d, p.key1, nullptr);
     if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
     if (e != hipSuccess) {
       (void)hipGetLastError();
-      if (h->dense_f32) (void)hipFree(h->dense_f32);
-      if (h->dense_bf16) (void)hipFree(h->dense_bf16);
+      if (h->dense) (void)hipFree(h->dense);
       const bool oom = (e == hipErrorOutOfMemory);
       delete h;
       return oom ? FS_ERR_ALLOC : FS_ERR_HIP;
@@ -233,8 +232,7 @@ fs_status fs_sketch_destroy(fs_sketch_t h) {
   release_events(h);
   if (h->ws && h->ws_owned && hipFree(h->ws) != hipSuccess) st = FS_ERR_HIP;
   if (h->orbit && hipFree(h->orbit) != hipSuccess) st = FS_ERR_HIP;
-  if (h->dense_f32 && hipFree(h->dense_f32) != hipSuccess) st = FS_ERR_HIP;
-  if (h->dense_bf16 && hipFree(h->dense_bf16) != hipSuccess) st = FS_ERR_HIP;
+  if (h->dense && hipFree(h->dense) != hipSuccess) st = FS_ERR_HIP;
   if (st != FS_OK) (void)hipGetLastError();
   delete h;
   return st;
@@ -321,7 +319,7 @@ fs_status fs_sketch_apply_ld(fs_sketch_t h, const void* A, int64_t lda, int64_t 
   if (h->kind == FS_KIND_SJLT_SCATTER) {
     e = fs::launch_scatter(h->p, A, lda, n, out, ldo, dt, h->ws, st, ev);
   } else if (h->kind == FS_KIND_GAUSS_DENSE) {
-    e = fs::launch_gauss(h->dense_f32, h->dense_bf16, h->p.k, h->p.d, A, lda, n, out, ldo, dt, st, ev);
+    e = fs::launch_gauss(h->dense, h->p.k, h->p.d, A, lda, n, out, ldo, dt, st, ev);
   } else if (variant == FS_VARIANT_MFMA) {
     e = fs::launch_mfma(h->p, A, lda, n, out, ldo, dt, h->ws, h->orbit, st, ev, &mode);
   } else {
@@ -349,7 +347,7 @@ fs_status fs_sketch_export(fs_sketch_t h, int32_t* rows, int8_t* signs, void* st
 fs_status fs_sketch_export_dense(fs_sketch_t h, float* S_dense, void* stream) {
   if (!h || !S_dense) return FS_ERR_INVALID_ARG;
   if (h->kind != FS_KIND_GAUSS_DENSE) return FS_ERR_UNSUPPORTED;
-  hipError_t e = hipMemcpyAsync(S_dense, h->dense_f32, (size_t)h->p.k * h->p.d * sizeof(float),
+  hipError_t e = hipMemcpyAsync(S_dense, h->dense, (size_t)h->p.k * h->p.d * sizeof(float),
                                 hipMemcpyDeviceToDevice, (hipStream_t)stream);
   if (e != hipSuccess) return hip_fail(h, e);
   return FS_OK;

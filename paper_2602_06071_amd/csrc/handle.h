@@ -36,9 +36,8 @@ struct fs_sketch_s {
   std::vector<hipEvent_t> prof_start, prof_stop;
   // orbit order of the blocks under the wiring map (2*M words, device), built on first use
   uint32_t* orbit;
-  // GAUSS_DENSE: k x d matrix, fp32 and bf16 copies
-  float* dense_f32;
-  void* dense_bf16;
+  // GAUSS_DENSE: the k x d matrix in its fp32 and bf16 forms (one allocation)
+  void* dense;
 };
 
 namespace fs {
@@ -73,11 +72,12 @@ size_t scatter_workspace_bytes(const SketchParams& p, int64_t n, fs_dtype dt);
 hipError_t launch_scatter(const SketchParams& p, const void* A, int64_t lda, int64_t n, void* out,
                           int64_t ldo, fs_dtype dt, void* ws, hipStream_t st, EventPair ev);
 
-// Dense Gaussian sketch.
-hipError_t gauss_fill(float* S_f32, void* S_bf16, int64_t k, int64_t d, uint32_t key1,
-                      hipStream_t st);
-hipError_t launch_gauss(const float* S_f32, const void* S_bf16, int64_t k, int64_t d, const void* A,
-                        int64_t lda, int64_t n, void* out, int64_t ldo, fs_dtype dt,
-                        hipStream_t st, EventPair ev);
+// Dense Gaussian sketch.  `storage` holds the k x d matrix as fp32, then four bf16
+// copies (rounded, and the exact split hi / mid / lo): gauss_bytes(k, d) bytes.
+size_t gauss_bytes(int64_t k, int64_t d);
+hipError_t gauss_fill(void* storage, int64_t k, int64_t d, uint32_t key1, hipStream_t st);
+bool gauss_supported(int64_t k, int64_t d, const void* A, int64_t lda, int64_t n, fs_dtype dt);
+hipError_t launch_gauss(const void* storage, int64_t k, int64_t d, const void* A, int64_t lda,
+                        int64_t n, void* out, int64_t ldo, fs_dtype dt, hipStream_t st, EventPair ev);
 
 }  // namespace fs

@@ -232,6 +232,25 @@ def test_plain_sjlt_scatter_matches_oracle(d, k, s, n, dtype):
     assert np.array_equal(signs.cpu().numpy(), want_s)
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("k,d,n,pad", [(128, 1024, 256, 0), (256, 4096, 300, 4), (1024, 2048, 1000, 0)])
+def test_dense_gaussian_matches_oracle(k, d, n, pad, dtype):
+    from oracle import gaussian as G
+    print("gauss", k, d, n, dtype, flush=True)
+    g = torch.Generator(device=DEV).manual_seed(7)
+    A = torch.randn((d, n + pad), generator=g, device=DEV).to(dtype)[:, :n]
+    sk = B.Sketch(d, k, d, k, 1, 1, seed=2, kind=B.KIND_GAUSS_DENSE)
+    out = sk.apply(A)
+    S_dev = sk.export_dense()
+    torch.cuda.synchronize()
+    S = G.gaussian_matrix(k, d, 2)
+    # the same matrix up to the last bit of the device's double-precision log / cos
+    Sd = S_dev.cpu().double().numpy()
+    assert np.abs(Sd - S).max() <= 2.0 ** -22 * np.abs(S).max()
+    assert (Sd != S).mean() < 1e-3
+    check(out, G.apply(S, host64(A)), dtype, "dense gaussian")
+
+
 # ------------------------------------------------ full-size configs -------
 def _sampled_parity(cfg, A, out, ncols=12, seed=0):
     """Oracle on a sample of columns of the full-size problem."""
