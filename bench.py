@@ -70,19 +70,24 @@ def time_workload(torch, B, cfg, A, variant, steps, warmup, kind=None, sketch_pa
     return (t1 - t0) / steps, kernel_ms, used, out
 
 
-def cpu_baseline(torch, cfg, A, budget_cols=None):
-    """The float64 oracle, as it stands, on a bounded sample of the same workload."""
+def cpu_baseline(torch, cfg, A, budget_s=12.0, slice_cols=32):
+    """The float64 oracle, as it stands, on a bounded sample of the same workload:
+    the CSC product S @ A[:, cols] over leading column slices until ~budget_s of CPU
+    time is spent (each slice is widened to float64 on the host first)."""
     from oracle import blockperm as O
     t0 = time.perf_counter()
     S = O.build_csc(O.Params(*cfg.params), cfg.sketch_seed)
     t_build = time.perf_counter() - t0
-    # size the sample for roughly 10 s of sparse-times-dense work (~1.5e9 f64 MAC/s/core)
-    nnz = cfg.d * cfg.kappa * cfg.s
-    cols = budget_cols or int(max(1, min(cfg.n, 1.5e10 // nnz)))
-    A_host = A[:, :cols].to("cpu").to(torch.float64).numpy()
-    t0 = time.perf_counter()
-    Y = O.apply(S, A_host)
-    t_apply = time.perf_counter() - t0
+    t_apply, cols, outs = 0.0, 0, []
+    while cols < cfg.n and t_apply < budget_s:
+        c1 = min(cfg.n, cols + slice_cols)
+        A_host = A[:, cols:c1].to("cpu").to(torch.float64).numpy()
+        t0 = time.perf_counter()
+        outs.append(O.apply(S, A_host))
+        t_apply += time.perf_counter() - t0
+        cols = c1
+    import numpy as np
+    Y = np.concatenate(outs, axis=1)
     gbps = cfg.d * cols * cfg.elt / t_apply / 1e9
     return {
         "value": gbps, "unit": "GB/s", "cores": 1, "kind": "oracle",
