@@ -23,6 +23,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
+# HBM bytes per launch of the dominant kernel on the default workload, from the rocprofv3
+# FETCH_SIZE / WRITE_SIZE runs summarised in profiles/blockperm_mfma_grad_bf16_chunk256.md
+MEASURED_TRAFFIC = {("grad", "mfma"): (2_097_744 + 22_528) * 1024}
 
 
 def parse():
@@ -142,7 +145,8 @@ def main():
         },
         "roofline": {
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-            "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+            "frac": achieved / HBM_PEAK_GBPS,
+            "traffic": MEASURED_TRAFFIC.get((cfg.name, {1: "generic", 2: "mfma"}.get(used))),
             "kernel_ms_avg": avg_kernel_s * 1e3, "launches_timed": len(kernel_ms),
             "algorithmic_bytes_per_launch": alg_bytes,
         },
@@ -178,6 +182,8 @@ def extra_measurements(torch, B, W, dev, skip):
         if name != skip:
             cfg = W.CONFIGS[name]
             res[name] = one(cfg, W.make_input(cfg, dev))
+    if skip != "tall":
+        res["tall_ose"] = tall_distortion(torch, B, W, dev)
     if skip != "mid":
         base = W.CONFIGS["mid"]
         A = W.make_input(base, dev)
@@ -195,6 +201,28 @@ def extra_measurements(torch, B, W, dev, skip):
             res[f"wide_n{n}"] = one(dataclasses.replace(base, n=n), A[:, :n].contiguous())
         del A
     return res
+
+
+def tall_distortion(torch, B, W, dev):
+    """Subspace-embedding distortion ||(SQ)^T (SQ) - I||_2 of S on col(A) for the coherent tall
+    matrix (Q from a float64 QR of A), from the GPU apply on fp32(Q) and from the oracle, next
+    to the block / neighbourhood coherence of Q that the paper's OSE bound is stated in."""
+    import numpy as np
+    from oracle import blockperm as O
+    cfg = W.CONFIGS["tall"]
+    A64, _ = W.coherent_tall(cfg.d, cfg.n, cfg.data_seed)
+    Q = np.linalg.qr(A64.numpy())[0]
+    sk = B.Sketch(*cfg.params, seed=cfg.sketch_seed)
+    SQ = sk.apply(torch.from_numpy(Q).to(torch.float32).to(dev))
+    torch.cuda.synchronize()
+    i = sk.info()
+    S = O.build_csc(O.Params(*cfg.params), cfg.sketch_seed)
+    return {
+        "ose_error_gpu": O.ose_error(SQ.cpu().double().numpy()),
+        "ose_error_oracle": O.ose_error(O.apply(S, Q)),
+        "mu_blk": O.block_coherence(Q, i.M),
+        "mu_nbr": O.nbr_coherence(Q, i.M, i.a, i.b, cfg.kappa),
+    }
 
 
 if __name__ == "__main__":
