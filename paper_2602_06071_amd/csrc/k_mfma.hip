@@ -63,54 +63,64 @@ struct MfmaArgs {
   int zsplit;       // IN: row splits of an input block
   int stages;       // stages per work-group
   int out_vec;      // out rows allow 4-column vector stores
+  uint32_t log2_br;
 };
 
-template <typename T, int MT, int NRG, int NCG, bool IN_STAT, int RUN>
+template <typename T, int MT, int NRG, int NCG, bool IN_STAT, int RUN, int CPL>
 __global__ __launch_bounds__(64 * NRG * NCG * RUN) __attribute__((amdgpu_waves_per_eu(2)))
 void mfma_kernel(MfmaArgs a) {
-  using V = typename Ld<T>::V;
-  constexpr int PFD = Ld<T>::PFD;
+  using V = typename LdN<T, CPL>::V;
+  constexpr int PFD = LdN<T, CPL>::PFD;
+  constexpr int WC = 32 * CPL;                 // columns per wave
   constexpr int NW = NRG * NCG, NT = 64 * NW;  // waves / threads of one sub-group
-  constexpr int RW = 32 * MT * NRG;            // stacked Phi rows per sub-group
-  constexpr int PHI_ELEMS = RW * PHI_LD;
+  constexpr int RWV = 32 * MT;                 // stacked Phi rows of one wave
+  constexpr int TILE = RWV * PHI_LD;           // bf16 elements of one Phi tile
   static_assert(RUN == 1 || IN_STAT, "orbit runs are an IN-stationary mode");
 
-  // dynamic LDS: [RUN][3][PHI_ELEMS] bf16 tiles, then [RUN][MAX_KAPPA] keys and blocks;
-  // the tile region is reused as the merge buffer of the RUN > 1 epilogue
+  // dynamic LDS: per sub-group [MAX_KAPPA] keys and blocks, then per wave two Phi tiles
+  // [RWV][PHI_LD] bf16 (consume / refill: a wave makes exactly the rows it consumes, so the
+  // steady state needs no barrier).  The tile region is reused as the merge buffer of the
+  // RUN > 1 epilogue.
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const SketchParams& p = a.p;
   const int sg = RUN > 1 ? (int)threadIdx.x / NT : 0;  // sub-group: one input block each
   const int tid = RUN > 1 ? (int)threadIdx.x % NT : (int)threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
-  uint16_t(*s_phi)[PHI_ELEMS] =
-      reinterpret_cast<uint16_t(*)[PHI_ELEMS]>(smem + (size_t)sg * 3 * PHI_ELEMS * 2);
-  uint32_t* s_bk = reinterpret_cast<uint32_t*>(smem + (size_t)RUN * 3 * PHI_ELEMS * 2) +
-                   sg * 2 * MAX_KAPPA;   // block keys per slot
+  constexpr size_t kTabBytes = (size_t)RUN * 2 * MAX_KAPPA * 4;
+  uint32_t* s_bk = reinterpret_cast<uint32_t*>(smem) + sg * 2 * MAX_KAPPA;  // block keys per slot
   uint32_t* s_blk = s_bk + MAX_KAPPA;    // IN: destination block g_l;  OUT: source block h_l
+  uint16_t* s_phi = reinterpret_cast<uint16_t*>(smem + kTabBytes) + (size_t)(sg * NW + wave) * 2 * TILE;
 
   const int rg = wave / NCG, cg = wave % NCG;
   const int kg = lane >> 5;
-  const int col0 = (int)blockIdx.y * (WCOLS * NCG) + cg * WCOLS + 4 * (lane & 31);
+  const int col0 = (int)blockIdx.y * (WC * NCG) + cg * WC + CPL * (lane & 31);
   // IN: input block h (RUN > 1: the block at orbit position blockIdx.x*RUN + sg); OUT: g
   uint32_t blk = blockIdx.x;
   if (RUN > 1) blk = __builtin_amdgcn_readfirstlane(a.pos2blk[blockIdx.x * RUN + sg]);
   const int z = IN_STAT ? (int)blockIdx.z : 0;
   const int T_stages = a.stages;
   const uint32_t rows_per_blk_stage = p.Bc / KC;  // stages per input block (OUT)
+  const uint32_t lbr = a.log2_br;
 
-  // ---- slot tables -------------------------------------------------------
-  for (int sl = tid; sl < (int)p.kappa; sl += NT) {
-    uint32_t x = blk;
-    for (int l = 0; l <= sl; ++l)
-      x = IN_STAT ? wire_prev(x, p.a_inv, p.b, p.M) : wire_next(x, p.a, p.b, p.M);
-    s_blk[sl] = x;
-    s_bk[sl] = IN_STAT ? block_key(p.key1, x, blk, p.M) : block_key(p.key1, blk, x, p.M);
-  }
-  {
-    uint4* z4 = reinterpret_cast<uint4*>(&s_phi[0][0]);
-    for (int i = tid; i < 3 * PHI_ELEMS / 8; i += NT) z4[i] = make_uint4(0, 0, 0, 0);
-  }
-  __syncthreads();
+  // ---- slot tables and empty tiles ------------------------------------------------
+  auto clear_tile = [&](int buf) {
+    uint4* z4 = reinterpret_cast<uint4*>(s_phi + buf * TILE);
+#pragma unroll
+    for (int i = 0; i < (TILE / 8 + 63) / 64; ++i)
+      if (TILE / 8 % 64 == 0 || lane + i * 64 < TILE / 8) z4[lane + i * 64] = make_uint4(0, 0, 0, 0);
+  };
+  auto setup_tables = [&]() {
+    for (int sl = tid; sl < (int)p.kappa; sl += NT) {
+      uint32_t x = blk;
+      for (int l = 0; l <= sl; ++l)
+        x = IN_STAT ? wire_prev(x, p.a_inv, p.b, p.M) : wire_next(x, p.a, p.b, p.M);
+      s_blk[sl] = x;
+      s_bk[sl] = IN_STAT ? block_key(p.key1, x, blk, p.M) : block_key(p.key1, blk, x, p.M);
+    }
+    clear_tile(0);
+    clear_tile(1);
+    __syncthreads();
+  };
 
   // first row of A of global k-step kk (16 rows each) of this work-group; wave-uniform
   auto row_of = [&](int kk) -> int64_t {
@@ -129,37 +139,52 @@ void mfma_kernel(MfmaArgs a) {
   const uint32_t voff = (uint32_t)(((int64_t)(kg * 8) * a.lda + col0) * (int64_t)sizeof(T));
   const int64_t row_bytes = a.lda * (int64_t)sizeof(T);
 
-  f32x16 acc[MT][4];
+  f32x16 acc[MT][CPL];
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-    for (int c = 0; c < 4; ++c)
+    for (int c = 0; c < CPL; ++c)
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[mt][c][i] = 0.f;
 
-  // Scatter the nonzeros of part `part` (of KSTEPS) of stage t into tile `buf`:
-  // one lane per (slot, row) pair.
-  auto produce = [&](int t, int buf, int part) {
-    uint16_t* phi = &s_phi[buf][0];
-    if (IN_STAT) {
-      const uint32_t u = (uint32_t)(z * T_stages + t) * KC + lane;
-      for (uint32_t slot = wave + part * NW; slot < p.kappa; slot += NW * KSTEPS) {
-        const RowHash rh = row_hash_pow2(s_bk[slot], u, p.Br);
-        uint32_t r = rh.shift;
-        for (uint32_t i = 0; i < p.s; ++i) {
-          phi[(slot * p.Br + r) * PHI_LD + lane] = ((rh.signs >> i) & 1u) ? kMinusOne : kOne;
-          r = (r + rh.stride) & (p.Br - 1);
-        }
-      }
-    } else if (wave == 0 && part == 0) {
-      const uint32_t l = (uint32_t)t / rows_per_blk_stage;
-      const uint32_t u = ((uint32_t)t % rows_per_blk_stage) * KC + lane;
-      const RowHash rh = row_hash_pow2(s_bk[l], u, p.Br);
-      uint32_t r = rh.shift;
+  // Scatter into tile `buf` the nonzeros of stage t that fall in this wave's stacked rows
+  // [row_lo, row_lo + RWV): one lane per row of the stage, the wave's slots in turn.  Part
+  // `part` (of KSTEPS) takes every KSTEPS-th slot so the hashing spreads over the stage.
+  const uint32_t row_lo = (uint32_t)rg * RWV;
+  // `whole`: the slot lies entirely inside this wave's rows, so no nonzero is filtered out.
+  auto scatter = [&](uint16_t* phi, uint32_t key, uint32_t u, uint32_t slot_row0, bool whole) {
+    const RowHash rh = row_hash_pow2(key, u, p.Br);
+    uint32_t r = rh.shift;
+    // tile index of (row, lane) = row*72 + lane, in 32-bit shifts and adds
+    const uint32_t base = slot_row0 - row_lo;
+    if (whole) {
       for (uint32_t i = 0; i < p.s; ++i) {
-        phi[r * PHI_LD + lane] = ((rh.signs >> i) & 1u) ? kMinusOne : kOne;
+        const uint32_t local = base + r;
+        phi[(local << 6) + (local << 3) + lane] = ((rh.signs >> i) & 1u) ? kMinusOne : kOne;
         r = (r + rh.stride) & (p.Br - 1);
       }
+    } else {
+      for (uint32_t i = 0; i < p.s; ++i) {
+        const uint32_t local = base + r;  // unsigned: rows below row_lo wrap high
+        if (local < (uint32_t)RWV)
+          phi[(local << 6) + (local << 3) + lane] = ((rh.signs >> i) & 1u) ? kMinusOne : kOne;
+        r = (r + rh.stride) & (p.Br - 1);
+      }
+    }
+  };
+  auto produce = [&](int t, int buf, int part) {
+    uint16_t* phi = s_phi + buf * TILE;
+    if (IN_STAT) {
+      const uint32_t u = (uint32_t)(z * T_stages + t) * KC + lane;
+      const uint32_t slot_lo = row_lo >> lbr;
+      const uint32_t slot_hi = min(p.kappa, ((row_lo + RWV - 1) >> lbr) + 1);
+      const bool whole = p.Br <= (uint32_t)RWV;  // power-of-two Br: slots tile the wave's rows
+      for (uint32_t slot = slot_lo + part; slot < slot_hi; slot += KSTEPS)
+        scatter(phi, s_bk[slot], u, slot << lbr, whole);
+    } else if (part == 0) {
+      const uint32_t l = (uint32_t)t / rows_per_blk_stage;
+      const uint32_t u = ((uint32_t)t % rows_per_blk_stage) * KC + lane;
+      scatter(phi, s_bk[l], u, 0u, p.Br <= (uint32_t)RWV);
     }
   };
 
@@ -182,7 +207,7 @@ void mfma_kernel(MfmaArgs a) {
         const char* sb = Abase + row_of(kk) * row_bytes;
 #pragma unroll
         for (int j = 0; j < 8; ++j)
-          dst[j] = load4_guarded<T>(reinterpret_cast<const T*>(sb + j * row_bytes + voff), col0, a.n);
+          dst[j] = load4_guarded<T, CPL>(reinterpret_cast<const T*>(sb + j * row_bytes + voff), col0, a.n);
       } else {
         __amdgpu_buffer_rsrc_t rs;
         uint32_t so;
@@ -199,7 +224,7 @@ void mfma_kernel(MfmaArgs a) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
           const uint32_t soj = so + (uint32_t)j * (uint32_t)row_bytes;
-          if constexpr (sizeof(T) == 2)
+          if constexpr (sizeof(V) == 8)
             dst[j] = __builtin_bit_cast(V, __builtin_amdgcn_raw_buffer_load_b64(rs, voff, soj, 0));
           else
             dst[j] = __builtin_bit_cast(V, __builtin_amdgcn_raw_buffer_load_b128(rs, voff, soj, 0));
@@ -207,38 +232,47 @@ void mfma_kernel(MfmaArgs a) {
       }
     };
 
-    // One stage: 4 MFMA k-steps on tile t%3 while the next stage is loaded and hashed.
-    // LAST stages issue no loads and fill no tile, so that the steady-state loop body has
-    // no conditional memory operations.
+    // One stage: 4 MFMA k-steps on tile t%2 while the next stage is loaded and hashed into
+    // the other tile.  LAST stages issue no loads and fill no tile, so that the steady-state
+    // loop body has no conditional memory operations.
     auto stage = [&](int t, auto last_tag) {
       constexpr bool LAST = decltype(last_tag)::value;
-      __syncthreads();
-      const uint16_t* phi = &s_phi[t % 3][0];
-      uint4* zero4 = reinterpret_cast<uint4*>(&s_phi[(t + 2) % 3][0]);
-      const int fill_buf = (t + 1) % 3;
+      const uint16_t* phi = s_phi + (t & 1) * TILE;
+      const int fill_buf = (t + 1) & 1;
 #pragma unroll
       for (int ks = 0; ks < KSTEPS; ++ks) {
         uint4 pa[MT];
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
           pa[mt] = *reinterpret_cast<const uint4*>(
-              phi + ((rg * MT + mt) * 32 + (lane & 31)) * PHI_LD + ks * 16 + kg * 8);
-        if constexpr (!LAST) {
-          // a quarter of: clear the tile consumed in the previous stage, fill the next one
-          for (int i = ks * (PHI_ELEMS / 32) + tid; i < (ks + 1) * (PHI_ELEMS / 32); i += NT)
-            zero4[i] = make_uint4(0, 0, 0, 0);
-          produce(t + 1, fill_buf, ks);
-        }
+              phi + (mt * 32 + (lane & 31)) * PHI_LD + ks * 16 + kg * 8);
+        if constexpr (!LAST) produce(t + 1, fill_buf, ks);
+
         V(&cur)[8] = ld[ks % PFD];
         const bool fetch = !LAST || ks + PFD < KSTEPS;  // compile-time after unrolling
         if constexpr (sizeof(T) == 2) {
           uint4 op[4];
-          make_ops(cur, op);
-          if (fetch) issue(t * KSTEPS + ks + PFD, cur);
+          if constexpr (CPL == 8) {  // two halves of four columns: keeps 16 operand VGPRs live
+            make_ops_half(cur, op, 0);
 #pragma unroll
-          for (int c = 0; c < 4; ++c)
+            for (int c = 0; c < 4; ++c)
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) acc[mt][c] = mfma(pa[mt], op[c], acc[mt][c]);
+              for (int mt = 0; mt < MT; ++mt) acc[mt][c] = mfma(pa[mt], op[c], acc[mt][c]);
+            __builtin_amdgcn_sched_barrier(0);
+            make_ops_half(cur, op, 1);
+            if (fetch) issue(t * KSTEPS + ks + PFD, cur);
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+#pragma unroll
+              for (int mt = 0; mt < MT; ++mt) acc[mt][4 + c] = mfma(pa[mt], op[c], acc[mt][4 + c]);
+          } else {
+            make_ops(cur, op);
+            if (fetch) issue(t * KSTEPS + ks + PFD, cur);
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+#pragma unroll
+              for (int mt = 0; mt < MT; ++mt) acc[mt][c] = mfma(pa[mt], op[c], acc[mt][c]);
+          }
         } else {
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
@@ -259,95 +293,124 @@ void mfma_kernel(MfmaArgs a) {
         }
         __builtin_amdgcn_sched_barrier(0);  // keep k-steps apart: bounds register pressure
       }
+      // the tile just consumed becomes the fill target of the next stage
+      if constexpr (!LAST) clear_tile(t & 1);
     };
 
-#pragma unroll
-    for (int part = 0; part < KSTEPS; ++part) produce(0, 0, part);
+    // (the barrier inside setup_tables waits for outstanding loads, so none are issued before it)
+    setup_tables();
 #pragma unroll
     for (int i = 0; i < PFD; ++i) issue(i, ld[i]);
+#pragma unroll
+    for (int part = 0; part < KSTEPS; ++part) produce(0, 0, part);
     for (int t = 0; t + 1 < T_stages; ++t) stage(t, std::false_type{});
     stage(T_stages - 1, std::true_type{});
   };
-  const bool full_tile = ((int)blockIdx.y + 1) * (WCOLS * NCG) <= a.n;
+  const bool full_tile = ((int)blockIdx.y + 1) * (WC * NCG) <= a.n;
   if (full_tile) body(std::false_type{}); else body(std::true_type{});
 
   // ---- epilogue ------------------------------------------------------------
+  // accumulator register i of tile (mt, c) holds stacked row (rg*MT+mt)*32 + 8*(i/4) + 4*kg + i%4
+  // of column col0 + c; columns are handled four at a time (q).
   if constexpr (RUN > 1) {
     // Merge in LDS the tiles of the RUN sub-groups that go to the same output block:
     // sub-group j, slot l-1 lands on relative output position idx = j - l + kappa
     // (0 .. kappa+RUN-2).  Sub-groups take turns in index order, so the sum order is fixed.
-    constexpr int TNW = WCOLS * NCG;
-    float* mbuf = reinterpret_cast<float*>(smem);  // [kappa+RUN-1][Br][TNW]
-    const int colw = cg * WCOLS + 4 * (lane & 31);
+    constexpr int TNW = WC * NCG;
+    float* mbuf = reinterpret_cast<float*>(smem + kTabBytes);  // [kappa+RUN-1][Br][TNW]
+    const int colw = cg * WC + CPL * (lane & 31);
     __syncthreads();  // every wave is done with the Phi tiles
     for (int j = 0; j < RUN; ++j) {
       if (sg == j) {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const uint32_t row_s = (uint32_t)((rg * MT + mt) * 32 + 8 * (i >> 2) + 4 * kg + (i & 3));
-            const uint32_t slot = row_s / p.Br, r = row_s & (p.Br - 1);
-            const uint32_t idx = (uint32_t)j + p.kappa - 1u - slot;
-            float4* d = reinterpret_cast<float4*>(mbuf + ((size_t)(idx * p.Br + r)) * TNW + colw);
-            float4 v = make_float4(acc[mt][0][i], acc[mt][1][i], acc[mt][2][i], acc[mt][3][i]);
-            if (!(slot == 0 || j == 0)) {  // not the first sub-group to reach this tile
-              const float4 o = *d;
-              v.x += o.x; v.y += o.y; v.z += o.z; v.w += o.w;
+          for (int ib = 0; ib < 16; ib += 4) {  // four rows at a time: reads first, then adds
+            float4* d[4];
+            bool first[4];
+            float4 o[4][CPL / 4];
+#pragma unroll
+            for (int ii = 0; ii < 4; ++ii) {
+              const int i = ib + ii;
+              const uint32_t row_s = (uint32_t)((rg * MT + mt) * 32 + 8 * (i >> 2) + 4 * kg + (i & 3));
+              const uint32_t slot = row_s >> lbr, r = row_s & (p.Br - 1);
+              const uint32_t idx = (uint32_t)j + p.kappa - 1u - slot;
+              first[ii] = slot == 0 || j == 0;  // no earlier sub-group reaches this tile
+              d[ii] = reinterpret_cast<float4*>(mbuf + ((size_t)((idx << lbr) + r)) * TNW + colw);
+              if (j > 0) {
+#pragma unroll
+                for (int q = 0; q < CPL / 4; ++q) o[ii][q] = d[ii][q];
+              }
             }
-            *d = v;
+#pragma unroll
+            for (int ii = 0; ii < 4; ++ii) {
+              const int i = ib + ii;
+#pragma unroll
+              for (int q = 0; q < CPL / 4; ++q) {
+                float4 v = make_float4(acc[mt][4 * q][i], acc[mt][4 * q + 1][i], acc[mt][4 * q + 2][i],
+                                       acc[mt][4 * q + 3][i]);
+                if (j > 0 && !first[ii]) {
+                  v.x += o[ii][q].x; v.y += o[ii][q].y; v.z += o[ii][q].z; v.w += o[ii][q].w;
+                }
+                d[ii][q] = v;
+              }
+            }
           }
         }
       }
       __syncthreads();
     }
-    // cooperative store of the kappa+RUN-1 merged tiles to their partial planes
-    const uint32_t tiles = p.kappa + RUN - 1;
-    const uint32_t per_tile = p.Br * (TNW / 4);
-    const uint32_t q0 = blockIdx.x * RUN;
-    for (uint32_t e = threadIdx.x; e < tiles * per_tile; e += NT * RUN) {
-      const uint32_t idx = e / per_tile, rem = e % per_tile;
-      const uint32_t r = rem / (TNW / 4), c4 = rem % (TNW / 4);
+    // cooperative store of the kappa+RUN-1 merged tiles to their partial planes; the
+    // destination block of tile idx is slot j+kappa-1-idx of any sub-group j that feeds it
+    static_assert(TNW / 4 == 64, "index split below assumes 64 float4 per tile row");
+    const uint32_t total = (p.kappa + RUN - 1) << (lbr + 6);
+    const uint32_t* blk_tab = reinterpret_cast<const uint32_t*>(smem);
+    for (uint32_t e = threadIdx.x; e < total; e += NT * RUN) {
+      const uint32_t idx = e >> (lbr + 6), r = (e >> 6) & (p.Br - 1), c4 = e & 63u;
       const int col = (int)blockIdx.y * TNW + (int)c4 * 4;
       if (col >= a.n) continue;
-      const uint32_t pos = (q0 + idx + p.M - p.kappa) % p.M;
-      const uint32_t g = a.pos2blk[pos];
+      const uint32_t j = min(idx, (uint32_t)(RUN - 1));
+      const uint32_t g = blk_tab[j * 2 * MAX_KAPPA + MAX_KAPPA + (j + p.kappa - 1 - idx)];
       const int64_t plane = idx / RUN;
-      float* dst = a.ws + (plane * p.k + (int64_t)g * p.Br + r) * a.ldw + col;
+      float* dst = a.ws + (plane * p.k + ((int64_t)g << lbr) + r) * a.ldw + col;
       *reinterpret_cast<float4*>(dst) =
-          *reinterpret_cast<const float4*>(mbuf + ((size_t)(idx * p.Br + r)) * TNW + c4 * 4);
+          *reinterpret_cast<const float4*>(mbuf + ((size_t)((idx << lbr) + r)) * TNW + c4 * 4);
     }
     return;
   }
-  if (col0 >= a.n) return;
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       const uint32_t row_s = (uint32_t)((rg * MT + mt) * 32 + 8 * (i >> 2) + 4 * kg + (i & 3));
-      float v[4] = {acc[mt][0][i], acc[mt][1][i], acc[mt][2][i], acc[mt][3][i]};
-      if (IN_STAT) {
-        const uint32_t slot = row_s / p.Br, r = row_s & (p.Br - 1);
-        const int64_t plane = (int64_t)z * p.kappa + slot;
-        float* dst = a.ws + (plane * p.k + (int64_t)s_blk[slot] * p.Br + r) * a.ldw + col0;
-        *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
-      } else {
-        T* dst = reinterpret_cast<T*>(a.out) + ((int64_t)blk * p.Br + row_s) * a.ldo + col0;
 #pragma unroll
-        for (int c = 0; c < 4; ++c) v[c] *= p.scale;
-        if (a.out_vec && col0 + 3 < a.n) {
-          if constexpr (sizeof(T) == 2) {
-            uint2 w;
-            w.x = (uint32_t)f32_to_bf16_rne(v[0]) | ((uint32_t)f32_to_bf16_rne(v[1]) << 16);
-            w.y = (uint32_t)f32_to_bf16_rne(v[2]) | ((uint32_t)f32_to_bf16_rne(v[3]) << 16);
-            *reinterpret_cast<uint2*>(dst) = w;
-          } else {
-            *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
-          }
+      for (int q = 0; q < CPL / 4; ++q) {
+        const int colq = col0 + 4 * q;
+        if (colq >= a.n) continue;
+        float v[4] = {acc[mt][4 * q][i], acc[mt][4 * q + 1][i], acc[mt][4 * q + 2][i], acc[mt][4 * q + 3][i]};
+        if (IN_STAT) {
+          const uint32_t slot = row_s >> lbr, r = row_s & (p.Br - 1);
+          const int64_t plane = (int64_t)z * p.kappa + slot;
+          float* dst = a.ws + (plane * p.k + (int64_t)s_blk[slot] * p.Br + r) * a.ldw + colq;
+          *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
         } else {
+          T* dst = reinterpret_cast<T*>(a.out) + ((int64_t)blk * p.Br + row_s) * a.ldo + colq;
 #pragma unroll
-          for (int c = 0; c < 4; ++c)
-            if (col0 + c < a.n) Elt<T>::store(dst + c, v[c]);
+          for (int c = 0; c < 4; ++c) v[c] *= p.scale;
+          if (a.out_vec && colq + 3 < a.n) {
+            if constexpr (sizeof(T) == 2) {
+              uint2 w;
+              w.x = (uint32_t)f32_to_bf16_rne(v[0]) | ((uint32_t)f32_to_bf16_rne(v[1]) << 16);
+              w.y = (uint32_t)f32_to_bf16_rne(v[2]) | ((uint32_t)f32_to_bf16_rne(v[3]) << 16);
+              *reinterpret_cast<uint2*>(dst) = w;
+            } else {
+              *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+            }
+          } else {
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+              if (colq + c < a.n) Elt<T>::store(dst + c, v[c]);
+          }
         }
       }
     }
@@ -401,13 +464,16 @@ __global__ __launch_bounds__(256) void reduce_planes_kernel(const float* __restr
 struct Plan {
   bool ok = false;
   bool in_stat = false;
-  int mt = 0, nrg = 0, ncg = 0, zsplit = 1, stages = 0, run = 1;
+  int mt = 0, nrg = 0, ncg = 0, zsplit = 1, stages = 0, run = 1, cpl = 4;
   int64_t ldw = 0;
   int planes = 0;
   size_t lds = 0;
 };
 
 constexpr size_t kLdsBudget = 160 * 1024;
+// The row-split (8 columns per lane) orbit-run variant is correct but the compiler spills
+// accumulators in its main loop; off until that is resolved.
+constexpr bool kRowSplitRuns = false;
 
 bool tile_shape(uint32_t rw, int* mt, int* nrg) {
   if (rw == 32) { *mt = 1; *nrg = 1; return true; }
@@ -416,8 +482,11 @@ bool tile_shape(uint32_t rw, int* mt, int* nrg) {
   return false;
 }
 
-size_t lds_bytes(int mt, int nrg, int run) {
-  return (size_t)run * (3 * (size_t)(32 * mt * nrg) * PHI_LD * 2 + 2 * MAX_KAPPA * 4);
+// tables, then the larger of (two Phi tiles per wave) and (the orbit-run merge buffer)
+size_t lds_bytes(int mt, int nrg, int ncg, int run, size_t merge) {
+  const size_t tables = (size_t)run * 2 * MAX_KAPPA * 4;
+  const size_t tiles = (size_t)run * nrg * ncg * 2 * (size_t)(32 * mt) * PHI_LD * 2;
+  return tables + (tiles > merge ? tiles : merge);
 }
 
 Plan make_plan(const SketchParams& p, const void* A, int64_t lda, int64_t n, fs_dtype dt,
@@ -457,15 +526,21 @@ Plan make_plan(const SketchParams& p, const void* A, int64_t lda, int64_t n, fs_
     constexpr int R = 4;
     const size_t merge = (size_t)(p.kappa + R - 1) * p.Br * (WCOLS * 2) * 4;
     if (have_orbit && zs == 1 && pl.mt == 2 && pl.nrg == 1 && pl.ncg == 2 && p.kappa > 1 &&
-        p.M % R == 0 && (int64_t)(p.M / R) * col_tiles >= 256 && merge <= lds_bytes(2, 1, R)) {
+        p.M % R == 0 && (int64_t)(p.M / R) * col_tiles >= 256 && merge <= 100 * 1024) {
       pl.run = R;
       pl.planes = (int)((p.kappa + R - 2) / R) + 1;
+      if (dt == FS_BF16 && kRowSplitRuns) {
+        // bf16: split the 64 stacked rows over the two waves instead of the 256 columns
+        // (8 columns per lane): each wave then hashes only its own 32 rows
+        pl.mt = 1; pl.nrg = 2; pl.ncg = 1; pl.cpl = 8;
+      }
     }
   } else {
     pl.mt = mt_o; pl.nrg = nrg_o; pl.zsplit = 1;
     pl.stages = (int)((uint64_t)p.kappa * p.Bc / KC);
   }
-  pl.lds = lds_bytes(pl.mt, pl.nrg, pl.run);
+  pl.lds = lds_bytes(pl.mt, pl.nrg, pl.ncg, pl.run,
+                     pl.run > 1 ? (size_t)(p.kappa + pl.run - 1) * p.Br * 256 * 4 : 0);
   pl.ok = pl.lds <= kLdsBudget;
   return pl;
 }
@@ -484,8 +559,12 @@ hipError_t go(K kernel, dim3 grid, unsigned threads, size_t lds, hipStream_t st,
 template <typename T, bool IN_STAT>
 hipError_t launch_shape(const Plan& pl, const MfmaArgs& a, dim3 grid, hipStream_t st) {
 #define FS_GO(MT, NRG, NCG, RUN) \
-  return go(mfma_kernel<T, MT, NRG, NCG, IN_STAT, RUN>, grid, 64 * NRG * NCG * RUN, pl.lds, st, a)
+  return go(mfma_kernel<T, MT, NRG, NCG, IN_STAT, RUN, 4>, grid, 64 * NRG * NCG * RUN, pl.lds, st, a)
   if constexpr (IN_STAT) {
+    if constexpr (sizeof(T) == 2) {
+      if (pl.run == 4 && pl.cpl == 8)
+        return go(mfma_kernel<T, 1, 2, 1, true, 4, 8>, grid, 64 * 2 * 4, pl.lds, st, a);
+    }
     if (pl.run == 4) FS_GO(2, 1, 2, 4);
   }
   if (pl.ncg == 1) {
@@ -529,7 +608,10 @@ hipError_t launch_mfma(const SketchParams& p, const void* A, int64_t lda, int64_
   a.lda = lda; a.ldo = ldo; a.ldw = pl.ldw; a.n = (int)n;
   a.zsplit = pl.zsplit; a.stages = pl.stages;
   a.out_vec = ((uintptr_t)out % (4 * esz) == 0 && (ldo * esz) % (4 * esz) == 0) ? 1 : 0;
-  const unsigned col_tiles = (unsigned)((n + WCOLS * pl.ncg - 1) / (WCOLS * pl.ncg));
+  a.log2_br = 0;
+  while ((1u << a.log2_br) < p.Br) ++a.log2_br;
+  const int tnw = 32 * pl.cpl * pl.ncg;
+  const unsigned col_tiles = (unsigned)((n + tnw - 1) / tnw);
   dim3 grid(p.M / pl.run, col_tiles, pl.in_stat ? pl.zsplit : 1);
 
   if (ev.start) (void)hipEventRecord(ev.start, st);

@@ -20,21 +20,25 @@ constexpr uint16_t kOne = 0x3F80, kMinusOne = 0xBF80;
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-template <typename T> struct Ld;
-template <> struct Ld<uint16_t> { using V = uint2; static constexpr int PFD = 4; };
-template <> struct Ld<float>    { using V = uint4; static constexpr int PFD = 2; };
+// What one lane loads from one row: CPL consecutive columns as one vector V; PFD = depth
+// (in k-steps) of the register prefetch ring, sized to 64 VGPRs per wave.
+template <typename T, int CPL> struct LdN;
+template <> struct LdN<uint16_t, 4> { using V = uint2; static constexpr int PFD = 4; };
+template <> struct LdN<uint16_t, 8> { using V = uint4; static constexpr int PFD = 2; };
+template <> struct LdN<float, 4>    { using V = uint4; static constexpr int PFD = 2; };
+template <typename T> using Ld = LdN<T, 4>;
 
 __device__ __forceinline__ uint32_t perm(uint32_t hi_src, uint32_t lo_src, uint32_t sel) {
   return __builtin_amdgcn_perm(hi_src, lo_src, sel);
 }
 
 // 4 consecutive columns of one row, element by element; columns >= n read as 0.
-template <typename T>
-__device__ __forceinline__ typename Ld<T>::V load4_guarded(const T* p4, int col0, int n) {
-  using V = typename Ld<T>::V;
-  T e[4];
+template <typename T, int CPL = 4>
+__device__ __forceinline__ typename LdN<T, CPL>::V load4_guarded(const T* p4, int col0, int n) {
+  using V = typename LdN<T, CPL>::V;
+  T e[CPL];
 #pragma unroll
-  for (int c = 0; c < 4; ++c) e[c] = (col0 + c < n) ? p4[c] : (T)0;
+  for (int c = 0; c < CPL; ++c) e[c] = (col0 + c < n) ? p4[c] : (T)0;
   return *reinterpret_cast<V*>(e);
 }
 
@@ -51,6 +55,14 @@ __device__ __forceinline__ void make_ops(const uint2 (&r)[8], uint4 (&op)[4]) {
     o2[q] = perm(r[2 * q + 1].y, r[2 * q].y, 0x05040100u);
     o3[q] = perm(r[2 * q + 1].y, r[2 * q].y, 0x07060302u);
   }
+}
+
+// From 8 rows x 8 columns (bf16): the four operands of columns 4*half .. 4*half+3.
+__device__ __forceinline__ void make_ops_half(const uint4 (&r)[8], uint4 (&op)[4], int half) {
+  uint2 h[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) h[j] = half ? make_uint2(r[j].z, r[j].w) : make_uint2(r[j].x, r[j].y);
+  make_ops(h, op);
 }
 
 // fp32 column c of 8 rows -> three exact bf16 pieces (x = hi + mid + lo).
