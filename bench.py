@@ -31,8 +31,8 @@ MEASURED_TRAFFIC = {("grad", "mfma"): (2_097_744 + 22_528) * 1024}
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="grad", choices=["tiny", "mid", "tall", "wide", "grad"])
     ap.add_argument("--variant", default="auto", choices=["auto", "generic", "mfma"])
     ap.add_argument("--no-extra", action="store_true", help="skip the side measurements")

@@ -158,10 +158,18 @@ void mfma_kernel(MfmaArgs a) {
     // tile index of (row, lane) = row*72 + lane, in 32-bit shifts and adds
     const uint32_t base = slot_row0 - row_lo;
     if (whole) {
-      for (uint32_t i = 0; i < p.s; ++i) {
-        const uint32_t local = base + r;
-        phi[(local << 6) + (local << 3) + lane] = ((rh.signs >> i) & 1u) ? kMinusOne : kOne;
+      // s >= 1; the first two updates are peeled (s = 2 and 4 are the common cases)
+      uint32_t local = base + r;
+      phi[(local << 6) + (local << 3) + lane] = (rh.signs & 1u) ? kMinusOne : kOne;
+      if (p.s >= 2) {
         r = (r + rh.stride) & (p.Br - 1);
+        local = base + r;
+        phi[(local << 6) + (local << 3) + lane] = (rh.signs & 2u) ? kMinusOne : kOne;
+        for (uint32_t i = 2; i < p.s; ++i) {
+          r = (r + rh.stride) & (p.Br - 1);
+          local = base + r;
+          phi[(local << 6) + (local << 3) + lane] = ((rh.signs >> i) & 1u) ? kMinusOne : kOne;
+        }
       }
     } else {
       for (uint32_t i = 0; i < p.s; ++i) {
