@@ -308,3 +308,61 @@ def test_full_config_grad_chunked_sampled():
     torch.cuda.synchronize()
     print("  applied; oracle on sampled columns", flush=True)
     _sampled_parity(cfg, A, out, ncols=6)
+
+
+# ------------------------------------------------ boundary behaviour ------
+def test_caller_workspace_and_too_small_workspace():
+    params, n = (65536, 8192, 64, 8, 8, 2), 256
+    A = torch.randn((params[0], n), device=DEV).to(torch.bfloat16)
+    sk = B.Sketch(*params, seed=1)
+    need = sk.workspace_bytes(n, torch.bfloat16)
+    assert need > 0
+    ref = sk.apply(A)                       # internal, lazily grown workspace
+    assert sk.info().workspace_bytes >= need
+    ws = torch.empty(need + 256, dtype=torch.uint8, device=DEV)
+    off = (-ws.data_ptr()) % 256
+    sk.set_workspace(ws[off:off + need])
+    got = sk.apply(A)                       # caller-owned workspace, no allocation
+    torch.cuda.synchronize()
+    assert torch.equal(ref, got)
+    sk.set_workspace(ws[off:off + 256])     # too small: must fail, not overrun
+    with pytest.raises(B.FlashSketchError) as e:
+        sk.apply(A)
+    assert e.value.status == 3
+    sk.set_workspace(None)
+    assert torch.equal(sk.apply(A), ref)
+
+
+def test_apply_on_a_side_stream_and_profile_brackets():
+    params, n = (4096, 256, 512, 32, 2, 4), 512
+    A = torch.randn((params[0], n), device=DEV)
+    sk = B.Sketch(*params, seed=0)
+    ref = sk.apply(A)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    out = torch.empty_like(ref)
+    sk.profile_begin(3)
+    with torch.cuda.stream(side):
+        for _ in range(5):                  # two more applies than brackets: extra ones run unbracketed
+            sk.apply(A, out, stream=side)
+    side.synchronize()
+    ms = sk.profile_end()
+    assert len(ms) == 3 and all(0.0 < t < 50.0 for t in ms)
+    assert torch.equal(out, ref)
+    with pytest.raises(B.FlashSketchError):
+        sk.profile_end()                    # not profiling any more
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+def test_variants_agree_with_each_other(dtype):
+    """Generic and MFMA paths implement the same S: they agree to accumulation rounding."""
+    params, n = (16384, 256, 2048, 32, 4, 4), 384
+    A = torch.randn((params[0], n), device=DEV).to(dtype)
+    outs = []
+    for v in (B.VARIANT_GENERIC, B.VARIANT_MFMA, B.VARIANT_AUTO):
+        sk = make_sketch(params, 9, v)
+        outs.append(host64(apply_or_skip(sk, A)))
+    torch.cuda.synchronize()
+    tol = 1e-5 if dtype == torch.float32 else 8e-3
+    assert O.rel_fro_err(outs[1], outs[0]) < tol
+    assert np.array_equal(outs[1], outs[2])  # AUTO picked the MFMA path
