@@ -93,10 +93,25 @@ void mfma_kernel(MfmaArgs a) {
 
   const int rg = wave / NCG, cg = wave % NCG;
   const int kg = lane >> 5;
-  const int col0 = (int)blockIdx.y * (WC * NCG) + cg * WC + CPL * (lane & 31);
+  // Which (block, column tile) this work-group takes.  OUT with an orbit table: work-groups
+  // are renumbered so that the ones an XCD runs side by side (the hardware deals linear ids
+  // round-robin over the 8 XCDs) are consecutive orbit positions of one column tile; together
+  // with the phase order below they then read the same input block at the same time, and the
+  // kappa re-reads of A are served by that XCD's L2 instead of the fabric.
+  uint32_t bx = blockIdx.x, jt = blockIdx.y, opos = 0;
+  const bool remap = !IN_STAT && a.pos2blk != nullptr;
+  if (remap) {
+    const uint32_t total = gridDim.x * gridDim.y;
+    uint32_t id = blockIdx.y * gridDim.x + blockIdx.x;
+    if (total % 8 == 0) id = (id % 8) * (total / 8) + id / 8;
+    opos = id % gridDim.x;
+    jt = id / gridDim.x;
+  }
+  const int col0 = (int)jt * (WC * NCG) + cg * WC + CPL * (lane & 31);
   // IN: input block h (RUN > 1: the block at orbit position blockIdx.x*RUN + sg); OUT: g
-  uint32_t blk = blockIdx.x;
+  uint32_t blk = bx;
   if (RUN > 1) blk = __builtin_amdgcn_readfirstlane(a.pos2blk[blockIdx.x * RUN + sg]);
+  if (remap) blk = __builtin_amdgcn_readfirstlane(a.pos2blk[opos]);
   const int z = IN_STAT ? (int)blockIdx.z : 0;
   const int T_stages = a.stages;
   const uint32_t rows_per_blk_stage = p.Bc / KC;  // stages per input block (OUT)
@@ -112,8 +127,15 @@ void mfma_kernel(MfmaArgs a) {
   auto setup_tables = [&]() {
     for (int sl = tid; sl < (int)p.kappa; sl += NT) {
       uint32_t x = blk;
-      for (int l = 0; l <= sl; ++l)
-        x = IN_STAT ? wire_prev(x, p.a_inv, p.b, p.M) : wire_next(x, p.a, p.b, p.M);
+      if (remap) {
+        // phase sl handles the neighbour whose (unwrapped) orbit position is sl mod kappa:
+        // every work-group of a column tile is then on the same input block in the same phase
+        const uint32_t l = (sl + p.kappa - (opos + 1) % p.kappa) % p.kappa;  // 0 .. kappa-1
+        x = a.pos2blk[(opos + 1 + l) % p.M];
+      } else {
+        for (int l = 0; l <= sl; ++l)
+          x = IN_STAT ? wire_prev(x, p.a_inv, p.b, p.M) : wire_next(x, p.a, p.b, p.M);
+      }
       s_blk[sl] = x;
       s_bk[sl] = IN_STAT ? block_key(p.key1, x, blk, p.M) : block_key(p.key1, blk, x, p.M);
     }
@@ -314,7 +336,7 @@ void mfma_kernel(MfmaArgs a) {
     for (int t = 0; t + 1 < T_stages; ++t) stage(t, std::false_type{});
     stage(T_stages - 1, std::true_type{});
   };
-  const bool full_tile = ((int)blockIdx.y + 1) * (WC * NCG) <= a.n;
+  const bool full_tile = ((int)jt + 1) * (WC * NCG) <= a.n;
   if (full_tile) body(std::false_type{}); else body(std::true_type{});
 
   // ---- epilogue ------------------------------------------------------------
