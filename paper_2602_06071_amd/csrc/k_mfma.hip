@@ -282,27 +282,12 @@ void mfma_kernel(MfmaArgs a) {
         const bool fetch = !LAST || ks + PFD < KSTEPS;  // compile-time after unrolling
         if constexpr (sizeof(T) == 2) {
           uint4 op[4];
-          if constexpr (CPL == 8) {  // two halves of four columns: keeps 16 operand VGPRs live
-            make_ops_half(cur, op, 0);
+          make_ops(cur, op);
+          if (fetch) issue(t * KSTEPS + ks + PFD, cur);
 #pragma unroll
-            for (int c = 0; c < 4; ++c)
+          for (int c = 0; c < 4; ++c)
 #pragma unroll
-              for (int mt = 0; mt < MT; ++mt) acc[mt][c] = mfma(pa[mt], op[c], acc[mt][c]);
-            __builtin_amdgcn_sched_barrier(0);
-            make_ops_half(cur, op, 1);
-            if (fetch) issue(t * KSTEPS + ks + PFD, cur);
-#pragma unroll
-            for (int c = 0; c < 4; ++c)
-#pragma unroll
-              for (int mt = 0; mt < MT; ++mt) acc[mt][4 + c] = mfma(pa[mt], op[c], acc[mt][4 + c]);
-          } else {
-            make_ops(cur, op);
-            if (fetch) issue(t * KSTEPS + ks + PFD, cur);
-#pragma unroll
-            for (int c = 0; c < 4; ++c)
-#pragma unroll
-              for (int mt = 0; mt < MT; ++mt) acc[mt][c] = mfma(pa[mt], op[c], acc[mt][c]);
-          }
+            for (int mt = 0; mt < MT; ++mt) acc[mt][c] = mfma(pa[mt], op[c], acc[mt][c]);
         } else {
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
@@ -501,9 +486,6 @@ struct Plan {
 };
 
 constexpr size_t kLdsBudget = 160 * 1024;
-// The row-split (8 columns per lane) orbit-run variant is correct but the compiler spills
-// accumulators in its main loop; off until that is resolved.
-constexpr bool kRowSplitRuns = false;
 
 bool tile_shape(uint32_t rw, int* mt, int* nrg) {
   if (rw == 32) { *mt = 1; *nrg = 1; return true; }
@@ -559,11 +541,6 @@ Plan make_plan(const SketchParams& p, const void* A, int64_t lda, int64_t n, fs_
         p.M % R == 0 && (int64_t)(p.M / R) * col_tiles >= 256 && merge <= 100 * 1024) {
       pl.run = R;
       pl.planes = (int)((p.kappa + R - 2) / R) + 1;
-      if (dt == FS_BF16 && kRowSplitRuns) {
-        // bf16: split the 64 stacked rows over the two waves instead of the 256 columns
-        // (8 columns per lane): each wave then hashes only its own 32 rows
-        pl.mt = 1; pl.nrg = 2; pl.ncg = 1; pl.cpl = 8;
-      }
     }
   } else {
     pl.mt = mt_o; pl.nrg = nrg_o; pl.zsplit = 1;
@@ -591,10 +568,6 @@ hipError_t launch_shape(const Plan& pl, const MfmaArgs& a, dim3 grid, hipStream_
 #define FS_GO(MT, NRG, NCG, RUN) \
   return go(mfma_kernel<T, MT, NRG, NCG, IN_STAT, RUN, 4>, grid, 64 * NRG * NCG * RUN, pl.lds, st, a)
   if constexpr (IN_STAT) {
-    if constexpr (sizeof(T) == 2) {
-      if (pl.run == 4 && pl.cpl == 8)
-        return go(mfma_kernel<T, 1, 2, 1, true, 4, 8>, grid, 64 * 2 * 4, pl.lds, st, a);
-    }
     if (pl.run == 4) FS_GO(2, 1, 2, 4);
   }
   if (pl.ncg == 1) {

@@ -24,7 +24,6 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 // (in k-steps) of the register prefetch ring, sized to 64 VGPRs per wave.
 template <typename T, int CPL> struct LdN;
 template <> struct LdN<uint16_t, 4> { using V = uint2; static constexpr int PFD = 4; };
-template <> struct LdN<uint16_t, 8> { using V = uint4; static constexpr int PFD = 2; };
 template <> struct LdN<float, 4>    { using V = uint4; static constexpr int PFD = 2; };
 template <typename T> using Ld = LdN<T, 4>;
 
@@ -55,14 +54,6 @@ __device__ __forceinline__ void make_ops(const uint2 (&r)[8], uint4 (&op)[4]) {
     o2[q] = perm(r[2 * q + 1].y, r[2 * q].y, 0x05040100u);
     o3[q] = perm(r[2 * q + 1].y, r[2 * q].y, 0x07060302u);
   }
-}
-
-// From 8 rows x 8 columns (bf16): the four operands of columns 4*half .. 4*half+3.
-__device__ __forceinline__ void make_ops_half(const uint4 (&r)[8], uint4 (&op)[4], int half) {
-  uint2 h[8];
-#pragma unroll
-  for (int j = 0; j < 8; ++j) h[j] = half ? make_uint2(r[j].z, r[j].w) : make_uint2(r[j].x, r[j].y);
-  make_ops(h, op);
 }
 
 // fp32 column c of 8 rows -> three exact bf16 pieces (x = hi + mid + lo).
