@@ -60,7 +60,7 @@ struct MfmaArgs {
   const uint32_t* pos2blk;  // orbit order of the blocks (RUN > 1 only)
   int64_t lda, ldo, ldw;
   int n;
-  int zsplit;       // IN: row splits of an input block
+  int zsplit;       // IN: row splits of an input block; OUT: splits of the kappa*Bc rows
   int stages;       // stages per work-group
   int out_vec;      // out rows allow 4-column vector stores
   uint32_t log2_br;
@@ -112,7 +112,7 @@ void mfma_kernel(MfmaArgs a) {
   uint32_t blk = bx;
   if (RUN > 1) blk = __builtin_amdgcn_readfirstlane(a.pos2blk[blockIdx.x * RUN + sg]);
   if (remap) blk = __builtin_amdgcn_readfirstlane(a.pos2blk[opos]);
-  const int z = IN_STAT ? (int)blockIdx.z : 0;
+  const int z = (int)blockIdx.z;
   const int T_stages = a.stages;
   const uint32_t rows_per_blk_stage = p.Bc / KC;  // stages per input block (OUT)
   const uint32_t lbr = a.log2_br;
@@ -150,7 +150,8 @@ void mfma_kernel(MfmaArgs a) {
       return (int64_t)blk * p.Bc + (int64_t)z * T_stages * KC + (int64_t)kk * 16;
     } else {
       const uint32_t per_blk = p.Bc / 16;
-      const uint32_t l = (uint32_t)kk / per_blk, kr = (uint32_t)kk % per_blk;
+      const uint32_t kg_ = (uint32_t)(z * T_stages * KSTEPS + kk);  // k-step among all kappa blocks
+      const uint32_t l = kg_ / per_blk, kr = kg_ % per_blk;
       const uint32_t hb = __builtin_amdgcn_readfirstlane(s_blk[l]);
       return (int64_t)hb * p.Bc + (int64_t)kr * 16;
     }
@@ -212,8 +213,9 @@ void mfma_kernel(MfmaArgs a) {
       for (uint32_t slot = slot_lo + part; slot < slot_hi; slot += KSTEPS)
         scatter(phi, s_bk[slot], u, slot << lbr, whole);
     } else if (part == 0) {
-      const uint32_t l = (uint32_t)t / rows_per_blk_stage;
-      const uint32_t u = ((uint32_t)t % rows_per_blk_stage) * KC + lane;
+      const uint32_t tg = (uint32_t)(z * T_stages + t);  // stage among all kappa blocks
+      const uint32_t l = tg / rows_per_blk_stage;
+      const uint32_t u = (tg % rows_per_blk_stage) * KC + lane;
       scatter(phi, s_bk[l], u, 0u, p.Br <= (uint32_t)RWV);
     }
   };
@@ -246,7 +248,8 @@ void mfma_kernel(MfmaArgs a) {
           so = (uint32_t)kk * 16u * (uint32_t)row_bytes;
         } else {
           const uint32_t per_blk = p.Bc / 16;
-          const uint32_t l = (uint32_t)kk / per_blk, kr = (uint32_t)kk % per_blk;
+          const uint32_t kg_ = (uint32_t)(z * T_stages * KSTEPS + kk);
+          const uint32_t l = kg_ / per_blk, kr = kg_ % per_blk;
           const uint32_t hb = __builtin_amdgcn_readfirstlane(s_blk[l]);
           rs = make_rsrc((int64_t)hb * p.Bc, p.Bc);
           so = kr * 16u * (uint32_t)row_bytes;
@@ -408,6 +411,9 @@ void mfma_kernel(MfmaArgs a) {
           const int64_t plane = (int64_t)z * p.kappa + slot;
           float* dst = a.ws + (plane * p.k + (int64_t)s_blk[slot] * p.Br + r) * a.ldw + colq;
           *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+        } else if (a.zsplit > 1) {  // OUT with split rows: plane z, summed by the reduce kernel
+          float* dst = a.ws + ((int64_t)z * p.k + (int64_t)blk * p.Br + row_s) * a.ldw + colq;
+          *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
         } else {
           T* dst = reinterpret_cast<T*>(a.out) + ((int64_t)blk * p.Br + row_s) * a.ldo + colq;
 #pragma unroll
@@ -543,8 +549,16 @@ Plan make_plan(const SketchParams& p, const void* A, int64_t lda, int64_t n, fs_
       pl.planes = (int)((p.kappa + R - 2) / R) + 1;
     }
   } else {
-    pl.mt = mt_o; pl.nrg = nrg_o; pl.zsplit = 1;
-    pl.stages = (int)((uint64_t)p.kappa * p.Bc / KC);
+    // split the kappa*Bc rows of a work-group over grid.z when there are too few output tiles to
+    // fill the chip (small n), as long as the extra plane traffic stays below that of reading A
+    const int total_stages = (int)((uint64_t)p.kappa * p.Bc / KC);
+    int zo = 1;
+    while ((int64_t)p.M * col_tiles * zo < 512 && zo < 8 && total_stages % (zo * 2) == 0 &&
+           2.0 * (zo * 2) * (double)p.k * 4.0 / ((double)p.d * esz) <= 1.0)
+      zo *= 2;
+    pl.mt = mt_o; pl.nrg = nrg_o; pl.zsplit = zo;
+    pl.stages = total_stages / zo;
+    if (zo > 1) { pl.ldw = (n + 3) & ~(int64_t)3; pl.planes = zo; }
   }
   pl.lds = lds_bytes(pl.mt, pl.nrg, pl.ncg, pl.run,
                      pl.run > 1 ? (size_t)(p.kappa + pl.run - 1) * p.Br * 256 * 4 : 0);
@@ -594,7 +608,7 @@ size_t mfma_workspace_bytes(const SketchParams& p, int64_t n, fs_dtype dt) {
   // sized without the orbit-run saving, so it holds for either mode
   const int64_t ld = (n + 7) & ~(int64_t)7;
   const Plan pl = make_plan(p, (const void*)(uintptr_t)256, ld, n, dt, false);
-  if (!pl.ok || !pl.in_stat) return 0;
+  if (!pl.ok || pl.planes == 0) return 0;
   return (size_t)pl.planes * (size_t)p.k * (size_t)pl.ldw * sizeof(float);
 }
 
@@ -615,7 +629,7 @@ hipError_t launch_mfma(const SketchParams& p, const void* A, int64_t lda, int64_
   while ((1u << a.log2_br) < p.Br) ++a.log2_br;
   const int tnw = 32 * pl.cpl * pl.ncg;
   const unsigned col_tiles = (unsigned)((n + tnw - 1) / tnw);
-  dim3 grid(p.M / pl.run, col_tiles, pl.in_stat ? pl.zsplit : 1);
+  dim3 grid(p.M / pl.run, col_tiles, pl.zsplit);
 
   if (ev.start) (void)hipEventRecord(ev.start, st);
   hipError_t e;
@@ -624,7 +638,7 @@ hipError_t launch_mfma(const SketchParams& p, const void* A, int64_t lda, int64_
   else
     e = pl.in_stat ? launch_shape<float, true>(pl, a, grid, st) : launch_shape<float, false>(pl, a, grid, st);
   if (ev.stop) (void)hipEventRecord(ev.stop, st);
-  if (e != hipSuccess || !pl.in_stat) return e;
+  if (e != hipSuccess || pl.planes == 0) return e;
 
   const int64_t work = p.k * (pl.ldw / 4);
   const unsigned blocks = (unsigned)((work + 255) / 256);
