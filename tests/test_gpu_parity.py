@@ -366,3 +366,47 @@ def test_variants_agree_with_each_other(dtype):
     tol = 1e-5 if dtype == torch.float32 else 8e-3
     assert O.rel_fro_err(outs[1], outs[0]) < tol
     assert np.array_equal(outs[1], outs[2])  # AUTO picked the MFMA path
+
+
+# ------------------------------------------------ seeded random shapes ----
+def _random_cases(count, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    while len(cases) < count:
+        Br = int(rng.choice([1, 2, 4, 8, 16, 32, 64, 128, 3, 12]))
+        M = int(rng.choice([1, 2, 4, 8, 16, 64, 256, 6]))
+        Bc = int(rng.choice([64, 128, 256, 512, 96]))
+        kappa = int(rng.integers(1, min(M, 8) + 1))
+        s = int(rng.integers(1, min(Br, 8) + 1))
+        n = int(rng.choice([1, 5, 64, 127, 128, 129, 255, 256, 260, 515]))
+        if M * Bc * n > 2 ** 24:
+            continue
+        cases.append(((M * Bc, M * Br, Bc, Br, kappa, s), n, int(rng.integers(0, 2 ** 62))))
+    return cases
+
+
+@pytest.mark.parametrize("variant", [B.VARIANT_AUTO, B.VARIANT_GENERIC], ids=lambda v: VNAME[v])
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+def test_random_shapes_match_oracle(dtype, variant):
+    """40 seeded random parameter sets (power-of-two and odd Br, composite M, ragged n): whichever
+    kernel the dispatcher (or the forced generic variant) runs must match the oracle, and the
+    exported nonzeros must be the oracle's."""
+    modes = set()
+    for params, n, seed in _random_cases(40, 2024):
+        print("random", params, n, seed, dtype, VNAME[variant], flush=True)
+        g = torch.Generator(device=DEV).manual_seed(seed % (2 ** 31))
+        A = torch.randn((params[0], n + (-n) % 4), generator=g, device=DEV).to(dtype)[:, :n]
+        sk = make_sketch(params, seed, variant)
+        out = sk.apply(A)
+        i = sk.info()
+        modes.add((i.last_variant, i.last_mode))
+        S = O.build_csc(O.Params(*params), seed)
+        check(out, O.apply(S, host64(A)), dtype, f"{params} n={n}")
+        if dtype == torch.float32 and variant == B.VARIANT_AUTO:
+            rows, signs = sk.export()
+            want_r, want_s = O.build_tables(O.Params(*params), seed)
+            assert np.array_equal(rows.cpu().numpy().astype(np.int64), want_r)
+            assert np.array_equal(signs.cpu().numpy(), want_s)
+    if variant == B.VARIANT_AUTO:
+        assert {m for v, m in modes if v == B.VARIANT_MFMA} >= {1, 2}, modes  # both MFMA modes were hit
+        assert (B.VARIANT_GENERIC, 0) in modes
