@@ -6,7 +6,9 @@
  * S in R^{k x d}, Y := S A).
  *
  * S is never stored.  It is a pure function of (d, k, Bc, Br, kappa, s, seed):
- *   - an M x M grid of Br x Bc blocks, M = d/Bc = k/Br (Section 4, "Block model");
+ *   - an M x M grid of Br x Bc blocks, M = k/Br = ceil(d/Bc) (Section 4, "Block model"); when
+ *     Bc does not divide d the input is treated as zero-padded to M*Bc rows (the paper's
+ *     "padding"), i.e. S is the first d columns of the padded sketch;
  *   - block (g, h) is nonzero iff h = f^l(g) for some l in 1..kappa, where
  *     f(x) = (a x + b) mod M is a full-period affine map whose (a, b) are
  *     derived from the seed (Section 4, "Block-level wiring"; Appendix E,
@@ -102,7 +104,7 @@ typedef struct {
 
 /* Create a BLOCKPERM handle.  Pure host work (no HIP call, usable without a GPU).
  * Errors (FS_ERR_INVALID_ARG): out == NULL; d, k, Bc, Br, kappa, s < 1;
- * Bc does not divide d, Br does not divide k, d/Bc != k/Br; kappa > M
+ * Br does not divide k, ceil(d/Bc) != k/Br; kappa > M
  * (Appendix E: the kappa neighbours are distinct only for kappa <= M);
  * s > Br (rows must be distinct, Alg. 1) or s > 32; Br > 65536; M > 2^24. */
 fs_status fs_sketch_create(fs_sketch_t* out, int64_t d, int64_t k, int32_t Bc, int32_t Br,

@@ -168,15 +168,21 @@ class Params:
 
     @property
     def M(self) -> int:
-        return self.d // self.Bc
+        return self.k // self.Br
+
+    @property
+    def d_padded(self) -> int:
+        """Input dimension rounded up to whole blocks (Section 4: the general case is handled
+        by padding): S is the first d columns of the sketch of the zero-padded input."""
+        return self.M * self.Bc
 
     def check(self) -> None:
         if min(self.d, self.k, self.Bc, self.Br, self.kappa, self.s) < 1:
             raise ValueError("all parameters must be positive")
-        if self.d % self.Bc or self.k % self.Br:
-            raise ValueError("Bc must divide d and Br must divide k")
-        if self.d // self.Bc != self.k // self.Br:
-            raise ValueError("d/Bc must equal k/Br (square block grid)")
+        if self.k % self.Br:
+            raise ValueError("Br must divide k")
+        if -(-self.d // self.Bc) != self.k // self.Br:
+            raise ValueError("ceil(d/Bc) must equal k/Br (square block grid)")
         if self.kappa > self.M:
             raise ValueError("kappa must not exceed M")
         if self.s > self.Br or self.s > 32 or self.Br > 65536:
@@ -193,8 +199,8 @@ def build_tables(p: Params, seed: int):
     M, Bc, Br, kappa, s = p.M, p.Bc, p.Br, p.kappa, p.s
     _, k1 = seed_keys(seed)
     a, b = wiring(M, k1)
-    rows = np.empty((p.d, kappa * s), dtype=np.int64)
-    signs = np.empty((p.d, kappa * s), dtype=np.int8)
+    rows = np.empty((p.d_padded, kappa * s), dtype=np.int64)
+    signs = np.empty((p.d_padded, kappa * s), dtype=np.int8)
     u = np.arange(Bc, dtype=np.uint32)
     g_all = np.arange(M, dtype=np.int64)
     h_l = g_all.copy()
@@ -208,7 +214,7 @@ def build_tables(p: Params, seed: int):
         cols = (h_l[:, None] * Bc + np.arange(Bc)[None, :]).reshape(-1)
         rows[cols, (l - 1) * s:l * s] = r.reshape(-1, s)
         signs[cols, (l - 1) * s:l * s] = sg.reshape(-1, s)
-    return rows, signs
+    return rows[:p.d], signs[:p.d]  # columns of the padding are dropped
 
 
 def build_csc(p: Params, seed: int) -> sp.csc_matrix:
@@ -248,6 +254,8 @@ def dense_by_loops(p: Params, seed: int) -> np.ndarray:
                 c = (h1 >> 16) % Br
                 while math.gcd(c, Br) != 1:
                     c = (c + 1) % Br
+                if h * Bc + u >= p.d:  # padding column
+                    continue
                 for i in range(p.s):
                     r = (shift + i * c) % Br
                     sigma = 1.0 if ((h2 >> i) & 1) == 0 else -1.0

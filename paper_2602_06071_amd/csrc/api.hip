@@ -138,8 +138,10 @@ fs_status fs_sketch_create_kind(fs_sketch_t* out, fs_kind kind, int64_t d, int64
   if (kind == FS_KIND_GAUSS_DENSE) { Bc = (int32_t)(d > 0x7fffffff ? 0x7fffffff : d); Br = 1; kappa = 1; s = 1; }
   if (kind != FS_KIND_GAUSS_DENSE) {
     if (Bc < 1 || Br < 1 || kappa < 1 || s < 1) return FS_ERR_INVALID_ARG;
-    if (d % Bc || k % Br || d / Bc != k / Br) return FS_ERR_INVALID_ARG;
-    const int64_t M = d / Bc;
+    // the block grid is square: M = k/Br = ceil(d/Bc); a last input block that is only partly
+    // filled is treated as zero-padded (Section 4, "general cases ... by padding")
+    if (k % Br || (d + Bc - 1) / Bc != k / Br) return FS_ERR_INVALID_ARG;
+    const int64_t M = k / Br;
     if (M > (1 << 24) || kappa > M) return FS_ERR_INVALID_ARG;
     if (s > Br || s > 32 || Br > 65536) return FS_ERR_INVALID_ARG;
     if (kind == FS_KIND_SJLT_SCATTER && (M != 1 || kappa != 1)) return FS_ERR_INVALID_ARG;
@@ -149,7 +151,7 @@ fs_status fs_sketch_create_kind(fs_sketch_t* out, fs_kind kind, int64_t d, int64
   SketchParams& p = h->p;
   p.d = d; p.k = k;
   p.Bc = (uint32_t)Bc; p.Br = (uint32_t)Br; p.kappa = (uint32_t)kappa; p.s = (uint32_t)s;
-  p.M = kind == FS_KIND_GAUSS_DENSE ? 1u : (uint32_t)(d / Bc);
+  p.M = kind == FS_KIND_GAUSS_DENSE ? 1u : (uint32_t)(k / Br);
   h->key0 = fs::mix32((uint32_t)(seed & 0xFFFFFFFFu) ^ fs::kC1);
   p.key1 = fs::mix32((uint32_t)(seed >> 32) ^ h->key0 ^ fs::kC2);
   derive_wiring(p.M, p.key1, &p.a, &p.b, &p.a_inv);

@@ -41,7 +41,8 @@ __global__ __launch_bounds__(256) void generic_kernel(SketchParams p, const T* _
       float v[kRowUnroll];
 #pragma unroll
       for (int q = 0; q < kRowUnroll; ++q)
-        v[q] = (active && u0 + q < p.Bc) ? Elt<T>::load(src + (int64_t)(u0 + q) * lda) : 0.f;
+        v[q] = (active && u0 + q < p.Bc && (int64_t)h * p.Bc + u0 + q < p.d)  // padding rows read as 0
+                   ? Elt<T>::load(src + (int64_t)(u0 + q) * lda) : 0.f;
 #pragma unroll
       for (int q = 0; q < kRowUnroll; ++q) {
         if (u0 + q >= p.Bc) break;

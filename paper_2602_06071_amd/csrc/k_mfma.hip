@@ -229,17 +229,22 @@ void mfma_kernel(MfmaArgs a) {
     // Buffer descriptor over the rows this work-group reads from one input block
     // (dword 3 = 32-bit data format for gfx9-family raw buffers).  The scalar offset
     // walks the rows, the lane offset (voff) selects row-in-k-step and column.
+    // Rows at or beyond d (the zero padding of a partly filled last input block) lie outside
+    // the descriptor's range, and out-of-range buffer loads return 0 without touching memory.
     auto make_rsrc = [&](int64_t first_row, int64_t nrows) {
-      const int64_t bytes = (nrows - 1) * row_bytes + (int64_t)a.n * (int64_t)sizeof(T);
+      const int64_t valid = min(nrows, p.d - first_row);
+      const int64_t bytes = valid > 0 ? (valid - 1) * row_bytes + (int64_t)a.n * (int64_t)sizeof(T) : 0;
       return __builtin_amdgcn_make_buffer_rsrc(
           const_cast<char*>(Abase + first_row * row_bytes), 0, (int)bytes, 0x00020000);
     };
     auto issue = [&](int kk, V (&dst)[8]) {
       if constexpr (RAGGED) {
-        const char* sb = Abase + row_of(kk) * row_bytes;
+        const int64_t row0 = row_of(kk);
+        const char* sb = Abase + row0 * row_bytes;
 #pragma unroll
         for (int j = 0; j < 8; ++j)
-          dst[j] = load4_guarded<T, CPL>(reinterpret_cast<const T*>(sb + j * row_bytes + voff), col0, a.n);
+          dst[j] = load4_guarded<T, CPL>(reinterpret_cast<const T*>(sb + j * row_bytes + voff), col0,
+                                         row0 + kg * 8 + j < p.d ? a.n : 0);  // padding rows read as 0
       } else {
         __amdgpu_buffer_rsrc_t rs;
         uint32_t so;

@@ -36,9 +36,10 @@ def _create(*args, kind=B.KIND_BLOCKPERM):
 @pytest.mark.parametrize("args", [
     (0, 256, 512, 32, 2, 4, 0),       # d < 1
     (4096, 0, 512, 32, 2, 4, 0),      # k < 1
-    (4096, 256, 500, 32, 2, 4, 0),    # Bc does not divide d
+    (4096, 256, 500, 32, 2, 4, 0),    # ceil(d/Bc) = 9 != k/Br = 8
     (4096, 256, 512, 48, 2, 4, 0),    # Br does not divide k
     (4096, 256, 512, 64, 2, 4, 0),    # d/Bc != k/Br
+    (3584, 256, 512, 32, 2, 4, 0),    # one whole block short of a square grid
     (4096, 256, 512, 32, 9, 4, 0),    # kappa > M
     (4096, 256, 512, 32, 0, 4, 0),    # kappa < 1
     (4096, 256, 512, 32, 2, 0, 0),    # s < 1
@@ -73,6 +74,7 @@ def test_create_null_out_and_bad_kind():
 @pytest.mark.parametrize("cfg", [
     (4096, 256, 512, 32, 2, 4), (16384, 1024, 1024, 64, 8, 8), (262144, 4096, 2048, 32, 4, 4),
     (65536, 4096, 2048, 128, 4, 8), (4194304, 8192, 4096, 8, 8, 2), (1152, 72, 96, 6, 5, 3),
+    (4000, 256, 512, 32, 2, 4), (3585, 256, 512, 32, 2, 4),
     (1440, 180, 80, 10, 18, 10), (512, 512, 1, 1, 3, 1), (1024, 64, 1024, 64, 1, 8),
 ])
 @pytest.mark.parametrize("seed", [0, 1, 0xDEADBEEF12345678])

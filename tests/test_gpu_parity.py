@@ -53,6 +53,7 @@ def apply_or_skip(sk, A, out=None):
 
 # ------------------------------------------------------------ export ------
 @pytest.mark.parametrize("params", [
+    (4000, 256, 512, 32, 2, 4), (65500, 8192, 64, 8, 8, 2),
     (4096, 256, 512, 32, 2, 4), (2048, 1024, 128, 64, 4, 2), (1152, 72, 96, 6, 5, 3),
     (1440, 180, 80, 10, 18, 10), (512, 512, 1, 1, 3, 1), (1024, 64, 1024, 64, 1, 8),
     (16384, 1024, 1024, 64, 8, 8), (262144, 4096, 2048, 32, 4, 4), (65536, 4096, 2048, 128, 4, 8),
@@ -99,6 +100,11 @@ SMALL = [
     ((65536, 8192, 64, 8, 8, 2), 300, 4, 4),        # the same with a ragged second column tile
     ((32768, 4096, 128, 16, 4, 4), 1024, 0, 0),     # M = 256, four column tiles, Br = 16
     ((16384, 2048, 64, 8, 8, 2), 2500, 0, 0),       # M = 256, ten column tiles, ragged
+    ((4000, 256, 512, 32, 2, 4), 300, 0, 0),        # d not a multiple of Bc (zero-padded last block)
+    ((32700, 64, 4096, 8, 8, 2), 256, 0, 0),
+    ((65500, 8192, 64, 8, 8, 2), 300, 4, 0),        # the same in orbit-run mode, ragged tile
+    ((7201, 512, 1024, 64, 8, 8), 264, 0, 0),       # the same in OUT-stationary mode
+    ((1100, 72, 96, 6, 5, 3), 65, 0, 0),            # the same on the generic kernel only
 ]
 
 

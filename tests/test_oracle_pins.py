@@ -24,6 +24,8 @@ PARAM_GRID = [
     (1440, 180, 80, 10, 18, 10),    # M = 18, kappa = M, s = Br
     (512, 512, 1, 1, 3, 1),         # Br = Bc = 1
     (4096, 64, 512, 8, 8, 2),       # kappa = M = 8, gradient-config block shape
+    (4000, 256, 512, 32, 2, 4),     # d not a multiple of Bc: last input block partly filled
+    (1100, 72, 96, 6, 5, 3),        # the same with composite M and odd Br
 ]
 
 
@@ -244,6 +246,26 @@ def test_bruteforce_dense_equals_csc(cfg):
         Sc = O.build_csc(p, seed)
         np.testing.assert_array_equal(Sd, Sc.toarray())
         np.testing.assert_allclose(O.apply(Sc, A), Sd @ A, rtol=1e-13, atol=1e-13)
+
+
+@pytest.mark.parametrize("cfg,d_short", [((96, 24, 8, 2, 3, 2), 91), ((60, 30, 10, 5, 6, 5), 51),
+                                         ((4096, 256, 512, 32, 2, 4), 3585)])
+def test_padding_is_the_sketch_of_the_zero_padded_input(cfg, d_short):
+    """Section 4 handles d not divisible by Bc "by padding": S for the short d must be the
+    first d columns of the full-grid S, so S_short @ A == S_full @ [A; 0]."""
+    full = O.Params(*cfg)
+    short = O.Params(d_short, *cfg[1:])
+    assert short.M == full.M and short.d_padded == full.d
+    Sf, Ss = O.build_csc(full, 3), O.build_csc(short, 3)
+    assert Ss.shape == (full.k, d_short)
+    assert (Sf[:, :d_short] != Ss).nnz == 0
+    A = np.random.default_rng(0).standard_normal((d_short, 5))
+    Apad = np.vstack([A, np.zeros((full.d - d_short, 5))])
+    np.testing.assert_allclose(O.apply(Ss, A), O.apply(Sf, Apad), rtol=1e-14, atol=1e-14)
+    if full.d <= 128:
+        np.testing.assert_array_equal(O.dense_by_loops(short, 3), Ss.toarray())
+    with pytest.raises(ValueError):
+        O.Params(full.d - full.Bc, *cfg[1:]).check()  # one whole block short: grid no longer square
 
 
 def test_plain_sjlt_special_case():
