@@ -197,6 +197,7 @@ def extra_measurements(torch, B, W, dev, skip, with_oracle):
             res[f"mid_plain_sjlt_scatter_s{s}"] = one(
                 base, A, kind=B.KIND_SJLT_SCATTER, sketch_params=(base.d, base.k, base.d, base.k, 1, s))
         res["mid_dense_gaussian"] = one(base, A, kind=B.KIND_GAUSS_DENSE)
+        res["mid_blockrow"] = one(base, A, kind=B.KIND_BLOCKROW)  # gather variant, reads k*kappa*s rows
         del A
     if skip != "wide":
         base = W.CONFIGS["wide"]

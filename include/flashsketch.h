@@ -70,11 +70,16 @@ typedef enum {
                                (Section 3 "GPU bottlenecks for Sparse Sketching").
                                Same S as BLOCKPERM with M = 1: needs Bc = d, Br = k,
                                kappa = 1.                                                  */
-  FS_KIND_GAUSS_DENSE = 2   /* dense Gaussian sketch S_ij ~ N(0, 1/k) (Section 1) applied
+  FS_KIND_GAUSS_DENSE = 2,  /* dense Gaussian sketch S_ij ~ N(0, 1/k) (Section 1) applied
                                by an MFMA GEMM; Bc, Br, kappa, s are ignored.  Reference
                                point only: needs 64 | d, 128 | k, 4 | lda, a 16-byte (fp32)
                                or 8-byte (bf16) aligned A and d*lda*sizeof(elt) < 2^31,
                                else apply returns FS_ERR_UNSUPPORTED.                      */
+  FS_KIND_BLOCKROW = 3      /* FlashBlockRow (Appendix D, Alg. 2): gather-only block-row
+                               sampling.  Same parameters as BLOCKPERM; output row (g, r)
+                               adds s signed rows of A from each of the kappa blocks f^l(g)
+                               and scales by sqrt(d/k)/sqrt(kappa*s).  Reads k*kappa*s rows
+                               of A; input coordinates that no row samples are ignored.   */
 } fs_kind;
 
 /* Kernel variants of the BLOCKPERM apply (fs_sketch_set_variant). */
@@ -130,7 +135,10 @@ fs_status fs_sketch_apply_ld(fs_sketch_t h, const void* A, int64_t lda, int64_t 
 /* Materialise the nonzeros of S on the device (BLOCKPERM / SJLT_SCATTER):
  * rows[c*kappa*s + (l-1)*s + i] = global output row, signs[...] = +1/-1, for
  * column c of S, wiring slot l (the l with f^l(g) = c / Bc) and update i.
- * Both buffers hold d*kappa*s entries. */
+ * Both buffers hold d*kappa*s entries.
+ * BLOCKROW: the sketch is stored by rows instead: rows[i*kappa*s + (l-1)*s + t] = global
+ * COLUMN index read by output row i (it may lie in the zero padding, >= d), signs likewise;
+ * both buffers hold k*kappa*s entries. */
 fs_status fs_sketch_export(fs_sketch_t h, int32_t* rows, int8_t* signs, void* stream);
 
 /* GAUSS_DENSE only: copy the k x d fp32 matrix (row-major, ld = d) to S_dense. */

@@ -7,7 +7,7 @@ ImportError.  (`python -m paper_2602_06071_amd.build` builds it.)
 """
 
 _BINDING_NAMES = {
-    "FS_BF16", "FS_F32", "KIND_BLOCKPERM", "KIND_GAUSS_DENSE", "KIND_SJLT_SCATTER",
+    "FS_BF16", "FS_F32", "KIND_BLOCKPERM", "KIND_BLOCKROW", "KIND_GAUSS_DENSE", "KIND_SJLT_SCATTER",
     "VARIANT_AUTO", "VARIANT_GENERIC", "VARIANT_MFMA", "FlashSketchError", "Sketch", "lib",
     "lib_path", "fs_info", "SYMBOLS",
 }

@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 lib_path = os.environ.get("FLASHSKETCH_LIB") or os.path.join(_HERE, "libflashsketch.so")
 
 FS_F32, FS_BF16 = 0, 1
-KIND_BLOCKPERM, KIND_SJLT_SCATTER, KIND_GAUSS_DENSE = 0, 1, 2
+KIND_BLOCKPERM, KIND_SJLT_SCATTER, KIND_GAUSS_DENSE, KIND_BLOCKROW = 0, 1, 2, 3
 VARIANT_AUTO, VARIANT_GENERIC, VARIANT_MFMA = 0, 1, 2
 
 SYMBOLS = [
@@ -159,12 +159,13 @@ class Sketch:
 
     def export(self, device="cuda", stream=None):
         i = self.info()
-        nnz = i.d * i.kappa * i.s
+        lead = i.k if i.kind == KIND_BLOCKROW else i.d  # BLOCKROW is stored by output row
+        nnz = lead * i.kappa * i.s
         rows = torch.empty(nnz, dtype=torch.int32, device=device)
         signs = torch.empty(nnz, dtype=torch.int8, device=device)
         _check(lib.fs_sketch_export(self._h, rows.data_ptr(), signs.data_ptr(), _stream_ptr(stream)),
                "fs_sketch_export")
-        return rows.view(i.d, i.kappa * i.s), signs.view(i.d, i.kappa * i.s)
+        return rows.view(lead, i.kappa * i.s), signs.view(lead, i.kappa * i.s)
 
     def export_dense(self, device="cuda", stream=None) -> torch.Tensor:
         S = torch.empty((self.k, self.d), dtype=torch.float32, device=device)

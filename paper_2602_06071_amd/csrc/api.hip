@@ -67,6 +67,7 @@ fs_status needed_workspace(fs_sketch_t h, const void* A, int64_t lda, int64_t n,
   }
   if (h->kind == FS_KIND_GAUSS_DENSE)
     return fs::gauss_supported(h->p.k, h->p.d, A, lda, n, dt) ? FS_OK : FS_ERR_UNSUPPORTED;
+  if (h->kind == FS_KIND_BLOCKROW) return FS_OK;
   const bool can = fs::mfma_supported(h->p, A, lda, n, out, ldo, dt);
   int v = h->variant;
   if (v == FS_VARIANT_AUTO) v = can ? FS_VARIANT_MFMA : FS_VARIANT_GENERIC;
@@ -132,7 +133,8 @@ fs_status fs_sketch_create_kind(fs_sketch_t* out, fs_kind kind, int64_t d, int64
                                 int32_t Br, int32_t kappa, int32_t s, uint64_t seed) {
   if (!out) return FS_ERR_INVALID_ARG;
   *out = nullptr;
-  if (kind != FS_KIND_BLOCKPERM && kind != FS_KIND_SJLT_SCATTER && kind != FS_KIND_GAUSS_DENSE)
+  if (kind != FS_KIND_BLOCKPERM && kind != FS_KIND_SJLT_SCATTER && kind != FS_KIND_GAUSS_DENSE &&
+      kind != FS_KIND_BLOCKROW)
     return FS_ERR_INVALID_ARG;
   if (d < 1 || k < 1 || d > ((int64_t)1 << 40) || k > ((int64_t)1 << 31)) return FS_ERR_INVALID_ARG;
   if (kind == FS_KIND_GAUSS_DENSE) { Bc = (int32_t)(d > 0x7fffffff ? 0x7fffffff : d); Br = 1; kappa = 1; s = 1; }
@@ -157,6 +159,7 @@ fs_status fs_sketch_create_kind(fs_sketch_t* out, fs_kind kind, int64_t d, int64
   derive_wiring(p.M, p.key1, &p.a, &p.b, &p.a_inv);
   p.br_pow2 = is_pow2(p.Br) ? 1u : 0u;
   p.scale = kind == FS_KIND_GAUSS_DENSE ? (float)(1.0 / sqrt((double)k))
+            : kind == FS_KIND_BLOCKROW  ? (float)(sqrt((double)d / (double)k) / sqrt((double)kappa * (double)s))
                                         : (float)(1.0 / sqrt((double)kappa * (double)s));
   h->kind = (int)kind;
   h->variant = FS_VARIANT_AUTO;
@@ -322,6 +325,8 @@ fs_status fs_sketch_apply_ld(fs_sketch_t h, const void* A, int64_t lda, int64_t 
     e = fs::launch_scatter(h->p, A, lda, n, out, ldo, dt, h->ws, st, ev);
   } else if (h->kind == FS_KIND_GAUSS_DENSE) {
     e = fs::launch_gauss(h->dense, h->p.k, h->p.d, A, lda, n, out, ldo, dt, st, ev);
+  } else if (h->kind == FS_KIND_BLOCKROW) {
+    e = fs::launch_blockrow(h->p, A, lda, n, out, ldo, dt, st, ev);
   } else if (variant == FS_VARIANT_MFMA) {
     e = fs::launch_mfma(h->p, A, lda, n, out, ldo, dt, h->ws, h->orbit, st, ev, &mode);
   } else {
@@ -341,7 +346,9 @@ fs_status fs_sketch_apply(fs_sketch_t h, const void* A, int64_t lda, int64_t n, 
 fs_status fs_sketch_export(fs_sketch_t h, int32_t* rows, int8_t* signs, void* stream) {
   if (!h || !rows || !signs) return FS_ERR_INVALID_ARG;
   if (h->kind == FS_KIND_GAUSS_DENSE) return FS_ERR_UNSUPPORTED;
-  hipError_t e = fs::launch_export(h->p, rows, signs, (hipStream_t)stream);
+  hipError_t e = h->kind == FS_KIND_BLOCKROW
+                     ? fs::launch_blockrow_export(h->p, rows, signs, (hipStream_t)stream)
+                     : fs::launch_export(h->p, rows, signs, (hipStream_t)stream);
   if (e != hipSuccess) return hip_fail(h, e);
   return FS_OK;
 }

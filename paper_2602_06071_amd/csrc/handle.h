@@ -72,6 +72,11 @@ size_t scatter_workspace_bytes(const SketchParams& p, int64_t n, fs_dtype dt);
 hipError_t launch_scatter(const SketchParams& p, const void* A, int64_t lda, int64_t n, void* out,
                           int64_t ldo, fs_dtype dt, void* ws, hipStream_t st, EventPair ev);
 
+// FlashBlockRow gather sketch (kind BLOCKROW): no workspace.
+hipError_t launch_blockrow(const SketchParams& p, const void* A, int64_t lda, int64_t n, void* out,
+                           int64_t ldo, fs_dtype dt, hipStream_t st, EventPair ev);
+hipError_t launch_blockrow_export(const SketchParams& p, int32_t* cols, int8_t* signs, hipStream_t st);
+
 // Dense Gaussian sketch.  `storage` holds the k x d matrix as fp32, then four bf16
 // copies (rounded, and the exact split hi / mid / lo): gauss_bytes(k, d) bytes.
 size_t gauss_bytes(int64_t k, int64_t d);

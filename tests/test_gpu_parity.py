@@ -416,3 +416,29 @@ def test_random_shapes_match_oracle(dtype, variant):
     if variant == B.VARIANT_AUTO:
         assert {m for v, m in modes if v == B.VARIANT_MFMA} >= {1, 2}, modes  # both MFMA modes were hit
         assert (B.VARIANT_GENERIC, 0) in modes
+
+
+# ------------------------------------------------ FlashBlockRow kind ------
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("case", [
+    ((4096, 256, 512, 32, 2, 4), 512, 0), ((4000, 256, 512, 32, 2, 4), 301, 3),
+    ((1152, 72, 96, 6, 5, 3), 65, 0), ((65536, 8192, 64, 8, 8, 2), 260, 0),
+    ((16384, 1024, 2048, 128, 4, 8), 1000, 0), ((1024, 64, 1024, 64, 1, 8), 1, 0),
+], ids=lambda c: f"{c[0]}-n{c[1]}")
+def test_blockrow_matches_oracle(case, dtype):
+    from oracle import blockrow as R
+    params, n, pad = case
+    print("blockrow", params, n, dtype, flush=True)
+    seed = 11
+    g = torch.Generator(device=DEV).manual_seed(n)
+    A = torch.randn((params[0], n + pad), generator=g, device=DEV).to(dtype)[:, :n]
+    sk = B.Sketch(*params, seed=seed, kind=B.KIND_BLOCKROW)
+    out = sk.apply(A)
+    cols, signs = sk.export()
+    torch.cuda.synchronize()
+    p = O.Params(*params)
+    want_c, want_s = R.build_tables(p, seed)
+    assert np.array_equal(cols.cpu().numpy().astype(np.int64), want_c)
+    assert np.array_equal(signs.cpu().numpy(), want_s)
+    assert abs(sk.info().scale - R.scale(p)) <= 1e-7 * R.scale(p)
+    check(out, R.apply(R.build_csr(p, seed), host64(A)), dtype, "blockrow")
