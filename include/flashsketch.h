@@ -124,7 +124,10 @@ fs_status fs_sketch_create_kind(fs_sketch_t* out, fs_kind kind, int64_t d, int64
 /* out (k x n, ld = n) = S * A (d x n, ld = lda), both of type `dtype`.
  * n == 0 is FS_OK and launches nothing.  Errors: NULL handle/A/out, n < 0,
  * lda < n, unknown dtype.  May grow the handle's workspace with hipMalloc on
- * first use unless one was attached with fs_sketch_set_workspace. */
+ * first use unless one was attached with fs_sketch_set_workspace.  The first
+ * matrix-core apply of a handle also uploads a table of 8*M bytes (the orbit
+ * of the wiring map) with a synchronous copy; later applies only enqueue
+ * kernels (call apply once before capturing it into a HIP graph). */
 fs_status fs_sketch_apply(fs_sketch_t h, const void* A, int64_t lda, int64_t n, void* out,
                           fs_dtype dtype, void* stream);
 

@@ -573,10 +573,12 @@ Plan make_plan(const SketchParams& p, const void* A, int64_t lda, int64_t n, fs_
 
 template <typename K>
 hipError_t go(K kernel, dim3 grid, unsigned threads, size_t lds, hipStream_t st, const MfmaArgs& a) {
-  if (lds > 64 * 1024) {  // above the default dynamic-LDS limit: raise it for this kernel
+  static size_t raised = 64 * 1024;  // one per kernel instantiation: the limit set so far
+  if (lds > raised) {  // above the default dynamic-LDS limit: raise it for this kernel
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
+    raised = lds;
   }
   hipLaunchKernelGGL(kernel, grid, dim3(threads), lds, st, a);
   return hipGetLastError();
