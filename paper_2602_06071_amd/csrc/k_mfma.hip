@@ -67,7 +67,7 @@ struct MfmaArgs {
 };
 
 template <typename T, int MT, int NRG, int NCG, bool IN_STAT, int RUN, int CPL>
-__global__ __launch_bounds__(64 * NRG * NCG * RUN) __attribute__((amdgpu_waves_per_eu(2)))
+__global__ __launch_bounds__(64 * NRG * NCG * RUN) __attribute__((amdgpu_waves_per_eu(MT > 2 ? 1 : 2)))
 void mfma_kernel(MfmaArgs a) {
   using V = typename LdN<T, CPL>::V;
   constexpr int PFD = LdN<T, CPL>::PFD;
@@ -501,7 +501,7 @@ constexpr size_t kLdsBudget = 160 * 1024;
 bool tile_shape(uint32_t rw, int* mt, int* nrg) {
   if (rw == 32) { *mt = 1; *nrg = 1; return true; }
   if (rw == 64) { *mt = 2; *nrg = 1; return true; }
-  if (rw == 128) { *mt = 2; *nrg = 2; return true; }
+  if (rw == 128) { *mt = 4; *nrg = 1; return true; }
   return false;
 }
 
@@ -592,9 +592,9 @@ hipError_t launch_shape(const Plan& pl, const MfmaArgs& a, dim3 grid, hipStream_
     if (pl.run == 4) FS_GO(2, 1, 2, 4);
   }
   if (pl.ncg == 1) {
-    if (pl.mt == 1) FS_GO(1, 1, 1, 1); else if (pl.nrg == 1) FS_GO(2, 1, 1, 1); else FS_GO(2, 2, 1, 1);
+    if (pl.mt == 1) FS_GO(1, 1, 1, 1); else if (pl.mt == 2) FS_GO(2, 1, 1, 1); else FS_GO(4, 1, 1, 1);
   } else {
-    if (pl.mt == 1) FS_GO(1, 1, 2, 1); else if (pl.nrg == 1) FS_GO(2, 1, 2, 1); else FS_GO(2, 2, 2, 1);
+    if (pl.mt == 1) FS_GO(1, 1, 2, 1); else if (pl.mt == 2) FS_GO(2, 1, 2, 1); else FS_GO(4, 1, 2, 1);
   }
 #undef FS_GO
 }
