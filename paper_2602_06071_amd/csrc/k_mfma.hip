@@ -66,11 +66,14 @@ struct MfmaArgs {
   uint32_t log2_br;
 };
 
-template <typename T, int MT, int NRG, int NCG, bool IN_STAT, int RUN, int CPL>
+// PFX multiplies the depth of the register prefetch ring (1 or 2).  A ring deeper than one
+// stage (bf16, PFX = 2: 8 k-steps) needs an even number of stages, which the host checks.
+template <typename T, int MT, int NRG, int NCG, bool IN_STAT, int RUN, int CPL, int PFX = 1>
 __global__ __launch_bounds__(64 * NRG * NCG * RUN) __attribute__((amdgpu_waves_per_eu(MT > 2 ? 1 : 2)))
 void mfma_kernel(MfmaArgs a) {
   using V = typename LdN<T, CPL>::V;
-  constexpr int PFD = LdN<T, CPL>::PFD;
+  constexpr int PFD = LdN<T, CPL>::PFD * PFX;
+  static_assert(PFD <= KSTEPS || PFD == 2 * KSTEPS, "ring depth: within a stage, or exactly two stages");
   constexpr int WC = 32 * CPL;                 // columns per wave
   constexpr int NW = NRG * NCG, NT = 64 * NW;  // waves / threads of one sub-group
   constexpr int RWV = 32 * MT;                 // stacked Phi rows of one wave
@@ -178,27 +181,28 @@ void mfma_kernel(MfmaArgs a) {
   auto scatter = [&](uint16_t* phi, uint32_t key, uint32_t u, uint32_t slot_row0, bool whole) {
     const RowHash rh = row_hash_pow2(key, u, p.Br);
     uint32_t r = rh.shift;
-    // tile index of (row, lane) = row*72 + lane, in 32-bit shifts and adds
+    // tile index of (row, lane) = row*72 + lane (24-bit multiply-add); the stored half-word is
+    // +-1.0 in bf16: 0x3F80 with sign bit i of the hash word moved to bit 15 (bits above 15 of
+    // the 32-bit value are dropped by the 16-bit store)
     const uint32_t base = slot_row0 - row_lo;
+    auto put = [&](uint32_t local, uint32_t i) {
+      phi[__umul24(local, (uint32_t)PHI_LD) + lane] = (uint16_t)(((rh.signs >> i) << 15) | kOne);
+    };
     if (whole) {
       // s >= 1; the first two updates are peeled (s = 2 and 4 are the common cases)
-      uint32_t local = base + r;
-      phi[(local << 6) + (local << 3) + lane] = (rh.signs & 1u) ? kMinusOne : kOne;
+      put(base + r, 0);
       if (p.s >= 2) {
         r = (r + rh.stride) & (p.Br - 1);
-        local = base + r;
-        phi[(local << 6) + (local << 3) + lane] = (rh.signs & 2u) ? kMinusOne : kOne;
+        put(base + r, 1);
         for (uint32_t i = 2; i < p.s; ++i) {
           r = (r + rh.stride) & (p.Br - 1);
-          local = base + r;
-          phi[(local << 6) + (local << 3) + lane] = ((rh.signs >> i) & 1u) ? kMinusOne : kOne;
+          put(base + r, i);
         }
       }
     } else {
       for (uint32_t i = 0; i < p.s; ++i) {
         const uint32_t local = base + r;  // unsigned: rows below row_lo wrap high
-        if (local < (uint32_t)RWV)
-          phi[(local << 6) + (local << 3) + lane] = ((rh.signs >> i) & 1u) ? kMinusOne : kOne;
+        if (local < (uint32_t)RWV) put(local, i);
         r = (r + rh.stride) & (p.Br - 1);
       }
     }
@@ -237,6 +241,40 @@ void mfma_kernel(MfmaArgs a) {
       return __builtin_amdgcn_make_buffer_rsrc(
           const_cast<char*>(Abase + first_row * row_bytes), 0, (int)bytes, 0x00020000);
     };
+    // Fetch cursor (unguarded path).  k-steps are issued strictly in order, so the OUT mode
+    // keeps (descriptor of the current input block, byte offset, k-step within the block) in
+    // scalar registers and only rebuilds the descriptor when it crosses into the next block.
+    __amdgpu_buffer_rsrc_t f_rs = make_rsrc(0, 0);
+    uint32_t f_so = 0, f_kr = 0, f_l = 0;
+    const uint32_t per_blk_k = p.Bc / 16;
+    auto cursor_init = [&]() {
+      if (IN_STAT) {
+        f_rs = make_rsrc((int64_t)blk * p.Bc + (int64_t)z * T_stages * KC, (int64_t)T_stages * KC);
+      } else {
+        const uint32_t kg0 = (uint32_t)(z * T_stages * KSTEPS);
+        f_l = kg0 / per_blk_k;
+        f_kr = kg0 % per_blk_k;
+        const uint32_t hb = __builtin_amdgcn_readfirstlane(s_blk[f_l]);
+        f_rs = make_rsrc((int64_t)hb * p.Bc, p.Bc);
+        f_so = f_kr * 16u * (uint32_t)row_bytes;
+      }
+    };
+    // OUT mode, after every issue: step the cursor (wave-uniform; the branch is taken once per
+    // input block).  Kept apart from issue() so that it can sit at the end of a k-step and the
+    // k-step stays one basic block.
+    auto advance = [&]() {
+      if constexpr (!IN_STAT && !RAGGED) {
+        f_so += 16u * (uint32_t)row_bytes;
+        if (++f_kr == per_blk_k) {
+          f_kr = 0;
+          f_so = 0;
+          if (++f_l < p.kappa) {
+            const uint32_t hb = __builtin_amdgcn_readfirstlane(s_blk[f_l]);
+            f_rs = make_rsrc((int64_t)hb * p.Bc, p.Bc);
+          }
+        }
+      }
+    };
     auto issue = [&](int kk, V (&dst)[8]) {
       if constexpr (RAGGED) {
         const int64_t row0 = row_of(kk);
@@ -246,19 +284,8 @@ void mfma_kernel(MfmaArgs a) {
           dst[j] = load4_guarded<T, CPL>(reinterpret_cast<const T*>(sb + j * row_bytes + voff), col0,
                                          row0 + kg * 8 + j < p.d ? a.n : 0);  // padding rows read as 0
       } else {
-        __amdgpu_buffer_rsrc_t rs;
-        uint32_t so;
-        if (IN_STAT) {
-          rs = make_rsrc((int64_t)blk * p.Bc + (int64_t)z * T_stages * KC, (int64_t)T_stages * KC);
-          so = (uint32_t)kk * 16u * (uint32_t)row_bytes;
-        } else {
-          const uint32_t per_blk = p.Bc / 16;
-          const uint32_t kg_ = (uint32_t)(z * T_stages * KSTEPS + kk);
-          const uint32_t l = kg_ / per_blk, kr = kg_ % per_blk;
-          const uint32_t hb = __builtin_amdgcn_readfirstlane(s_blk[l]);
-          rs = make_rsrc((int64_t)hb * p.Bc, p.Bc);
-          so = kr * 16u * (uint32_t)row_bytes;
-        }
+        const __amdgpu_buffer_rsrc_t rs = f_rs;
+        const uint32_t so = IN_STAT ? (uint32_t)kk * 16u * (uint32_t)row_bytes : f_so;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
           const uint32_t soj = so + (uint32_t)j * (uint32_t)row_bytes;
@@ -270,11 +297,15 @@ void mfma_kernel(MfmaArgs a) {
       }
     };
 
-    // One stage: 4 MFMA k-steps on tile t%2 while the next stage is loaded and hashed into
-    // the other tile.  LAST stages issue no loads and fill no tile, so that the steady-state
-    // loop body has no conditional memory operations.
-    auto stage = [&](int t, auto last_tag) {
-      constexpr bool LAST = decltype(last_tag)::value;
+    // One stage: 4 MFMA k-steps on tile t%2 while a later stage is loaded and the next one is
+    // hashed into the other tile.  FETCH (compile time): 2 = every k-step issues the loads PFD
+    // k-steps ahead, 1 = only those that stay inside this stage, 0 = none; FILL: whether a next
+    // stage exists.  The steady-state loop body thus has no conditional memory operations.
+    // PAR is the stage's parity when the ring spans two stages (it makes the ring slot static).
+    auto stage = [&](int t, auto par_tag, auto fetch_tag, auto fill_tag) {
+      constexpr int PAR = decltype(par_tag)::value;
+      constexpr int FETCH = decltype(fetch_tag)::value;
+      constexpr bool LAST = !decltype(fill_tag)::value;
       const uint16_t* phi = s_phi + (t & 1) * TILE;
       const int fill_buf = (t + 1) & 1;
 #pragma unroll
@@ -286,8 +317,8 @@ void mfma_kernel(MfmaArgs a) {
               phi + (mt * 32 + (lane & 31)) * PHI_LD + ks * 16 + kg * 8);
         if constexpr (!LAST) produce(t + 1, fill_buf, ks);
 
-        V(&cur)[8] = ld[ks % PFD];
-        const bool fetch = !LAST || ks + PFD < KSTEPS;  // compile-time after unrolling
+        V(&cur)[8] = ld[(PAR * KSTEPS + ks) % PFD];
+        const bool fetch = FETCH == 2 || (FETCH == 1 && ks + PFD < KSTEPS);  // compile-time
         if constexpr (sizeof(T) == 2) {
           uint4 op[4];
           make_ops(cur, op);
@@ -314,20 +345,144 @@ void mfma_kernel(MfmaArgs a) {
           }
           if (fetch) issue(t * KSTEPS + ks + PFD, cur);
         }
+        if (fetch) advance();
         __builtin_amdgcn_sched_barrier(0);  // keep k-steps apart: bounds register pressure
       }
       // the tile just consumed becomes the fill target of the next stage
       if constexpr (!LAST) clear_tile(t & 1);
     };
 
+    // OUT mode runs a software-pipelined variant of the stage, written as straight-line code so
+    // that the scheduler can place the non-MFMA work between the MFMAs (with one wave per SIMD
+    // nothing else would hide it):
+    //  * the Phi operands of k-step ks+1 are read from LDS during k-step ks (two register sets);
+    //  * the s nonzeros of a row of the next stage are written two per k-step, without a loop:
+    //    updates beyond s go to a pad column of the tile that no MFMA reads (only s > 8 needs a
+    //    loop, after the MFMAs of the last k-step);
+    //  * the tile being consumed is cleared in 16-column slices, slice ks during k-step ks (its
+    //    reads were issued one k-step earlier and LDS operations of a wave complete in order).
+    uint4 pa2[2][MT];
+    RowHash prh{0u, 0u, 0u};
+    uint32_t pr = 0;
+    const uint32_t pad_at = (uint32_t)((lane & 31) * PHI_LD + KC + (lane >> 5));
+    auto read_pa = [&](const uint16_t* tile, int ks, uint4 (&dst)[MT]) {
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+        dst[mt] = *reinterpret_cast<const uint4*>(tile + (mt * 32 + (lane & 31)) * PHI_LD + ks * 16 + kg * 8);
+    };
+    auto put_one = [&](uint16_t* tile, uint32_t i, bool real) {
+      tile[real ? __umul24(pr, (uint32_t)PHI_LD) + lane : pad_at] = (uint16_t)(((prh.signs >> i) << 15) | kOne);
+      pr = (pr + prh.stride) & (p.Br - 1);
+    };
+    auto fill_part = [&](int t1, uint16_t* tile, int ks) {
+      if (ks == 0) {
+        const uint32_t tg = (uint32_t)(z * T_stages + t1);  // stage among all kappa blocks
+        const uint32_t l = tg / rows_per_blk_stage;
+        prh = row_hash_pow2(s_bk[l], (tg % rows_per_blk_stage) * KC + lane, p.Br);
+        pr = prh.shift;
+      }
+      put_one(tile, 2u * ks, 2u * ks < p.s);
+      put_one(tile, 2u * ks + 1u, 2u * ks + 1u < p.s);
+    };
+    auto clear_slice = [&](uint16_t* tile, int ks) {
+#pragma unroll
+      for (int i = 0; i < MT; ++i) {  // RWV rows x 32 bytes = 2*RWV 16-byte units
+        const int unit = lane + 64 * i;
+        *reinterpret_cast<uint4*>(tile + (unit >> 1) * PHI_LD + ks * 16 + (unit & 1) * 8) = make_uint4(0, 0, 0, 0);
+      }
+    };
+    auto stage_out = [&](int t, auto par_tag, auto fetch_tag, auto fill_tag) {
+      constexpr int PAR = decltype(par_tag)::value;
+      constexpr int FETCH = decltype(fetch_tag)::value;
+      constexpr bool FILL = decltype(fill_tag)::value;
+      uint16_t* cur_tile = s_phi + (t & 1) * TILE;
+      uint16_t* fill_tile = s_phi + ((t + 1) & 1) * TILE;
+#pragma unroll
+      for (int ks = 0; ks < KSTEPS; ++ks) {
+        V(&cur)[8] = ld[(PAR * KSTEPS + ks) % PFD];
+        const bool fetch = FETCH == 2 || (FETCH == 1 && ks + PFD < KSTEPS);  // compile-time
+        uint4(&pa)[MT] = pa2[ks & 1];
+        uint4(&pn)[MT] = pa2[(ks + 1) & 1];
+        if constexpr (FILL) {
+          fill_part(t + 1, fill_tile, ks);
+          clear_slice(cur_tile, ks);
+        }
+        if (ks + 1 < KSTEPS) read_pa(cur_tile, ks + 1, pn);
+        else if constexpr (FILL) read_pa(fill_tile, 0, pn);
+        if constexpr (sizeof(T) == 2) {
+          uint4 op[4];
+          make_ops(cur, op);
+          if (fetch) issue(t * KSTEPS + ks + PFD, cur);
+#pragma unroll
+          for (int c = 0; c < 4; ++c)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) acc[mt][c] = mfma(pa[mt], op[c], acc[mt][c]);
+          if constexpr (MT == 4) {  // one wave per SIMD: spread the rest between the MFMAs
+            __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+#pragma unroll
+            for (int i = 0; i < 4 * MT; ++i) {
+              __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+              __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
+              __builtin_amdgcn_sched_group_barrier(0x090, 2, 0);
+            }
+          }
+        } else {
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            uint32_t xs[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+              xs[j] = c == 0 ? cur[j].x : c == 1 ? cur[j].y : c == 2 ? cur[j].z : cur[j].w;
+            uint4 hi, mid, lo;
+            split_ops(xs, hi, mid, lo);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+              acc[mt][c] = mfma(pa[mt], hi, acc[mt][c]);
+              acc[mt][c] = mfma(pa[mt], mid, acc[mt][c]);
+              acc[mt][c] = mfma(pa[mt], lo, acc[mt][c]);
+            }
+          }
+          if (fetch) issue(t * KSTEPS + ks + PFD, cur);
+        }
+        if (fetch) advance();
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if constexpr (FILL) {
+        if (p.s > 2u * KSTEPS) {  // rare: the remaining nonzeros, then re-read the first operands
+          for (uint32_t i = 2u * KSTEPS; i < p.s; ++i) put_one(fill_tile, i, true);
+          read_pa(fill_tile, 0, pa2[0]);
+        }
+      }
+    };
+
     // (the barrier inside setup_tables waits for outstanding loads, so none are issued before it)
     setup_tables();
+    if constexpr (!RAGGED) cursor_init();
 #pragma unroll
-    for (int i = 0; i < PFD; ++i) issue(i, ld[i]);
+    for (int i = 0; i < PFD; ++i) { issue(i, ld[i]); advance(); }
 #pragma unroll
     for (int part = 0; part < KSTEPS; ++part) produce(0, 0, part);
-    for (int t = 0; t + 1 < T_stages; ++t) stage(t, std::false_type{});
-    stage(T_stages - 1, std::true_type{});
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+    using I2 = std::integral_constant<int, 2>;
+    // (fp32 with two waves per SIMD has no registers to spare for the second operand set)
+    constexpr bool PIPE = !IN_STAT && (sizeof(T) == 2 || MT == 4);
+    auto run_stage = [&](int t, auto par_tag, auto fetch_tag, auto fill_tag) {
+      if constexpr (PIPE) stage_out(t, par_tag, fetch_tag, fill_tag);
+      else stage(t, par_tag, fetch_tag, fill_tag);
+    };
+    if constexpr (PIPE) read_pa(s_phi, 0, pa2[0]);
+    if constexpr (PFD <= KSTEPS) {
+      for (int t = 0; t + 1 < T_stages; ++t) run_stage(t, I0{}, I2{}, std::true_type{});
+      run_stage(T_stages - 1, I0{}, I1{}, std::false_type{});
+    } else {  // T_stages is even: the last two stages find all their loads already in flight
+      for (int t = 0; t + 2 < T_stages; t += 2) {
+        run_stage(t, I0{}, I2{}, std::true_type{});
+        run_stage(t + 1, I1{}, I2{}, std::true_type{});
+      }
+      run_stage(T_stages - 2, I0{}, I0{}, std::true_type{});
+      run_stage(T_stages - 1, I1{}, I0{}, std::false_type{});
+    }
   };
   const bool full_tile = ((int)jt + 1) * (WC * NCG) <= a.n;
   if (full_tile) body(std::false_type{}); else body(std::true_type{});
@@ -490,7 +645,7 @@ __global__ __launch_bounds__(256) void reduce_planes_kernel(const float* __restr
 struct Plan {
   bool ok = false;
   bool in_stat = false;
-  int mt = 0, nrg = 0, ncg = 0, zsplit = 1, stages = 0, run = 1, cpl = 4;
+  int mt = 0, nrg = 0, ncg = 0, zsplit = 1, stages = 0, run = 1, cpl = 4, pfx = 1;
   int64_t ldw = 0;
   int planes = 0;
   size_t lds = 0;
@@ -529,11 +684,24 @@ Plan make_plan(const SketchParams& p, const void* A, int64_t lda, int64_t n, fs_
   const bool can_out = tile_shape(p.Br, &mt_o, &nrg_o);
   if (!can_in && !can_out) return pl;
 
-  // IN-stationary row split: enough work-groups to fill 256 CUs a few times over
+  // IN-stationary row split: more work-groups fill the chip better, but every split adds kappa
+  // partial planes.  Pick the split with the smallest modelled time: A streamed at ~6 TB/s once
+  // there is a wave per SIMD (1024 of them), planes written at ~3.4 TB/s and read back at ~6 TB/s
+  // (rates measured on this kernel pair).
   int zs = 1;
-  while ((int64_t)p.M * col_tiles * zs < 1024 && zs < 16 && (p.Bc / (zs * 2)) % KC == 0 &&
-         p.Bc / (zs * 2) >= (uint32_t)KC)
-    zs *= 2;
+  {
+    const double a_bytes = (double)p.d * (double)n * esz;
+    const double waves_per_wg = pl.ncg * (can_in ? nrg_i : 1);
+    double best = 0;
+    for (int zc = 1; zc <= 16; zc *= 2) {
+      if (zc > 1 && ((p.Bc / zc) % KC != 0 || p.Bc / zc < (uint32_t)KC)) break;
+      const double waves = (double)p.M * col_tiles * zc * waves_per_wg;
+      const double plane_bytes = (double)zc * p.kappa * (double)p.k * (double)n * 4.0;
+      const double t = a_bytes / (6e12 * (waves < 1024 ? waves / 1024 : 1.0)) + plane_bytes / 3.4e12 +
+                       plane_bytes / 6e12;
+      if (zc == 1 || t < best) { best = t; zs = zc; }
+    }
+  }
   // workspace traffic (write + read of the partial planes) relative to reading A once
   const double rho = 2.0 * zs * p.kappa * (double)p.k * 4.0 / ((double)p.d * esz);
   const bool out_starved = (int64_t)p.M * col_tiles < 256;  // fewer output tiles than CUs
@@ -565,6 +733,10 @@ Plan make_plan(const SketchParams& p, const void* A, int64_t lda, int64_t n, fs_
     pl.stages = total_stages / zo;
     if (zo > 1) { pl.ldw = (n + 3) & ~(int64_t)3; pl.planes = zo; }
   }
+  // bf16 with one wave per SIMD (128-row tiles) has the registers for a ring twice as deep, and
+  // with a single wave nothing else hides the latency of A; the two-stage ring needs an even
+  // stage count.  (For fp32 the deeper ring measured no gain.)
+  if (pl.mt == 4 && dt == FS_BF16 && pl.stages % 2 == 0) pl.pfx = 2;
   pl.lds = lds_bytes(pl.mt, pl.nrg, pl.ncg, pl.run,
                      pl.run > 1 ? (size_t)(p.kappa + pl.run - 1) * p.Br * 256 * 4 : 0);
   pl.ok = pl.lds <= kLdsBudget;
@@ -588,15 +760,24 @@ template <typename T, bool IN_STAT>
 hipError_t launch_shape(const Plan& pl, const MfmaArgs& a, dim3 grid, hipStream_t st) {
 #define FS_GO(MT, NRG, NCG, RUN) \
   return go(mfma_kernel<T, MT, NRG, NCG, IN_STAT, RUN, 4>, grid, 64 * NRG * NCG * RUN, pl.lds, st, a)
+#define FS_GO4(NCG)                                                                            \
+  do {                                                                                         \
+    if constexpr (sizeof(T) == 2) {                                                            \
+      if (pl.pfx == 2)                                                                         \
+        return go(mfma_kernel<T, 4, 1, NCG, IN_STAT, 1, 4, 2>, grid, 64 * NCG, pl.lds, st, a); \
+    }                                                                                          \
+    return go(mfma_kernel<T, 4, 1, NCG, IN_STAT, 1, 4, 1>, grid, 64 * NCG, pl.lds, st, a);     \
+  } while (0)
   if constexpr (IN_STAT) {
     if (pl.run == 4) FS_GO(2, 1, 2, 4);
   }
   if (pl.ncg == 1) {
-    if (pl.mt == 1) FS_GO(1, 1, 1, 1); else if (pl.mt == 2) FS_GO(2, 1, 1, 1); else FS_GO(4, 1, 1, 1);
+    if (pl.mt == 1) FS_GO(1, 1, 1, 1); else if (pl.mt == 2) FS_GO(2, 1, 1, 1); else FS_GO4(1);
   } else {
-    if (pl.mt == 1) FS_GO(1, 1, 2, 1); else if (pl.mt == 2) FS_GO(2, 1, 2, 1); else FS_GO(4, 1, 2, 1);
+    if (pl.mt == 1) FS_GO(1, 1, 2, 1); else if (pl.mt == 2) FS_GO(2, 1, 2, 1); else FS_GO4(2);
   }
 #undef FS_GO
+#undef FS_GO4
 }
 
 }  // namespace

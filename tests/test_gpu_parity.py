@@ -105,6 +105,13 @@ SMALL = [
     ((65500, 8192, 64, 8, 8, 2), 300, 4, 0),        # the same in orbit-run mode, ragged tile
     ((7201, 512, 1024, 64, 8, 8), 264, 0, 0),       # the same in OUT-stationary mode
     ((1100, 72, 96, 6, 5, 3), 65, 0, 0),            # the same on the generic kernel only
+    ((16384, 1024, 2048, 128, 4, 8), 520, 0, 0),    # 128-row wave tiles: two full column tiles + ragged
+    ((8192, 1024, 512, 64, 4, 12), 300, 4, 0),      # OUT-stationary with s > 8 (tail of the pipelined fill)
+    ((8192, 1024, 512, 64, 4, 3), 256, 0, 0),       # odd s
+    ((4096, 1024, 128, 32, 8, 1), 256, 0, 0),       # s = 1, two stages per block
+    ((2048, 4096, 64, 128, 2, 32), 256, 0, 0),      # s = 32, one stage per block, Br = 128, two stages in all
+    ((2048, 4096, 64, 128, 3, 4), 256, 0, 0),       # the same with an odd stage count (shallow prefetch ring)
+    ((6144, 4096, 192, 128, 1, 4), 256, 0, 0),      # kappa = 1, 128 stacked rows, three stages
 ]
 
 
