@@ -147,22 +147,13 @@ void mfma_kernel(MfmaArgs a) {
     __syncthreads();
   };
 
-  // first row of A of global k-step kk (16 rows each) of this work-group; wave-uniform
-  auto row_of = [&](int kk) -> int64_t {
-    if (IN_STAT) {
-      return (int64_t)blk * p.Bc + (int64_t)z * T_stages * KC + (int64_t)kk * 16;
-    } else {
-      const uint32_t per_blk = p.Bc / 16;
-      const uint32_t kg_ = (uint32_t)(z * T_stages * KSTEPS + kk);  // k-step among all kappa blocks
-      const uint32_t l = kg_ / per_blk, kr = kg_ % per_blk;
-      const uint32_t hb = __builtin_amdgcn_readfirstlane(s_blk[l]);
-      return (int64_t)hb * p.Bc + (int64_t)kr * 16;
-    }
-  };
   const char* Abase = reinterpret_cast<const char*>(a.A);
   // per-lane byte offset of its first row inside a 16-row k-step (fits 32 bits: checked on
   // the host); the other 7 rows are reached through the scalar base
-  const uint32_t voff = (uint32_t)(((int64_t)(kg * 8) * a.lda + col0) * (int64_t)sizeof(T));
+  // (a lane whose columns all lie at or beyond n gets an offset outside every descriptor range
+  // instead, 2^31: its loads return 0 and move no data)
+  const uint32_t voff = col0 < a.n ? (uint32_t)(((int64_t)(kg * 8) * a.lda + col0) * (int64_t)sizeof(T))
+                                   : 0x80000000u;
   const int64_t row_bytes = a.lda * (int64_t)sizeof(T);
 
   f32x16 acc[MT][CPL];
@@ -224,9 +215,8 @@ void mfma_kernel(MfmaArgs a) {
     }
   };
 
-  // The main loop, once for full column tiles (unguarded vector loads) and once
-  // for the ragged last tile (guarded element loads); the choice is uniform per
-  // work-group.
+  // The main loop, once for full column tiles and once for the ragged last tile (the same
+  // vector loads, masked at the point of use); the choice is uniform per work-group.
   auto body = [&](auto ragged_tag) {
     constexpr bool RAGGED = decltype(ragged_tag)::value;
     V ld[PFD][8];
@@ -235,13 +225,17 @@ void mfma_kernel(MfmaArgs a) {
     // walks the rows, the lane offset (voff) selects row-in-k-step and column.
     // Rows at or beyond d (the zero padding of a partly filled last input block) lie outside
     // the descriptor's range, and out-of-range buffer loads return 0 without touching memory.
+    // The range ends with the last valid row's columns, rounded up to the 4-column vector: in the
+    // ragged tile a lane's vector may straddle column n; what it reads beyond n (the row's own
+    // padding, inside the same aligned 8/16-byte granule as a valid element) is masked to zero.
     auto make_rsrc = [&](int64_t first_row, int64_t nrows) {
       const int64_t valid = min(nrows, p.d - first_row);
-      const int64_t bytes = valid > 0 ? (valid - 1) * row_bytes + (int64_t)a.n * (int64_t)sizeof(T) : 0;
+      const int64_t ncols = ((int64_t)a.n + 3) & ~(int64_t)3;
+      const int64_t bytes = valid > 0 ? (valid - 1) * row_bytes + ncols * (int64_t)sizeof(T) : 0;
       return __builtin_amdgcn_make_buffer_rsrc(
           const_cast<char*>(Abase + first_row * row_bytes), 0, (int)bytes, 0x00020000);
     };
-    // Fetch cursor (unguarded path).  k-steps are issued strictly in order, so the OUT mode
+    // Fetch cursor.  k-steps are issued strictly in order, so the OUT mode
     // keeps (descriptor of the current input block, byte offset, k-step within the block) in
     // scalar registers and only rebuilds the descriptor when it crosses into the next block.
     __amdgpu_buffer_rsrc_t f_rs = make_rsrc(0, 0);
@@ -263,7 +257,7 @@ void mfma_kernel(MfmaArgs a) {
     // input block).  Kept apart from issue() so that it can sit at the end of a k-step and the
     // k-step stays one basic block.
     auto advance = [&]() {
-      if constexpr (!IN_STAT && !RAGGED) {
+      if constexpr (!IN_STAT) {
         f_so += 16u * (uint32_t)row_bytes;
         if (++f_kr == per_blk_k) {
           f_kr = 0;
@@ -276,23 +270,41 @@ void mfma_kernel(MfmaArgs a) {
       }
     };
     auto issue = [&](int kk, V (&dst)[8]) {
-      if constexpr (RAGGED) {
-        const int64_t row0 = row_of(kk);
-        const char* sb = Abase + row0 * row_bytes;
+      const __amdgpu_buffer_rsrc_t rs = f_rs;
+      const uint32_t so = IN_STAT ? (uint32_t)kk * 16u * (uint32_t)row_bytes : f_so;
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
-          dst[j] = load4_guarded<T, CPL>(reinterpret_cast<const T*>(sb + j * row_bytes + voff), col0,
-                                         row0 + kg * 8 + j < p.d ? a.n : 0);  // padding rows read as 0
+      for (int j = 0; j < 8; ++j) {
+        const uint32_t soj = so + (uint32_t)j * (uint32_t)row_bytes;
+        if constexpr (sizeof(V) == 8)
+          dst[j] = __builtin_bit_cast(V, __builtin_amdgcn_raw_buffer_load_b64(rs, voff, soj, 0));
+        else
+          dst[j] = __builtin_bit_cast(V, __builtin_amdgcn_raw_buffer_load_b128(rs, voff, soj, 0));
+      }
+    };
+    // Ragged tile: zero, at the point of use, the columns at or beyond n of what a lane loaded.
+    V cmask;
+    {
+      const int vc = a.n - col0;  // valid columns of this lane's vector (may be <= 0 or >= 4)
+      if constexpr (sizeof(V) == 8) {
+        cmask.x = vc >= 2 ? 0xFFFFFFFFu : vc == 1 ? 0x0000FFFFu : 0u;
+        cmask.y = vc >= 4 ? 0xFFFFFFFFu : vc == 3 ? 0x0000FFFFu : 0u;
       } else {
-        const __amdgpu_buffer_rsrc_t rs = f_rs;
-        const uint32_t so = IN_STAT ? (uint32_t)kk * 16u * (uint32_t)row_bytes : f_so;
+        cmask.x = vc >= 1 ? 0xFFFFFFFFu : 0u;
+        cmask.y = vc >= 2 ? 0xFFFFFFFFu : 0u;
+        cmask.z = vc >= 3 ? 0xFFFFFFFFu : 0u;
+        cmask.w = vc >= 4 ? 0xFFFFFFFFu : 0u;
+      }
+    }
+    auto mask_cur = [&](V (&cur)[8]) {
+      if constexpr (RAGGED) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-          const uint32_t soj = so + (uint32_t)j * (uint32_t)row_bytes;
-          if constexpr (sizeof(V) == 8)
-            dst[j] = __builtin_bit_cast(V, __builtin_amdgcn_raw_buffer_load_b64(rs, voff, soj, 0));
-          else
-            dst[j] = __builtin_bit_cast(V, __builtin_amdgcn_raw_buffer_load_b128(rs, voff, soj, 0));
+          cur[j].x &= cmask.x;
+          cur[j].y &= cmask.y;
+          if constexpr (sizeof(V) == 16) {
+            cur[j].z &= cmask.z;
+            cur[j].w &= cmask.w;
+          }
         }
       }
     };
@@ -319,6 +331,7 @@ void mfma_kernel(MfmaArgs a) {
 
         V(&cur)[8] = ld[(PAR * KSTEPS + ks) % PFD];
         const bool fetch = FETCH == 2 || (FETCH == 1 && ks + PFD < KSTEPS);  // compile-time
+        mask_cur(cur);
         if constexpr (sizeof(T) == 2) {
           uint4 op[4];
           make_ops(cur, op);
@@ -328,20 +341,26 @@ void mfma_kernel(MfmaArgs a) {
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) acc[mt][c] = mfma(pa[mt], op[c], acc[mt][c]);
         } else {
+          // two columns at a time, piece by piece: an accumulator is reused only after
+          // 2*MT other MFMAs (back-to-back dependent MFMAs stall the matrix pipe)
 #pragma unroll
-          for (int c = 0; c < 4; ++c) {
-            uint32_t xs[8];
+          for (int c = 0; c < 4; c += 2) {
+            uint4 pc[2][3];
 #pragma unroll
-            for (int j = 0; j < 8; ++j)
-              xs[j] = c == 0 ? cur[j].x : c == 1 ? cur[j].y : c == 2 ? cur[j].z : cur[j].w;
-            uint4 hi, mid, lo;
-            split_ops(xs, hi, mid, lo);
+            for (int cc = 0; cc < 2; ++cc) {
+              uint32_t xs[8];
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-              acc[mt][c] = mfma(pa[mt], hi, acc[mt][c]);
-              acc[mt][c] = mfma(pa[mt], mid, acc[mt][c]);
-              acc[mt][c] = mfma(pa[mt], lo, acc[mt][c]);
+              for (int j = 0; j < 8; ++j)
+                xs[j] = c + cc == 0 ? cur[j].x : c + cc == 1 ? cur[j].y : c + cc == 2 ? cur[j].z : cur[j].w;
+              split_ops(xs, pc[cc][0], pc[cc][1], pc[cc][2]);
             }
+#pragma unroll
+            for (int piece = 0; piece < 3; ++piece)
+#pragma unroll
+              for (int cc = 0; cc < 2; ++cc)
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+                  acc[mt][c + cc] = mfma(pa[mt], pc[cc][piece], acc[mt][c + cc]);
           }
           if (fetch) issue(t * KSTEPS + ks + PFD, cur);
         }
@@ -401,6 +420,7 @@ void mfma_kernel(MfmaArgs a) {
       for (int ks = 0; ks < KSTEPS; ++ks) {
         V(&cur)[8] = ld[(PAR * KSTEPS + ks) % PFD];
         const bool fetch = FETCH == 2 || (FETCH == 1 && ks + PFD < KSTEPS);  // compile-time
+        mask_cur(cur);
         uint4(&pa)[MT] = pa2[ks & 1];
         uint4(&pn)[MT] = pa2[(ks + 1) & 1];
         if constexpr (FILL) {
@@ -427,20 +447,26 @@ void mfma_kernel(MfmaArgs a) {
             }
           }
         } else {
+          // two columns at a time, piece by piece: an accumulator is reused only after
+          // 2*MT other MFMAs (back-to-back dependent MFMAs stall the matrix pipe)
 #pragma unroll
-          for (int c = 0; c < 4; ++c) {
-            uint32_t xs[8];
+          for (int c = 0; c < 4; c += 2) {
+            uint4 pc[2][3];
 #pragma unroll
-            for (int j = 0; j < 8; ++j)
-              xs[j] = c == 0 ? cur[j].x : c == 1 ? cur[j].y : c == 2 ? cur[j].z : cur[j].w;
-            uint4 hi, mid, lo;
-            split_ops(xs, hi, mid, lo);
+            for (int cc = 0; cc < 2; ++cc) {
+              uint32_t xs[8];
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-              acc[mt][c] = mfma(pa[mt], hi, acc[mt][c]);
-              acc[mt][c] = mfma(pa[mt], mid, acc[mt][c]);
-              acc[mt][c] = mfma(pa[mt], lo, acc[mt][c]);
+              for (int j = 0; j < 8; ++j)
+                xs[j] = c + cc == 0 ? cur[j].x : c + cc == 1 ? cur[j].y : c + cc == 2 ? cur[j].z : cur[j].w;
+              split_ops(xs, pc[cc][0], pc[cc][1], pc[cc][2]);
             }
+#pragma unroll
+            for (int piece = 0; piece < 3; ++piece)
+#pragma unroll
+              for (int cc = 0; cc < 2; ++cc)
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt)
+                  acc[mt][c + cc] = mfma(pa[mt], pc[cc][piece], acc[mt][c + cc]);
           }
           if (fetch) issue(t * KSTEPS + ks + PFD, cur);
         }
@@ -457,7 +483,12 @@ void mfma_kernel(MfmaArgs a) {
 
     // (the barrier inside setup_tables waits for outstanding loads, so none are issued before it)
     setup_tables();
-    if constexpr (!RAGGED) cursor_init();
+    if constexpr (RAGGED) {
+      // a wave whose 128 columns all lie at or beyond n has nothing to add (its accumulators
+      // stay zero and the epilogue stores nothing); it only had to take part in the barrier
+      if ((int)jt * (WC * NCG) + cg * WC >= a.n) return;
+    }
+    cursor_init();
 #pragma unroll
     for (int i = 0; i < PFD; ++i) { issue(i, ld[i]); advance(); }
 #pragma unroll

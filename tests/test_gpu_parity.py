@@ -125,6 +125,8 @@ def test_apply_matches_oracle(case, dtype, variant):
     d, k = params[0], params[1]
     g = torch.Generator(device=DEV).manual_seed(n + d)
     Abuf = torch.randn((d, n + pa), generator=g, device=DEV).to(dtype)
+    if pa:
+        Abuf[:, n:] = float("nan")  # the padding between n and lda must never reach the result
     A = Abuf[:, :n]
     obuf = torch.full((k, n + po), float("nan"), device=DEV, dtype=dtype)
     sk = make_sketch(params, seed, variant)
