@@ -368,6 +368,41 @@ def test_apply_on_a_side_stream_and_profile_brackets():
         sk.profile_end()                    # not profiling any more
 
 
+@pytest.mark.parametrize("params,n,chunk", [
+    ((32768, 64, 4096, 8, 8, 2), 1024, 256),     # IN-stationary with partial planes + reduce kernel
+    ((65536, 8192, 64, 8, 8, 2), 512, 256),      # orbit-run mode
+    ((8192, 1024, 512, 64, 4, 8), 512, 512),     # OUT-stationary, direct store
+])
+def test_chunked_apply_replays_from_a_hip_graph(params, n, chunk):
+    """The apply only enqueues kernels once a handle has run once (workspace and orbit table
+    exist), so a chunk loop can be captured into a HIP graph.  Several replays, with eager work
+    and synchronisations between them, must each reproduce the eager result bit for bit."""
+    print("graph", params, flush=True)
+    d, k = params[0], params[1]
+    g = torch.Generator(device=DEV).manual_seed(11)
+    A = torch.randn((d, n), generator=g, device=DEV).to(torch.bfloat16)
+    sk = B.Sketch(*params, seed=2)
+    eager = torch.empty((k, n), device=DEV, dtype=A.dtype)
+    for c in range(0, n, chunk):
+        sk.apply(A[:, c:c + chunk], eager[:, c:c + chunk])
+    torch.cuda.synchronize()
+    out = torch.zeros_like(eager)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for c in range(0, n, chunk):
+            sk.apply(A[:, c:c + chunk], out[:, c:c + chunk])
+    for rep in range(3):
+        out.zero_()
+        scratch = sk.apply(A[:, :chunk])          # eager work of the same handle in between
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), f"replay {rep} differs from the eager result"
+        assert torch.equal(scratch, eager[:, :chunk])
+    ref = O.apply(oracle_csc(params, 2), host64(A))
+    check(out, ref, torch.bfloat16, "graph replay")
+
+
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
 def test_variants_agree_with_each_other(dtype):
     """Generic and MFMA paths implement the same S: they agree to accumulation rounding."""
