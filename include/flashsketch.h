@@ -28,7 +28,11 @@
  *   Alignment  A and out must be aligned to their element size.  The fast
  *              kernels additionally want 16-byte aligned bases and
  *              lda*sizeof(elt) a multiple of 16; otherwise a slower generic
- *              kernel is used (never an error).
+ *              kernel is used (never an error).  When n is not a multiple of
+ *              4 the fast kernels load, and discard, up to 3 elements of a
+ *              row's own padding (columns n .. lda-1, inside the aligned
+ *              4-element group of the row's last valid element); their
+ *              values, NaN included, never reach the result.
  *   Streams    `stream` is a hipStream_t passed as void* (NULL = default
  *              stream).  Calls enqueue work and return; they never synchronise.
  *              A handle must not be used from two streams at the same time
