@@ -164,6 +164,7 @@ def main():
 
     if not args.no_extra:
         rec["extra"] = extra_measurements(torch, B, W, dev, cfg.name, with_oracle=not args.no_cpu)
+        rec["extra"]["rows_layout"] = rows_layout_measurement(torch, B, cfg, A, out)
     print(json.dumps(rec))
 
 
@@ -205,6 +206,41 @@ def extra_measurements(torch, B, W, dev, skip, with_oracle):
         for n in W.WIDE_NS:
             res[f"wide_n{n}"] = one(dataclasses.replace(base, n=n), A[:, :n].contiguous())
         del A
+    return res
+
+
+def rows_layout_measurement(torch, B, cfg, A, out, steps=10):
+    """The same workload held examples-as-rows (G = A^T, n x d; out^T, n x k): fs_sketch_apply_rows
+    on the same chunks of `chunk` examples, once with the packed row stride ld = d and once with
+    ld = d + 64 elements (a power-of-two stride maps all rows of a tile to one HBM channel).  The
+    result is compared with the column-layout output of the main measurement."""
+    res = {}
+    for pad in (64, 0):
+        try:
+            Gbuf = torch.empty((cfg.n, cfg.d + pad), device=A.device, dtype=A.dtype)
+            G = Gbuf[:, :cfg.d]
+            G.copy_(A.t())
+            sk = B.Sketch(*cfg.params, seed=cfg.sketch_seed)
+            o = torch.empty((cfg.n, cfg.k), device=A.device, dtype=A.dtype)
+            w = cfg.chunk if cfg.chunk else cfg.n
+
+            def step():
+                for c in range(0, cfg.n, w):
+                    sk.apply_rows(G[c:c + w], o[c:c + w])
+            step(); step()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                step()
+            torch.cuda.synchronize()
+            t = (time.perf_counter() - t0) / steps
+            diff = (o.t().float() - out.float()).norm() / out.float().norm()
+            res[f"ld_d_plus_{pad}"] = {"ms_per_step": t * 1e3, "GBps_A": cfg.a_bytes / t / 1e9,
+                                       "rel_diff_vs_column_layout": float(diff)}
+            sk.close()
+            del Gbuf, G, o
+        except B.FlashSketchError as e:
+            res[f"ld_d_plus_{pad}"] = {"error": str(e)}
     return res
 
 

@@ -139,6 +139,21 @@ fs_status fs_sketch_apply(fs_sketch_t h, const void* A, int64_t lda, int64_t n, 
 fs_status fs_sketch_apply_ld(fs_sketch_t h, const void* A, int64_t lda, int64_t n, void* out,
                              int64_t ldo, fs_dtype dtype, void* stream);
 
+/* The same sketch for inputs held examples-as-rows: G is n x d row-major (ld = ldg >= d,
+ * every row one vector to sketch, as a pipeline that compresses per-example gradients holds
+ * them: Section 7, "End-to-end ML: GraSS for Data Attribution", and Appendix F) and
+ * out (n x k, ld = ldo >= k) = G S^T, i.e. out[i, :] = S G[i, :] -- the transpose of what
+ * fs_sketch_apply_ld computes on G^T.  FS_KIND_BLOCKPERM only.  This entry point has only
+ * the matrix-core kernel: it needs a power-of-two Br with kappa*Br in {32, 64, 128}, Bc a
+ * multiple of 64 that divides d, a 16-byte aligned G with ldg*sizeof(elt) a multiple of 16
+ * and 128*ldg*sizeof(elt) < 2^31; otherwise FS_ERR_UNSUPPORTED (nothing is launched).
+ * n == 0 is FS_OK.  Errors: NULL handle/G/out, n < 0, ldg < d, ldo < k, unknown dtype.
+ * Workspace: kappa (times a row split) planes of n x k floats, grown or attached as for
+ * fs_sketch_apply; fs_sketch_rows_workspace_bytes gives its size for a well-aligned call. */
+fs_status fs_sketch_apply_rows(fs_sketch_t h, const void* G, int64_t ldg, int64_t n, void* out,
+                               int64_t ldo, fs_dtype dtype, void* stream);
+fs_status fs_sketch_rows_workspace_bytes(fs_sketch_t h, int64_t n, fs_dtype dtype, size_t* bytes);
+
 /* Materialise the nonzeros of S on the device (BLOCKPERM / SJLT_SCATTER):
  * rows[c*kappa*s + (l-1)*s + i] = global output row, signs[...] = +1/-1, for
  * column c of S, wiring slot l (the l with f^l(g) = c / Bc) and update i.

@@ -231,6 +231,13 @@ def apply(S: sp.csc_matrix, A) -> np.ndarray:
     return np.asarray(S @ np.asarray(A, dtype=np.float64))
 
 
+def apply_rows(S: sp.csc_matrix, G) -> np.ndarray:
+    """The same map for vectors held as rows: out[i, :] = S G[i, :], i.e. out = G S^T (float64).
+    (The layout of a per-example-gradient pipeline, Section 7 "GraSS for Data Attribution".)"""
+    G64 = np.asarray(G, dtype=np.float64)
+    return np.ascontiguousarray(np.asarray(S @ G64.T).T)
+
+
 def dense_by_loops(p: Params, seed: int) -> np.ndarray:
     """S as a dense array, one scalar at a time (tiny sizes only).
 

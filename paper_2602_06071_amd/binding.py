@@ -22,6 +22,7 @@ SYMBOLS = [
     "fs_sketch_export", "fs_sketch_export_dense", "fs_sketch_info", "fs_sketch_workspace_bytes",
     "fs_sketch_set_workspace", "fs_sketch_set_variant", "fs_sketch_destroy", "fs_status_string",
     "fs_sketch_profile_begin", "fs_sketch_profile_end",
+    "fs_sketch_apply_rows", "fs_sketch_rows_workspace_bytes",
 ]
 
 
@@ -55,6 +56,8 @@ def _load() -> C.CDLL:
     L.fs_sketch_create_kind.argtypes = [C.POINTER(vp), C.c_int, i64, i64, i32, i32, i32, i32, u64]
     L.fs_sketch_apply.argtypes = [vp, vp, i64, i64, vp, C.c_int, vp]
     L.fs_sketch_apply_ld.argtypes = [vp, vp, i64, i64, vp, i64, C.c_int, vp]
+    L.fs_sketch_apply_rows.argtypes = [vp, vp, i64, i64, vp, i64, C.c_int, vp]
+    L.fs_sketch_rows_workspace_bytes.argtypes = [vp, i64, C.c_int, C.POINTER(C.c_size_t)]
     L.fs_sketch_export.argtypes = [vp, vp, vp, vp]
     L.fs_sketch_export_dense.argtypes = [vp, vp, vp]
     L.fs_sketch_info.argtypes = [vp, C.POINTER(fs_info)]
@@ -156,6 +159,29 @@ class Sketch:
                                       out.stride(0), _dtype_code(A), _stream_ptr(stream)),
                "fs_sketch_apply_ld")
         return out
+
+    def apply_rows(self, G: torch.Tensor, out: torch.Tensor | None = None, stream=None) -> torch.Tensor:
+        """out (n x k) = G @ S^T for a 2-D row-major G (n x d, unit column stride): every row of G
+        is one vector to sketch."""
+        if G.dim() != 2 or G.shape[1] != self.d or G.stride(1) != 1:
+            raise ValueError("G must be n x d with contiguous rows")
+        n = G.shape[0]
+        if out is None:
+            out = torch.empty((n, self.k), dtype=G.dtype, device=G.device)
+        if out.shape != (n, self.k) or out.dtype != G.dtype or out.stride(1) != 1:
+            raise ValueError("out must be n x k, same dtype, contiguous rows")
+        _check(lib.fs_sketch_apply_rows(self._h, G.data_ptr(), G.stride(0) if n > 1 else max(G.stride(0), self.d),
+                                        n, out.data_ptr(), out.stride(0) if n > 1 else max(out.stride(0), self.k),
+                                        _dtype_code(G), _stream_ptr(stream)),
+               "fs_sketch_apply_rows")
+        return out
+
+    def rows_workspace_bytes(self, n: int, dtype: torch.dtype) -> int:
+        out = C.c_size_t()
+        code = FS_F32 if dtype == torch.float32 else FS_BF16
+        _check(lib.fs_sketch_rows_workspace_bytes(self._h, n, code, C.byref(out)),
+               "fs_sketch_rows_workspace_bytes")
+        return out.value
 
     def export(self, device="cuda", stream=None):
         i = self.info()

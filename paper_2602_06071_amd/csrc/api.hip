@@ -338,6 +338,43 @@ fs_status fs_sketch_apply_ld(fs_sketch_t h, const void* A, int64_t lda, int64_t 
   return FS_OK;
 }
 
+fs_status fs_sketch_apply_rows(fs_sketch_t h, const void* G, int64_t ldg, int64_t n, void* out,
+                               int64_t ldo, fs_dtype dt, void* stream) {
+  if (!h || n < 0 || (dt != FS_F32 && dt != FS_BF16)) return FS_ERR_INVALID_ARG;
+  if (n == 0) return FS_OK;
+  if (!G || !out || ldg < h->p.d || ldo < h->p.k) return FS_ERR_INVALID_ARG;
+  if (n > 0x7fffffff || ldg > ((int64_t)1 << 40) || ldo > ((int64_t)1 << 40)) return FS_ERR_INVALID_ARG;
+  const size_t esz = dt == FS_F32 ? 4 : 2;
+  if ((uintptr_t)G % esz || (uintptr_t)out % esz) return FS_ERR_INVALID_ARG;
+  if (h->kind != FS_KIND_BLOCKPERM) return FS_ERR_UNSUPPORTED;
+  if (!fs::rows_supported(h->p, G, ldg, n, dt)) return FS_ERR_UNSUPPORTED;
+  hipStream_t st = (hipStream_t)stream;
+  fs_status rc = ensure_workspace(h, fs::rows_workspace_bytes(h->p, G, ldg, n, dt));
+  if (rc != FS_OK) return rc;
+  fs::EventPair ev;
+  if (h->profiling && h->prof_used < (int)h->prof_start.size()) {
+    ev.start = h->prof_start[h->prof_used];
+    ev.stop = h->prof_stop[h->prof_used];
+    ++h->prof_used;
+  }
+  const hipError_t e = fs::launch_rows(h->p, G, ldg, n, out, ldo, dt, h->ws, st, ev);
+  h->last_variant = FS_VARIANT_MFMA;
+  h->last_mode = 2;
+  if (e != hipSuccess) return hip_fail(h, e);
+  return FS_OK;
+}
+
+fs_status fs_sketch_rows_workspace_bytes(fs_sketch_t h, int64_t n, fs_dtype dt, size_t* bytes) {
+  if (!h || !bytes || n < 0 || (dt != FS_F32 && dt != FS_BF16)) return FS_ERR_INVALID_ARG;
+  *bytes = 0;
+  if (n == 0 || h->kind != FS_KIND_BLOCKPERM) return FS_OK;
+  const size_t esz = dt == FS_F32 ? 4 : 2;
+  const int64_t ld = (h->p.d + 7) & ~(int64_t)7;  // a well-aligned call: packed rows rounded to 16 bytes
+  if (128 * ld * (int64_t)esz >= ((int64_t)1 << 31)) return FS_OK;
+  *bytes = fs::rows_workspace_bytes(h->p, (const void*)(uintptr_t)256, ld, n, dt);
+  return FS_OK;
+}
+
 fs_status fs_sketch_apply(fs_sketch_t h, const void* A, int64_t lda, int64_t n, void* out,
                           fs_dtype dt, void* stream) {
   return fs_sketch_apply_ld(h, A, lda, n, out, n, dt, stream);

@@ -403,6 +403,80 @@ def test_chunked_apply_replays_from_a_hip_graph(params, n, chunk):
     check(out, ref, torch.bfloat16, "graph replay")
 
 
+# ------------------------------------------ examples-as-rows layout -------
+ROWS = [
+    # params (d,k,Bc,Br,kappa,s), n examples, ldg pad, ldo pad
+    ((4096, 256, 512, 32, 2, 4), 300, 0, 0),        # tiny config: 64 stacked rows, ragged example tile
+    ((4096, 256, 512, 32, 2, 4), 128, 8, 4),        # padded leading dimensions
+    ((32768, 64, 4096, 8, 8, 2), 256, 0, 0),        # gradient-config blocks
+    ((32768, 64, 4096, 8, 8, 2), 5, 0, 0),          # a handful of examples
+    ((16384, 256, 2048, 32, 4, 4), 72, 0, 0),       # tall-config blocks: 128 stacked rows
+    ((8192, 512, 1024, 64, 2, 8), 130, 0, 0),       # mid-config blocks, kappa = 2
+    ((2048, 1024, 64, 32, 1, 1), 33, 0, 0),         # kappa = 1, one stage per block, s = 1
+    ((65536, 8192, 64, 8, 8, 2), 64, 0, 0),         # M = 1024
+]
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@pytest.mark.parametrize("case", ROWS, ids=lambda c: f"{c[0]}-n{c[1]}")
+def test_apply_rows_matches_oracle(case, dtype):
+    params, n, pg, po = case
+    print("rows", params, n, dtype, flush=True)
+    d, k = params[0], params[1]
+    g = torch.Generator(device=DEV).manual_seed(n + k)
+    Gbuf = torch.randn((n, d + pg), generator=g, device=DEV).to(dtype)
+    if pg:
+        Gbuf[:, d:] = float("nan")
+    G = Gbuf[:, :d]
+    obuf = torch.full((n, k + po), float("nan"), device=DEV, dtype=dtype)
+    sk = B.Sketch(*params, seed=9)
+    sk.apply_rows(G, obuf[:, :k])
+    torch.cuda.synchronize()
+    ref = O.apply_rows(oracle_csc(params, 9), host64(G))
+    check(obuf[:, :k], ref, dtype, "apply_rows")
+    if po:
+        assert torch.isnan(obuf[:, k:].float()).all(), "wrote outside the k output columns"
+    tol = (2e-5 if dtype == torch.float32 else 8e-3)
+    diff = np.abs(host64(obuf[:, :k]) - ref)
+    assert (diff <= tol * (np.abs(ref) + np.sqrt((ref ** 2).mean()))).all()
+    # and it is the transpose of the column-layout apply, to rounding
+    colwise = sk.apply(G.t().contiguous())
+    torch.cuda.synchronize()
+    check(colwise.t(), ref, dtype, "column layout on the transpose")
+
+
+def test_apply_rows_one_hot_rows_reproduce_columns_exactly():
+    params = (32768, 64, 4096, 8, 8, 2)  # kappa*s = 16: the scale is a power of two
+    d, k = params[0], params[1]
+    rng = np.random.default_rng(2)
+    cols = np.unique(np.r_[0, d - 1, 4095, 4096, rng.integers(0, d, 60)])
+    G = torch.zeros((len(cols), d), device=DEV, dtype=torch.bfloat16)
+    G[torch.arange(len(cols), device=DEV), torch.from_numpy(cols).to(DEV)] = 1.0
+    sk = B.Sketch(*params, seed=0)
+    out = sk.apply_rows(G)
+    torch.cuda.synchronize()
+    want = oracle_csc(params, 0)[:, cols].toarray().T
+    assert np.array_equal(host64(out), want)
+
+
+def test_apply_rows_unsupported_shapes_report_unsupported():
+    G = torch.zeros((4, 8192), device=DEV)
+    for params in [(8192, 1024, 512, 64, 4, 8),      # kappa*Br = 256
+                   (8192, 512, 96 * 0 + 1024, 64, 1, 8)]:   # fine shape, checked below with a bad stride
+        sk = B.Sketch(*params, seed=0)
+        if params[4] * params[3] > 128:
+            with pytest.raises(B.FlashSketchError) as e:
+                sk.apply_rows(G)
+            assert e.value.status == 2
+        else:
+            sk.apply_rows(G)  # supported
+            odd = torch.zeros((4, 8192 + 2), device=DEV)[:, :8192]  # row stride not a multiple of 16 bytes
+            with pytest.raises(B.FlashSketchError) as e:
+                sk.apply_rows(odd)
+            assert e.value.status == 2
+    torch.cuda.synchronize()
+
+
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
 def test_variants_agree_with_each_other(dtype):
     """Generic and MFMA paths implement the same S: they agree to accumulation rounding."""

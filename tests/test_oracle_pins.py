@@ -291,6 +291,24 @@ def test_one_hot_and_linearity():
                                rtol=1e-12, atol=1e-12)
 
 
+def test_rows_layout_is_the_same_map_row_by_row():
+    """apply_rows: vectors held as rows.  Pinned by brute force, one row at a time, against the
+    scalar-loop dense S (not against apply), and by one-hot rows reproducing columns of S."""
+    p = O.Params(96, 24, 32, 8, 2, 2)
+    S = O.build_csc(p, 5)
+    D = O.dense_by_loops(p, 5)
+    rng = np.random.default_rng(3)
+    G = rng.standard_normal((7, p.d))
+    out = O.apply_rows(S, G)
+    assert out.shape == (7, p.k)
+    for i in range(7):
+        want = np.array([sum(D[r, c] * G[i, c] for c in range(p.d)) for r in range(p.k)])
+        np.testing.assert_allclose(out[i], want, rtol=1e-12, atol=1e-12)
+    E = np.zeros((3, p.d))
+    E[[0, 1, 2], [0, 40, 95]] = 1.0
+    np.testing.assert_array_equal(O.apply_rows(S, E), D[:, [0, 40, 95]].T)
+
+
 # ---------------------------------------------------------------- P10 -----
 @pytest.mark.parametrize("kappa", [1, 2, 4, 8])
 def test_coherence_bounds(kappa):
