@@ -115,4 +115,21 @@ def test_apply_argument_errors_before_any_hip_call():
     assert L.fs_sketch_workspace_bytes(h, 0, 0, C.byref(out)) == 0 and out.value == 0
     assert L.fs_sketch_workspace_bytes(h, -1, 0, C.byref(out)) == 1
     assert L.fs_status_string(0) == b"ok" and L.fs_status_string(1) == b"invalid argument"
+    # examples-as-rows entry point: G is n x 4096 (ldg >= d), out is n x 256 (ldo >= k)
+    assert L.fs_sketch_apply_rows(None, buf, 4096, 8, buf, 256, 0, None) == 1
+    assert L.fs_sketch_apply_rows(h, buf, 4096, 0, buf, 256, 0, None) == 0    # n = 0
+    assert L.fs_sketch_apply_rows(h, None, 4096, 8, buf, 256, 0, None) == 1   # NULL G
+    assert L.fs_sketch_apply_rows(h, buf, 4096, 8, None, 256, 0, None) == 1   # NULL out
+    assert L.fs_sketch_apply_rows(h, buf, 4095, 8, buf, 256, 0, None) == 1    # ldg < d
+    assert L.fs_sketch_apply_rows(h, buf, 4096, 8, buf, 255, 0, None) == 1    # ldo < k
+    assert L.fs_sketch_apply_rows(h, buf, 4096, -1, buf, 256, 0, None) == 1   # n < 0
+    assert L.fs_sketch_apply_rows(h, buf, 4096, 8, buf, 256, 7, None) == 1    # unknown dtype
+    assert L.fs_sketch_apply_rows(h, buf, 4098, 8, buf, 256, 0, None) == 2    # rows not 16-byte aligned
+    assert L.fs_sketch_rows_workspace_bytes(h, 8, 0, C.byref(out)) == 0
+    one_set = 2 * 8 * 256 * 4                                                 # kappa planes of n x k floats
+    assert out.value >= one_set and out.value % one_set == 0                  # times the row split
+    assert L.fs_sketch_rows_workspace_bytes(h, -1, 0, C.byref(out)) == 1
     sk.close()
+    big = B.Sketch(8192, 1024, 512, 64, 4, 8)                                 # kappa*Br = 256
+    assert L.fs_sketch_apply_rows(big._h, buf, 8192, 8, buf, 1024, 0, None) == 2
+    big.close()

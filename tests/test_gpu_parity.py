@@ -325,6 +325,29 @@ def test_full_config_grad_chunked_sampled():
     _sampled_parity(cfg, A, out, ncols=6)
 
 
+def test_full_config_grad_rows_layout_sampled():
+    """The same 8 GiB input held examples-as-rows (row stride d + 64 elements), applied in four
+    chunks of 256 examples; the oracle on a sample of examples."""
+    cfg = W.CONFIGS["grad"]
+    print("full grad, rows layout", flush=True)
+    A = W.make_input(cfg, DEV)
+    Gbuf = torch.empty((cfg.n, cfg.d + 64), device=DEV, dtype=cfg.dtype)
+    G = Gbuf[:, :cfg.d]
+    G.copy_(A.t())
+    del A
+    sk = B.Sketch(*cfg.params, seed=cfg.sketch_seed)
+    out = torch.empty((cfg.n, cfg.k), device=DEV, dtype=cfg.dtype)
+    for c in range(0, cfg.n, cfg.chunk):
+        sk.apply_rows(G[c:c + cfg.chunk], out[c:c + cfg.chunk])
+    torch.cuda.synchronize()
+    print("  applied; oracle on sampled examples", flush=True)
+    rng = np.random.default_rng(0)
+    ex = np.unique(np.r_[0, cfg.n - 1, rng.integers(0, cfg.n, 6)])
+    idx = torch.from_numpy(ex).to(DEV)
+    ref = O.apply_rows(oracle_csc(cfg.params, cfg.sketch_seed), host64(G[idx]))
+    check(out[idx], ref, cfg.dtype, "grad rows layout, sampled examples")
+
+
 # ------------------------------------------------ boundary behaviour ------
 def test_caller_workspace_and_too_small_workspace():
     params, n = (65536, 8192, 64, 8, 8, 2), 256
