@@ -13,6 +13,7 @@ from __future__ import annotations
 
 import argparse
 import dataclasses
+import functools
 import json
 import os
 import sys
@@ -35,6 +36,10 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="grad", choices=["tiny", "mid", "tall", "wide", "grad"])
     ap.add_argument("--variant", default="auto", choices=["auto", "generic", "mfma"])
+    ap.add_argument("--layout", default="cols", choices=["cols", "rows"],
+                    help="cols: A is d x n, vectors are columns (the default, the metric's workload); "
+                         "rows: the same data held n x d, vectors are rows (fs_sketch_apply_rows)")
+    ap.add_argument("--ld-pad", type=int, default=64, help="rows layout: row stride = d + this many elements")
     ap.add_argument("--no-extra", action="store_true", help="skip the side measurements")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     return ap.parse_args()
@@ -45,19 +50,24 @@ def chunks_of(cfg):
     return [(c, min(cfg.n, c + w)) for c in range(0, cfg.n, w)]
 
 
-def run_steps(sk, A, out, cfg, steps):
+def run_steps(sk, A, out, cfg, steps, rows=False):
     for _ in range(steps):
         for c0, c1 in chunks_of(cfg):
-            sk.apply(A[:, c0:c1], out[:, c0:c1])
+            if rows:
+                sk.apply_rows(A[c0:c1], out[c0:c1])
+            else:
+                sk.apply(A[:, c0:c1], out[:, c0:c1])
 
 
-def time_workload(torch, B, cfg, A, variant, steps, warmup, kind=None, sketch_params=None):
-    """Wall-clock over `steps` steps plus HIP-event durations of the dominant kernel."""
+def time_workload(torch, B, cfg, A, variant, steps, warmup, kind=None, sketch_params=None, rows=False):
+    """Wall-clock over `steps` steps plus HIP-event durations of the dominant kernel.
+    rows: A is the n x d matrix of the examples-as-rows layout and out is n x k."""
     params = sketch_params or cfg.params
     sk = B.Sketch(*params, seed=cfg.sketch_seed, kind=B.KIND_BLOCKPERM if kind is None else kind)
     if kind is None:
         sk.set_variant({"auto": B.VARIANT_AUTO, "generic": B.VARIANT_GENERIC, "mfma": B.VARIANT_MFMA}[variant])
-    out = torch.empty((cfg.k, cfg.n), device=A.device, dtype=cfg.dtype)
+    out = torch.empty((cfg.n, cfg.k) if rows else (cfg.k, cfg.n), device=A.device, dtype=cfg.dtype)
+    run_steps = functools.partial(globals()["run_steps"], rows=rows)
     run_steps(sk, A, out, cfg, warmup)
     torch.cuda.synchronize()
     # HIP-event brackets around the dominant kernel on the last two timed steps only: every
@@ -121,7 +131,15 @@ def main():
     A = W.make_input(cfg, dev)
     torch.cuda.synchronize()
 
-    sec_per_step, kernel_ms, used, out = time_workload(torch, B, cfg, A, args.variant, args.steps, args.warmup)
+    rows = args.layout == "rows"
+    if rows:  # the same values, one example per row, row stride d + ld_pad elements
+        Gbuf = torch.empty((cfg.n, cfg.d + args.ld_pad), device=dev, dtype=cfg.dtype)
+        Gbuf[:, :cfg.d].copy_(A.t())
+        del A
+        A = Gbuf[:, :cfg.d]
+        torch.cuda.synchronize()
+    sec_per_step, kernel_ms, used, out = time_workload(torch, B, cfg, A, args.variant, args.steps, args.warmup,
+                                                       rows=rows)
     n_launch = len(chunks_of(cfg))
     cols_per_launch = cfg.n // n_launch
     # algorithmic bytes of one launch: read its columns of A once, write its columns of SA once
@@ -142,14 +160,15 @@ def main():
         "config": {
             "workload": f"{cfg.name}: A {cfg.d}x{cfg.n} {'bf16' if cfg.elt == 2 else 'fp32'}, k={cfg.k}, "
                         f"Bc={cfg.Bc}, Br={cfg.Br}, s={cfg.s}, kappa={cfg.kappa}, "
-                        f"{n_launch} launch(es) of {cols_per_launch} columns per step",
+                        f"{n_launch} launch(es) of {cols_per_launch} columns per step"
+                        + (f"; held examples-as-rows ({cfg.n} x {cfg.d}, row stride d+{args.ld_pad})" if rows else ""),
             "variant": {1: "generic", 2: "mfma"}.get(used, str(used)),
             "accumulate": "fp32",
         },
         "roofline": {
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBPS,
-            "traffic": MEASURED_TRAFFIC.get((cfg.name, {1: "generic", 2: "mfma"}.get(used))),
+            "traffic": None if rows else MEASURED_TRAFFIC.get((cfg.name, {1: "generic", 2: "mfma"}.get(used))),
             "kernel_ms_avg": avg_kernel_s * 1e3, "launches_timed": len(kernel_ms),
             "algorithmic_bytes_per_launch": alg_bytes,
         },
@@ -157,12 +176,13 @@ def main():
 
     if not args.no_cpu:
         from oracle import blockperm as O  # the CPU-baseline leg is the only user of the oracle here
-        base, Y, cols = cpu_baseline(torch, cfg, A)
-        err = O.rel_fro_err(out[:, :cols].to("cpu").to(torch.float64).numpy(), Y)
+        base, Y, cols = cpu_baseline(torch, cfg, A.t() if rows else A)
+        got = out[:cols].t() if rows else out[:, :cols]
+        err = O.rel_fro_err(got.to("cpu").to(torch.float64).numpy(), Y)
         rec["cpu_baseline"] = base
         rec["rel_fro_err_vs_oracle_on_sample"] = err
 
-    if not args.no_extra:
+    if not args.no_extra and not rows:
         rec["extra"] = extra_measurements(torch, B, W, dev, cfg.name, with_oracle=not args.no_cpu)
         rec["extra"]["rows_layout"] = rows_layout_measurement(torch, B, cfg, A, out)
     print(json.dumps(rec))

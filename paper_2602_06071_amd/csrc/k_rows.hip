@@ -2,13 +2,15 @@
 // one vector to sketch, e.g. one example's gradient) and out = G S^T is n x k row-major, i.e.
 // out[i, :] = S G[i, :].  The same linear map as the column layout (Alg. 1), only transposed.
 //
-// On the matrix cores this layout is the natural one: with D (examples x stacked output rows)
-// = G_tile (examples x K) * Phi^T (K x stacked rows) a lane's MFMA operand is 8 consecutive
-// K-values of ONE example row, which is 16 contiguous bytes of G: the operand is loaded
-// straight from HBM with one 128-bit buffer load, no register transposition.  K-values may be
-// assigned to MFMA k-steps in any order as long as both operands agree, so lane half kg takes
-// the K-range [32 kg, 32 kg + 32) of a 64-row stage and k-step j its j-th group of 8: the two
-// halves of a wave then read 128 contiguous bytes of every example row per stage.
+// With D (examples x stacked output rows) = G_tile (examples x K) * Phi^T (K x stacked rows) a
+// lane's MFMA operand is 8 consecutive K-values of ONE example row: 16 contiguous bytes of G,
+// no register transposition.  Loading the operands in that very lane order would touch 32
+// different rows with 32 bytes each per instruction, which the memory system serves at less
+// than half the streaming rate (measured with a read-only probe: 2.6 TB/s at a power-of-two row
+// stride, 5.4 TB/s at best).  So G is loaded coalesced -- 8 (bf16) or 16 (fp32) lanes cover the
+// 128 / 256 contiguous bytes a row contributes to a 64-value stage, 5.9-6.3 TB/s in the same
+// probe -- and each 32-example tile is passed through a small padded LDS tile of the wave to
+// reach the operand order (LDS operations of one wave complete in order: no barrier).
 //
 //  * input-stationary (one wave = one work-group): (input block h, 32*ET examples, row split z)
 //    reads its K-range of G once and accumulates the kappa stacked destination blocks
@@ -17,7 +19,8 @@
 //  * Phi^T is generated exactly as in the column layout: per 64-row stage one lane per input
 //    row hashes its kappa slots (Appendix E, "Within-block hashing") and scatters +-1 as bf16
 //    into the wave's own LDS tile [stacked row][64 + 8]; two tiles alternate, no barrier;
-//  * fp32 inputs: exact three-way bf16 split of the 8 values a lane holds, three MFMAs.
+//  * fp32 inputs: exact three-way bf16 split of the 8 values a lane holds, three MFMAs;
+//  * the prefetch ring holds whole example tiles (all lines of a tile are requested together).
 //
 // Shapes: power-of-two Br with kappa*Br in {32, 64, 128}, Bc a multiple of 64 that divides d,
 // 16-byte aligned rows.  Inputs must be finite (a dense product also multiplies by the zeros).
@@ -43,16 +46,20 @@ struct RowsArgs {
   uint32_t log2_br;
 };
 
-template <typename T> struct RowLd;  // what a lane loads per (example tile, k-step): 8 K-values
-template <> struct RowLd<uint16_t> { static constexpr int NV = 1; };  // one b128
-template <> struct RowLd<float>    { static constexpr int NV = 2; };  // two b128
-
-template <typename T, int MT, int ET>
+// STAGED: G goes through the wave's LDS transposition tile (coalesced loads); otherwise the
+// operands are loaded in MFMA lane order.
+template <typename T, int MT, int ET, bool STAGED>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2)))
 void rows_kernel(RowsArgs a) {
-  constexpr int NV = RowLd<T>::NV;
   constexpr int RWV = 32 * MT;         // stacked output rows = kappa * Br
-  constexpr int TILE = RWV * PHI_LD;   // bf16 elements of one Phi tile
+  constexpr int TILE = RWV * PHI_LD;   // bf16 elements of the Phi tile
+  constexpr int ROWB = KC * (int)sizeof(T);   // bytes of a row per stage: 128 / 256
+  constexpr int GLD = ROWB + 16;              // LDS row of the transposition tile (conflict-free b128)
+  constexpr int LPR = ROWB / 16;              // STAGED: lanes per row: 8 / 16
+  constexpr int RPI = 64 / LPR;               //         rows per load instruction: 8 / 4
+  constexpr int NLD = 32 / RPI;               // 16-byte loads per lane and 32-example tile: 4 / 8
+  constexpr int NV = (int)sizeof(T) / 2;      // 16-byte loads per k-step operand: 1 / 2
+  static_assert(NLD == KSTEPS * NV, "both load orders move the same registers");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const SketchParams& p = a.p;
   const int lane = (int)threadIdx.x;
@@ -60,6 +67,7 @@ void rows_kernel(RowsArgs a) {
   uint32_t* s_bk = reinterpret_cast<uint32_t*>(smem);   // [MAX_KAPPA] block keys per slot
   uint32_t* s_blk = s_bk + MAX_KAPPA;                   // [MAX_KAPPA] destination block g_l
   uint16_t* s_phi = reinterpret_cast<uint16_t*>(smem + 2 * MAX_KAPPA * 4);
+  unsigned char* s_g = smem + 2 * MAX_KAPPA * 4 + TILE * 2;  // STAGED: [32][GLD] bytes
 
   const uint32_t blk = blockIdx.x;  // input block h
   const int ex0 = (int)blockIdx.y * (32 * ET);
@@ -67,56 +75,57 @@ void rows_kernel(RowsArgs a) {
   const int T_stages = a.stages;
   const uint32_t lbr = a.log2_br;
 
-  // slot tables and empty tiles
+  // slot tables and an empty tile
   for (int sl = lane; sl < (int)p.kappa; sl += 64) {
     uint32_t x = blk;
     for (int l = 0; l <= sl; ++l) x = wire_prev(x, p.a_inv, p.b, p.M);
     s_blk[sl] = x;
     s_bk[sl] = block_key(p.key1, x, blk, p.M);
   }
-  {
+  auto clear_tile = [&]() {
     uint4* z4 = reinterpret_cast<uint4*>(s_phi);
-    static_assert((2 * TILE / 8) % 64 == 0, "two tiles are a whole number of 64-lane stores");
 #pragma unroll
-    for (int i = 0; i < 2 * TILE / 8 / 64; ++i) z4[lane + i * 64] = make_uint4(0, 0, 0, 0);
-  }
+    for (int i = 0; i < (TILE / 8 + 63) / 64; ++i)
+      if (TILE / 8 % 64 == 0 || lane + i * 64 < TILE / 8) z4[lane + i * 64] = make_uint4(0, 0, 0, 0);
+  };
+  clear_tile();
   __syncthreads();  // one wave: orders the table writes before the reads by other lanes
 
   // ---- loads ---------------------------------------------------------------------------
   // One descriptor per wave: base = first example row of the wave at the first K of its range;
   // the range ends with the last valid example row, so rows at or beyond n read as 0 without
-  // touching memory (lanes of such rows get the out-of-range offset 2^31 outright).
+  // touching memory.  The scalar offset selects example tile and stage (and, STAGED, the row
+  // group); the lane offset the row and the 16-byte piece.
+  // K-values of k-step j in lane half kg: STAGED 16 j + 8 kg (the natural operand order);
+  // otherwise 32 kg + 8 j, so that a lane's four pieces are 64 (128) contiguous bytes.
   const int64_t row_bytes = a.ldg * (int64_t)sizeof(T);
   const int rows_valid = min(32 * ET, a.n - ex0);
   const int64_t k_first = (int64_t)blk * p.Bc + (int64_t)z * T_stages * KC;
   const int64_t range =
-      rows_valid > 0 ? (int64_t)(rows_valid - 1) * row_bytes + (int64_t)T_stages * KC * (int64_t)sizeof(T) : 0;
+      rows_valid > 0 ? (int64_t)(rows_valid - 1) * row_bytes + (int64_t)T_stages * ROWB : 0;
   const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<char*>(reinterpret_cast<const char*>(a.G) + (int64_t)ex0 * row_bytes +
                         k_first * (int64_t)sizeof(T)),
       0, (int)(uint32_t)range, 0x00020000);
-  uint32_t voff[ET];
-#pragma unroll
-  for (int c = 0; c < ET; ++c)
-    voff[c] = c * 32 + m < rows_valid
-                  ? (uint32_t)((int64_t)(c * 32 + m) * row_bytes + (int64_t)kg * 32 * (int64_t)sizeof(T))
-                  : 0x80000000u;
+  const uint32_t voff = STAGED ? (uint32_t)((int64_t)(lane / LPR) * row_bytes + (lane % LPR) * 16)
+                               : (uint32_t)((int64_t)m * row_bytes + kg * 32 * (int)sizeof(T));
+  unsigned char* g_wr = s_g + (lane / LPR) * GLD + (lane % LPR) * 16;
+  const unsigned char* g_rd = s_g + m * GLD + kg * (8 * (int)sizeof(T));
+  const int phi_k = STAGED ? kg * 8 : kg * 32;  // + (STAGED ? 16 : 8) * j
 
-  // Prefetch ring of R example tiles, each with all four k-steps of a stage: the four 16-byte
-  // pieces a lane takes from one 128-byte line (bf16; two lines for fp32) are requested back to
-  // back, so the line is fetched once.  (Requesting them one k-step at a time, a stage apart,
-  // re-fetched every line four times: 1.9 TB/s instead of the rate below.)
+  // Prefetch ring of R example tiles, a whole stage of each: the lines of a tile are requested
+  // back to back, once.  (Requesting them one k-step at a time, a stage apart, re-fetched every
+  // line four times.)
   constexpr int R = sizeof(T) == 2 ? ET : 2;
   static_assert(ET % R == 0, "the ring divides a stage");
-  uint4 ld[R][KSTEPS][NV];
-  auto issue_tile = [&](int t, int c, uint4 (&dst)[KSTEPS][NV]) {
-    // stage t, example tile c: K offset 64 t + 8 j for k-step j (+ 32 kg in voff)
+  uint4 ld[R][NLD];
+  auto issue_tile = [&](int t, int c, uint4 (&dst)[NLD]) {
 #pragma unroll
-    for (int j = 0; j < KSTEPS; ++j)
-#pragma unroll
-      for (int v = 0; v < NV; ++v)
-        dst[j][v] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(
-            rs, voff[c], (uint32_t)(t * KC + j * 8) * (uint32_t)sizeof(T) + 16u * v, 0));
+    for (int i = 0; i < NLD; ++i) {
+      const uint32_t so = STAGED ? (uint32_t)(c * 32 + i * RPI) * (uint32_t)row_bytes + (uint32_t)(t * ROWB)
+                                 : (uint32_t)(c * 32) * (uint32_t)row_bytes + (uint32_t)(t * ROWB + i * 16);
+      dst[i] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rs, voff, so, 0));
+    }
   };
 
   f32x16 acc[ET][MT];
@@ -128,51 +137,56 @@ void rows_kernel(RowsArgs a) {
       for (int i = 0; i < 16; ++i) acc[c][rt][i] = 0.f;
 
   // ---- Phi^T: part `part` of a stage takes every 4th slot ---------------------------------
-  auto produce = [&](int t, int buf, int part) {
-    uint16_t* phi = s_phi + buf * TILE;
+  auto produce = [&](int t, int part) {
     const uint32_t u = (uint32_t)(z * T_stages + t) * KC + lane;
     for (uint32_t slot = part; slot < p.kappa; slot += KSTEPS) {
       const RowHash rh = row_hash_pow2(s_bk[slot], u, p.Br);
       uint32_t r = rh.shift;
       const uint32_t base = slot << lbr;
       for (uint32_t i = 0; i < p.s; ++i) {
-        phi[__umul24(base + r, (uint32_t)PHI_LD) + lane] = (uint16_t)(((rh.signs >> i) << 15) | kOne);
+        s_phi[__umul24(base + r, (uint32_t)PHI_LD) + lane] = (uint16_t)(((rh.signs >> i) << 15) | kOne);
         r = (r + rh.stride) & (p.Br - 1);
       }
     }
   };
-  auto clear_tile = [&](int buf) {
-    uint4* z4 = reinterpret_cast<uint4*>(s_phi + buf * TILE);
-#pragma unroll
-    for (int i = 0; i < (TILE / 8 + 63) / 64; ++i)
-      if (TILE / 8 % 64 == 0 || lane + i * 64 < TILE / 8) z4[lane + i * 64] = make_uint4(0, 0, 0, 0);
-  };
 
+  // One stage.  All Phi^T operands of the stage are read into registers first; LDS operations
+  // of a wave complete in order, so the one tile can be cleared and refilled for the next stage
+  // right behind those reads.
   auto stage = [&](int t, auto last_tag) {
     constexpr bool LAST = decltype(last_tag)::value;
-    const uint16_t* phi = s_phi + (t & 1) * TILE;
-    uint4 pb[KSTEPS][MT];  // Phi^T operands: stacked row rt*32 + m, K = 32 kg + 8 j .. + 7
+    uint4 pb[KSTEPS][MT];  // stacked row rt*32 + m, the K-values of (k-step j, half kg)
 #pragma unroll
     for (int j = 0; j < KSTEPS; ++j)
 #pragma unroll
       for (int rt = 0; rt < MT; ++rt)
-        pb[j][rt] = *reinterpret_cast<const uint4*>(phi + (rt * 32 + m) * PHI_LD + kg * 32 + j * 8);
+        pb[j][rt] = *reinterpret_cast<const uint4*>(s_phi + (rt * 32 + m) * PHI_LD + phi_k +
+                                                    (STAGED ? 16 : 8) * j);
+    if constexpr (!LAST) clear_tile();
 #pragma unroll
     for (int c = 0; c < ET; ++c) {
       if constexpr (!LAST) {
 #pragma unroll
-        for (int part = c * KSTEPS / ET; part < (c + 1) * KSTEPS / ET; ++part) produce(t + 1, (t + 1) & 1, part);
+        for (int part = c * KSTEPS / ET; part < (c + 1) * KSTEPS / ET; ++part) produce(t + 1, part);
       }
-      uint4(&cur)[KSTEPS][NV] = ld[c % R];
-      // the tile R places further on: same stage, or the next one
+      uint4(&cur)[NLD] = ld[c % R];
+      uint4 g[NLD];  // operand pieces: k-step j is g[j*NV .. j*NV + NV)
+      if constexpr (STAGED) {
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) *reinterpret_cast<uint4*>(g_wr + i * RPI * GLD) = cur[i];
+      } else {
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) g[i] = cur[i];
+      }
+      // refill the slot with the tile R places further on: same stage, or the next one
       const int CN = (c + R) % ET;  // compile-time after unrolling
       const bool wrap = c + R >= ET;
-      const bool fetch = !(LAST && wrap);  // compile-time after unrolling
-      if constexpr (sizeof(T) == 2) {
-        uint4 g[KSTEPS];
+      if (!(LAST && wrap)) issue_tile(wrap ? t + 1 : t, CN, cur);
+      if constexpr (STAGED) {
 #pragma unroll
-        for (int j = 0; j < KSTEPS; ++j) g[j] = cur[j][0];
-        if (fetch) issue_tile(wrap ? t + 1 : t, CN, cur);
+        for (int i = 0; i < NLD; ++i) g[i] = *reinterpret_cast<const uint4*>(g_rd + (i / NV) * (16 * (int)sizeof(T)) + (i % NV) * 16);
+      }
+      if constexpr (sizeof(T) == 2) {
 #pragma unroll
         for (int j = 0; j < KSTEPS; ++j)
 #pragma unroll
@@ -183,8 +197,8 @@ void rows_kernel(RowsArgs a) {
           uint4 pc[2][3];
 #pragma unroll
           for (int cc = 0; cc < 2; ++cc) {
-            const uint32_t xs[8] = {cur[jj + cc][0].x, cur[jj + cc][0].y, cur[jj + cc][0].z, cur[jj + cc][0].w,
-                                    cur[jj + cc][1].x, cur[jj + cc][1].y, cur[jj + cc][1].z, cur[jj + cc][1].w};
+            const uint4 x0 = g[(jj + cc) * 2], x1 = g[(jj + cc) * 2 + 1];
+            const uint32_t xs[8] = {x0.x, x0.y, x0.z, x0.w, x1.x, x1.y, x1.z, x1.w};
             split_ops(xs, pc[cc][0], pc[cc][1], pc[cc][2]);
           }
 #pragma unroll
@@ -195,18 +209,16 @@ void rows_kernel(RowsArgs a) {
               for (int rt = 0; rt < MT; ++rt)
                 acc[c][rt] = mfma(pc[cc][piece], pb[jj + cc][rt], acc[c][rt]);
         }
-        if (fetch) issue_tile(wrap ? t + 1 : t, CN, cur);
       }
       __builtin_amdgcn_sched_barrier(0);
     }
-    if constexpr (!LAST) clear_tile(t & 1);
   };
 
   if (rows_valid > 0) {
 #pragma unroll
     for (int c = 0; c < R; ++c) issue_tile(0, c, ld[c]);
 #pragma unroll
-    for (int part = 0; part < KSTEPS; ++part) produce(0, 0, part);
+    for (int part = 0; part < KSTEPS; ++part) produce(0, part);
     for (int t = 0; t + 1 < T_stages; ++t) stage(t, std::false_type{});
     stage(T_stages - 1, std::true_type{});
   }
@@ -233,6 +245,7 @@ void rows_kernel(RowsArgs a) {
 struct RowsPlan {
   bool ok = false;
   int mt = 0, et = 0, zsplit = 1, stages = 0, planes = 0;
+  bool staged = false;
   int64_t ldw = 0;
   size_t lds = 0;
 };
@@ -265,7 +278,11 @@ RowsPlan make_rows_plan(const SketchParams& p, const void* G, int64_t ldg, int64
   pl.stages = (int)(p.Bc / pl.zsplit / KC);
   pl.planes = pl.zsplit * (int)p.kappa;
   pl.ldw = (p.k + 3) & ~(int64_t)3;
-  pl.lds = 2 * MAX_KAPPA * 4 + 2 * (size_t)(32 * pl.mt) * PHI_LD * 2;
+  // measured: the LDS-staged loads win for bf16 (4.9 against 4.8 TB/s with a padded row stride,
+  // 4.4 against 2.6 at a power-of-two stride) and for 32 stacked rows; fp32 with 64 or 128
+  // stacked rows is short of registers and LDS and is faster with the direct loads
+  pl.staged = dt == FS_BF16 || pl.mt == 1;
+  pl.lds = 2 * MAX_KAPPA * 4 + (size_t)(32 * pl.mt) * PHI_LD * 2 + (pl.staged ? 32 * (KC * esz + 16) : 0);
   pl.ok = true;
   return pl;
 }
@@ -302,15 +319,13 @@ hipError_t launch_rows(const SketchParams& p, const void* G, int64_t ldg, int64_
 
   if (ev.start) (void)hipEventRecord(ev.start, st);
   hipError_t e;
-  if (dt == FS_BF16) {
-    e = pl.mt == 1   ? go(rows_kernel<uint16_t, 1, 4>, grid, pl.lds, st, a)
-        : pl.mt == 2 ? go(rows_kernel<uint16_t, 2, 4>, grid, pl.lds, st, a)
-                     : go(rows_kernel<uint16_t, 4, 2>, grid, pl.lds, st, a);
-  } else {
-    e = pl.mt == 1   ? go(rows_kernel<float, 1, 4>, grid, pl.lds, st, a)
-        : pl.mt == 2 ? go(rows_kernel<float, 2, 4>, grid, pl.lds, st, a)
-                     : go(rows_kernel<float, 4, 2>, grid, pl.lds, st, a);
-  }
+#define FS_ROWS(T, MT, ET) \
+  (pl.staged ? go(rows_kernel<T, MT, ET, true>, grid, pl.lds, st, a) : go(rows_kernel<T, MT, ET, false>, grid, pl.lds, st, a))
+  if (dt == FS_BF16)
+    e = pl.mt == 1 ? FS_ROWS(uint16_t, 1, 4) : pl.mt == 2 ? FS_ROWS(uint16_t, 2, 4) : FS_ROWS(uint16_t, 4, 2);
+  else
+    e = pl.mt == 1 ? FS_ROWS(float, 1, 4) : pl.mt == 2 ? FS_ROWS(float, 2, 4) : FS_ROWS(float, 4, 2);
+#undef FS_ROWS
   if (ev.stop) (void)hipEventRecord(ev.stop, st);
   if (e != hipSuccess) return e;
   // out[i][c] = scale * sum over planes: the plane reduction of the column layout with the
