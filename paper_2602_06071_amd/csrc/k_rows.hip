@@ -18,7 +18,8 @@
 //    and the fixed-order plane reduction give `out` without atomics on data;
 //  * Phi^T is generated exactly as in the column layout: per 64-row stage one lane per input
 //    row hashes its kappa slots (Appendix E, "Within-block hashing") and scatters +-1 as bf16
-//    into the wave's own LDS tile [stacked row][64 + 8]; two tiles alternate, no barrier;
+//    into the wave's own LDS tile [stacked row][64 + 8] (one tile: a stage reads all its
+//    operands first, then the tile is cleared and refilled behind those reads);
 //  * fp32 inputs: exact three-way bf16 split of the 8 values a lane holds, three MFMAs;
 //  * the prefetch ring holds whole example tiles (all lines of a tile are requested together).
 //
