@@ -357,7 +357,9 @@ fs_status fs_sketch_apply_rows(fs_sketch_t h, const void* G, int64_t ldg, int64_
     ev.stop = h->prof_stop[h->prof_used];
     ++h->prof_used;
   }
-  const hipError_t e = fs::launch_rows(h->p, G, ldg, n, out, ldo, dt, h->ws, st, ev);
+  rc = ensure_orbit(h);  // the gather-reduction walks the wiring through this table
+  if (rc != FS_OK) return rc;
+  const hipError_t e = fs::launch_rows(h->p, G, ldg, n, out, ldo, dt, h->ws, h->orbit, st, ev);
   h->last_variant = FS_VARIANT_MFMA;
   h->last_mode = 2;
   if (e != hipSuccess) return hip_fail(h, e);

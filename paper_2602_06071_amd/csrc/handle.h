@@ -76,7 +76,8 @@ hipError_t launch_reduce_planes(const float* ws, int planes, int64_t rows, int64
 bool rows_supported(const SketchParams& p, const void* G, int64_t ldg, int64_t n, fs_dtype dt);
 size_t rows_workspace_bytes(const SketchParams& p, const void* G, int64_t ldg, int64_t n, fs_dtype dt);
 hipError_t launch_rows(const SketchParams& p, const void* G, int64_t ldg, int64_t n, void* out,
-                       int64_t ldo, fs_dtype dt, void* ws, hipStream_t st, EventPair ev);
+                       int64_t ldo, fs_dtype dt, void* ws, const uint32_t* orbit, hipStream_t st,
+                       EventPair ev);
 
 // Plain SJLT, global float atomics.  ws: k*n floats for bf16 output, unused for fp32.
 size_t scatter_workspace_bytes(const SketchParams& p, int64_t n, fs_dtype dt);

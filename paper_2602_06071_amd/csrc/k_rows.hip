@@ -14,8 +14,8 @@
 //
 //  * input-stationary (one wave = one work-group): (input block h, 32*ET examples, row split z)
 //    reads its K-range of G once and accumulates the kappa stacked destination blocks
-//    g_l = f^{-l}(h) (kappa*Br = 32*MT MFMA columns); fp32 partial planes [plane][example][k]
-//    and the fixed-order plane reduction give `out` without atomics on data;
+//    g_l = f^{-l}(h) (kappa*Br = 32*MT MFMA columns); fp32 partial results stored by input
+//    block and a fixed-order gather-reduction give `out` without atomics on data;
 //  * Phi^T is generated exactly as in the column layout: per 64-row stage one lane per input
 //    row hashes its kappa slots (Appendix E, "Within-block hashing") and scatters +-1 as bf16
 //    into the wave's own LDS tile [stacked row][64 + 8] (one tile: a stage reads all its
@@ -41,6 +41,7 @@ struct RowsArgs {
   SketchParams p;
   const void* G;
   float* ws;
+  const uint32_t* orbit;  // 2M words: block at each orbit position of f from block 0, then the inverse (or NULL)
   int64_t ldg, ldw;
   int n;        // examples
   int stages;   // 64-row stages per work-group
@@ -225,22 +226,86 @@ void rows_kernel(RowsArgs a) {
   }
 
   // ---- epilogue: accumulator v of tile (c, rt) is example ex0 + 32 c + 8 (v/4) + 4 kg + v%4,
-  // stacked row 32 rt + m; a half-wave writes 32 consecutive stacked rows of one example
-#pragma unroll
-  for (int rt = 0; rt < MT; ++rt) {
-    const uint32_t srow = (uint32_t)(rt * 32 + m);
-    const uint32_t slot = srow >> lbr, r = srow & (p.Br - 1);
-    if (slot >= p.kappa) continue;
-    const int64_t plane = (int64_t)z * p.kappa + slot;
-    float* col = a.ws + plane * a.n * a.ldw + (int64_t)s_blk[slot] * p.Br + r;
+  // stacked row 32 rt + m.  The partial results are stored as [z][example][input block][stacked
+  // row]: a wave's 32*MT stacked rows of one example are contiguous, so every store instruction
+  // writes whole 128-byte lines (stored by destination block they were 32-byte runs for Br = 8,
+  // and the stores cost 15 % of the kernel).  The reduction gathers them by output block.
+  // Records are ordered by the ORBIT POSITION of the input block when the orbit table exists:
+  // the kappa records an output block needs are then adjacent (positions p+1 .. p+kappa of the
+  // output's position p), and neighbouring outputs read neighbouring records.
+  {
+    const uint32_t rec = a.orbit ? __builtin_amdgcn_readfirstlane(a.orbit[p.M + blk]) : blk;
+    float* base = a.ws + (((int64_t)z * a.n + ex0) * p.M + rec) * RWV + m;
+    const int64_t ex_stride = (int64_t)p.M * RWV;
 #pragma unroll
     for (int c = 0; c < ET; ++c)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int ex = c * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
-        if (ex < rows_valid) col[(int64_t)(ex0 + ex) * a.ldw] = acc[c][rt][v];
+        if (ex < rows_valid) {
+#pragma unroll
+          for (int rt = 0; rt < MT; ++rt) base[ex * ex_stride + rt * 32] = acc[c][rt][v];
+        }
       }
   }
+}
+
+// out[ex][g*Br + r] = scale * sum over slots l = 1..kappa (outer) and row splits z (inner) of
+// part[z][ex][record of f^l(g)][(l-1)*Br + r]: fixed order, no atomics.  One thread per VEC output
+// columns (VEC = 4 when 4 | Br, else 1).  With the orbit table (2M words: block at each orbit
+// position of f from block 0, then the inverse) threads are numbered by the orbit position pos of
+// their output block and the records are those at positions pos+1 .. pos+kappa: a sliding window
+// of contiguous memory.  Without it records are indexed by block and f is evaluated directly.
+template <typename T, int VEC>
+__global__ __launch_bounds__(256) void reduce_rows_kernel(const float* __restrict__ part, int zsplit, int n,
+                                                          SketchParams p, uint32_t lbr,
+                                                          const uint32_t* __restrict__ orbit,
+                                                          T* __restrict__ out, int64_t ldo) {
+  const int64_t q = p.k / VEC;
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (int64_t)n * q) return;
+  const int64_t ex = idx / q;
+  const uint32_t col0 = (uint32_t)(idx % q) * VEC;
+  const uint32_t bi = col0 >> lbr, r = col0 & (p.Br - 1);  // orbit position (or block) and row in block
+  const uint32_t g = orbit ? orbit[bi] : bi;
+  const uint32_t rw = p.kappa << lbr;
+  const int64_t z_stride = (int64_t)n * p.M * rw;
+  const float* src = part + ex * (int64_t)p.M * rw + r;
+  float s[VEC];
+#pragma unroll
+  for (int c = 0; c < VEC; ++c) s[c] = 0.f;
+  uint32_t rec = bi;
+  for (uint32_t l = 0; l < p.kappa; ++l) {
+    if (orbit) rec = rec + 1 == p.M ? 0u : rec + 1;
+    else rec = wire_next(rec, p.a, p.b, p.M);
+    const float* ph = src + (int64_t)rec * rw + (l << lbr);
+    for (int zc = 0; zc < zsplit; ++zc) {
+      if constexpr (VEC == 4) {
+        const float4 v = *reinterpret_cast<const float4*>(ph + zc * z_stride);
+        s[0] += v.x; s[1] += v.y; s[2] += v.z; s[3] += v.w;
+      } else {
+        s[0] += ph[zc * z_stride];
+      }
+    }
+  }
+  T* dst = out + ex * ldo + ((int64_t)g << lbr) + r;
+#pragma unroll
+  for (int c = 0; c < VEC; ++c) s[c] *= p.scale;
+  if constexpr (VEC == 4) {
+    if ((uintptr_t)dst % (4 * sizeof(T)) == 0) {  // one 8- or 16-byte store
+      if constexpr (sizeof(T) == 2) {
+        uint2 w;
+        w.x = (uint32_t)f32_to_bf16_rne(s[0]) | ((uint32_t)f32_to_bf16_rne(s[1]) << 16);
+        w.y = (uint32_t)f32_to_bf16_rne(s[2]) | ((uint32_t)f32_to_bf16_rne(s[3]) << 16);
+        *reinterpret_cast<uint2*>(dst) = w;
+      } else {
+        *reinterpret_cast<float4*>(dst) = make_float4(s[0], s[1], s[2], s[3]);
+      }
+      return;
+    }
+  }
+#pragma unroll
+  for (int c = 0; c < VEC; ++c) Elt<T>::store(dst + c, s[c]);
 }
 
 struct RowsPlan {
@@ -303,15 +368,16 @@ bool rows_supported(const SketchParams& p, const void* G, int64_t ldg, int64_t n
 size_t rows_workspace_bytes(const SketchParams& p, const void* G, int64_t ldg, int64_t n, fs_dtype dt) {
   const RowsPlan pl = make_rows_plan(p, G, ldg, n, dt);
   if (!pl.ok) return 0;
-  return (size_t)pl.planes * (size_t)n * (size_t)pl.ldw * sizeof(float);
+  return (size_t)pl.planes * (size_t)n * (size_t)p.k * sizeof(float);  // [z][example][block][kappa*Br]
 }
 
 hipError_t launch_rows(const SketchParams& p, const void* G, int64_t ldg, int64_t n, void* out,
-                       int64_t ldo, fs_dtype dt, void* ws, hipStream_t st, EventPair ev) {
+                       int64_t ldo, fs_dtype dt, void* ws, const uint32_t* orbit, hipStream_t st,
+                       EventPair ev) {
   const RowsPlan pl = make_rows_plan(p, G, ldg, n, dt);
   if (!pl.ok) return hipErrorInvalidValue;
   RowsArgs a;
-  a.p = p; a.G = G; a.ws = (float*)ws;
+  a.p = p; a.G = G; a.ws = (float*)ws; a.orbit = orbit;
   a.ldg = ldg; a.ldw = pl.ldw; a.n = (int)n;
   a.stages = pl.stages;
   a.log2_br = 0;
@@ -329,9 +395,16 @@ hipError_t launch_rows(const SketchParams& p, const void* G, int64_t ldg, int64_
 #undef FS_ROWS
   if (ev.stop) (void)hipEventRecord(ev.stop, st);
   if (e != hipSuccess) return e;
-  // out[i][c] = scale * sum over planes: the plane reduction of the column layout with the
-  // roles of rows and columns exchanged (n example rows of k columns)
-  return launch_reduce_planes(a.ws, pl.planes, n, pl.ldw, p.k, out, ldo, p.scale, dt, st);
+  const int vec = p.Br % 4 == 0 ? 4 : 1;
+  const int64_t work = n * (p.k / vec);
+  const dim3 rgrid((unsigned)((work + 255) / 256));
+#define FS_RED(T, VEC)                                                                                   \
+  hipLaunchKernelGGL((reduce_rows_kernel<T, VEC>), rgrid, dim3(256), 0, st, a.ws, pl.zsplit, (int)n, p, \
+                     a.log2_br, orbit, (T*)out, ldo)
+  if (dt == FS_BF16) { if (vec == 4) FS_RED(uint16_t, 4); else FS_RED(uint16_t, 1); }
+  else               { if (vec == 4) FS_RED(float, 4); else FS_RED(float, 1); }
+#undef FS_RED
+  return hipGetLastError();
 }
 
 }  // namespace fs
