@@ -67,11 +67,6 @@ hipError_t launch_mfma(const SketchParams& p, const void* A, int64_t lda, int64_
                        int64_t ldo, fs_dtype dt, void* ws, const uint32_t* orbit, hipStream_t st,
                        EventPair ev, int* mode);
 
-// out[r][c] = scale * sum_p ws[p][r][c] for rows x cols fp32 planes of leading dimension ldw
-// (a multiple of 4), planes added in index order; out is of type dt with leading dimension ldo.
-hipError_t launch_reduce_planes(const float* ws, int planes, int64_t rows, int64_t ldw, int64_t cols,
-                                void* out, int64_t ldo, float scale, fs_dtype dt, hipStream_t st);
-
 // Matrix-core path for inputs held examples-as-rows: G is n x d (ld = ldg), out is n x k.
 bool rows_supported(const SketchParams& p, const void* G, int64_t ldg, int64_t n, fs_dtype dt);
 size_t rows_workspace_bytes(const SketchParams& p, const void* G, int64_t ldg, int64_t n, fs_dtype dt);

@@ -819,21 +819,6 @@ bool mfma_supported(const SketchParams& p, const void* A, int64_t lda, int64_t n
   return make_plan(p, A, lda, n, dt, false).ok;
 }
 
-hipError_t launch_reduce_planes(const float* ws, int planes, int64_t rows, int64_t ldw, int64_t cols,
-                                void* out, int64_t ldo, float scale, fs_dtype dt, hipStream_t st) {
-  const size_t esz = dt == FS_F32 ? 4 : 2;
-  const int out_vec = ((uintptr_t)out % (4 * esz) == 0 && (ldo * esz) % (4 * esz) == 0) ? 1 : 0;
-  const int64_t work = rows * (ldw / 4);
-  const unsigned blocks = (unsigned)((work + 255) / 256);
-  if (dt == FS_BF16)
-    hipLaunchKernelGGL(reduce_planes_kernel<uint16_t>, dim3(blocks), dim3(256), 0, st, ws, planes, rows, ldw,
-                       (int)cols, (uint16_t*)out, ldo, scale, out_vec, 1, nullptr, 1u, 1u);
-  else
-    hipLaunchKernelGGL(reduce_planes_kernel<float>, dim3(blocks), dim3(256), 0, st, ws, planes, rows, ldw,
-                       (int)cols, (float*)out, ldo, scale, out_vec, 1, nullptr, 1u, 1u);
-  return hipGetLastError();
-}
-
 bool mfma_wants_orbit(const SketchParams& p) {
   return p.M >= 4 && p.M <= (1u << 20);
 }

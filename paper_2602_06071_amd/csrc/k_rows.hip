@@ -42,7 +42,8 @@ struct RowsArgs {
   const void* G;
   float* ws;
   const uint32_t* orbit;  // 2M words: block at each orbit position of f from block 0, then the inverse (or NULL)
-  int64_t ldg, ldw;
+  void* out;              // OUT mode: the result itself
+  int64_t ldg, ldo;
   int n;        // examples
   int stages;   // 64-row stages per work-group
   uint32_t log2_br;
@@ -50,7 +51,11 @@ struct RowsArgs {
 
 // STAGED: G goes through the wave's LDS transposition tile (coalesced loads); otherwise the
 // operands are loaded in MFMA lane order.
-template <typename T, int MT, int ET, bool STAGED>
+// OUT: output-stationary instead (Alg. 1's order): the wave owns output block g for its examples,
+// walks the kappa input blocks f^l(g) with Br = 32*MT MFMA columns, and stores the scaled result
+// itself; G is read kappa times (the re-reads hit L2 when neighbouring waves are in step), there
+// are no partial results.  Used when kappa*Br is more than one wave can accumulate.
+template <typename T, int MT, int ET, bool STAGED, bool OUT>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2)))
 void rows_kernel(RowsArgs a) {
   constexpr int RWV = 32 * MT;         // stacked output rows = kappa * Br
@@ -71,7 +76,7 @@ void rows_kernel(RowsArgs a) {
   uint16_t* s_phi = reinterpret_cast<uint16_t*>(smem + 2 * MAX_KAPPA * 4);
   unsigned char* s_g = smem + 2 * MAX_KAPPA * 4 + TILE * 2;  // STAGED: [32][GLD] bytes
 
-  const uint32_t blk = blockIdx.x;  // input block h
+  const uint32_t blk = blockIdx.x;  // input block h (OUT: output block g)
   const int ex0 = (int)blockIdx.y * (32 * ET);
   const int z = (int)blockIdx.z;
   const int T_stages = a.stages;
@@ -80,9 +85,9 @@ void rows_kernel(RowsArgs a) {
   // slot tables and an empty tile
   for (int sl = lane; sl < (int)p.kappa; sl += 64) {
     uint32_t x = blk;
-    for (int l = 0; l <= sl; ++l) x = wire_prev(x, p.a_inv, p.b, p.M);
+    for (int l = 0; l <= sl; ++l) x = OUT ? wire_next(x, p.a, p.b, p.M) : wire_prev(x, p.a_inv, p.b, p.M);
     s_blk[sl] = x;
-    s_bk[sl] = block_key(p.key1, x, blk, p.M);
+    s_bk[sl] = OUT ? block_key(p.key1, blk, x, p.M) : block_key(p.key1, x, blk, p.M);
   }
   auto clear_tile = [&]() {
     uint4* z4 = reinterpret_cast<uint4*>(s_phi);
@@ -94,21 +99,36 @@ void rows_kernel(RowsArgs a) {
   __syncthreads();  // one wave: orders the table writes before the reads by other lanes
 
   // ---- loads ---------------------------------------------------------------------------
-  // One descriptor per wave: base = first example row of the wave at the first K of its range;
-  // the range ends with the last valid example row, so rows at or beyond n read as 0 without
-  // touching memory.  The scalar offset selects example tile and stage (and, STAGED, the row
-  // group); the lane offset the row and the 16-byte piece.
+  // One descriptor per wave: base = first example row of the wave; the range ends with the last
+  // valid example row, so rows at or beyond n read as 0 without touching memory.  The scalar
+  // offset selects example tile and the stage's K-range (and, STAGED, the row group); the lane
+  // offset the row and the 16-byte piece.
   // K-values of k-step j in lane half kg: STAGED 16 j + 8 kg (the natural operand order);
   // otherwise 32 kg + 8 j, so that a lane's four pieces are 64 (128) contiguous bytes.
   const int64_t row_bytes = a.ldg * (int64_t)sizeof(T);
   const int rows_valid = min(32 * ET, a.n - ex0);
-  const int64_t k_first = (int64_t)blk * p.Bc + (int64_t)z * T_stages * KC;
   const int64_t range =
-      rows_valid > 0 ? (int64_t)(rows_valid - 1) * row_bytes + (int64_t)T_stages * ROWB : 0;
+      rows_valid > 0 ? (int64_t)(rows_valid - 1) * row_bytes + p.d * (int64_t)sizeof(T) : 0;
   const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<char*>(reinterpret_cast<const char*>(a.G) + (int64_t)ex0 * row_bytes +
-                        k_first * (int64_t)sizeof(T)),
-      0, (int)(uint32_t)range, 0x00020000);
+      const_cast<char*>(reinterpret_cast<const char*>(a.G) + (int64_t)ex0 * row_bytes), 0,
+      (int)(uint32_t)range, 0x00020000);
+  // Byte offset in a row of a stage's first K-value.  IN: the wave's own K-range.  OUT: stage t
+  // lies in input block s_blk[t / spb]; (sl_n, st_n, kb_n) describe stage "current + 1" and are
+  // stepped once per stage, kb_c is the current stage's offset.
+  const uint32_t spb = p.Bc / KC;  // stages per input block
+  uint32_t sl_n = 0, st_n = 0;
+  uint32_t kb_c = OUT ? (uint32_t)__builtin_amdgcn_readfirstlane(s_blk[0]) * p.Bc * (uint32_t)sizeof(T)
+                      : (uint32_t)(((int64_t)blk * p.Bc + (int64_t)z * T_stages * KC) * (int64_t)sizeof(T));
+  uint32_t kb_n = kb_c;
+  auto step_next = [&]() {  // (sl_n, st_n, kb_n) <- the stage after the one they describe
+    if constexpr (OUT) {
+      if (++st_n == spb) { st_n = 0; ++sl_n; }
+      const uint32_t hb = __builtin_amdgcn_readfirstlane(s_blk[min(sl_n, p.kappa - 1)]);
+      kb_n = (hb * p.Bc + st_n * KC) * (uint32_t)sizeof(T);
+    } else {
+      kb_n += ROWB;
+    }
+  };
   const uint32_t voff = STAGED ? (uint32_t)((int64_t)(lane / LPR) * row_bytes + (lane % LPR) * 16)
                                : (uint32_t)((int64_t)m * row_bytes + kg * 32 * (int)sizeof(T));
   unsigned char* g_wr = s_g + (lane / LPR) * GLD + (lane % LPR) * 16;
@@ -121,11 +141,11 @@ void rows_kernel(RowsArgs a) {
   constexpr int R = sizeof(T) == 2 ? ET : 2;
   static_assert(ET % R == 0, "the ring divides a stage");
   uint4 ld[R][NLD];
-  auto issue_tile = [&](int t, int c, uint4 (&dst)[NLD]) {
+  auto issue_tile = [&](uint32_t kb, int c, uint4 (&dst)[NLD]) {
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
-      const uint32_t so = STAGED ? (uint32_t)(c * 32 + i * RPI) * (uint32_t)row_bytes + (uint32_t)(t * ROWB)
-                                 : (uint32_t)(c * 32) * (uint32_t)row_bytes + (uint32_t)(t * ROWB + i * 16);
+      const uint32_t so = STAGED ? (uint32_t)(c * 32 + i * RPI) * (uint32_t)row_bytes + kb
+                                 : (uint32_t)(c * 32) * (uint32_t)row_bytes + kb + (uint32_t)(i * 16);
       dst[i] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rs, voff, so, 0));
     }
   };
@@ -138,8 +158,19 @@ void rows_kernel(RowsArgs a) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) acc[c][rt][i] = 0.f;
 
-  // ---- Phi^T: part `part` of a stage takes every 4th slot ---------------------------------
+  // ---- Phi^T of the stage (sl_n, st_n) / t: IN: part `part` takes every 4th slot; OUT: the one
+  // block of the stage, in part 0 -----------------------------------------------------------
   auto produce = [&](int t, int part) {
+    if constexpr (OUT) {
+      if (part != 0) return;
+      const RowHash rh = row_hash_pow2(s_bk[sl_n], st_n * KC + lane, p.Br);
+      uint32_t r = rh.shift;
+      for (uint32_t i = 0; i < p.s; ++i) {
+        s_phi[__umul24(r, (uint32_t)PHI_LD) + lane] = (uint16_t)(((rh.signs >> i) << 15) | kOne);
+        r = (r + rh.stride) & (p.Br - 1);
+      }
+      return;
+    }
     const uint32_t u = (uint32_t)(z * T_stages + t) * KC + lane;
     for (uint32_t slot = part; slot < p.kappa; slot += KSTEPS) {
       const RowHash rh = row_hash_pow2(s_bk[slot], u, p.Br);
@@ -164,7 +195,7 @@ void rows_kernel(RowsArgs a) {
       for (int rt = 0; rt < MT; ++rt)
         pb[j][rt] = *reinterpret_cast<const uint4*>(s_phi + (rt * 32 + m) * PHI_LD + phi_k +
                                                     (STAGED ? 16 : 8) * j);
-    if constexpr (!LAST) clear_tile();
+    if constexpr (!LAST) { clear_tile(); step_next(); }
 #pragma unroll
     for (int c = 0; c < ET; ++c) {
       if constexpr (!LAST) {
@@ -183,7 +214,7 @@ void rows_kernel(RowsArgs a) {
       // refill the slot with the tile R places further on: same stage, or the next one
       const int CN = (c + R) % ET;  // compile-time after unrolling
       const bool wrap = c + R >= ET;
-      if (!(LAST && wrap)) issue_tile(wrap ? t + 1 : t, CN, cur);
+      if (!(LAST && wrap)) issue_tile(wrap ? kb_n : kb_c, CN, cur);
       if constexpr (STAGED) {
 #pragma unroll
         for (int i = 0; i < NLD; ++i) g[i] = *reinterpret_cast<const uint4*>(g_rd + (i / NV) * (16 * (int)sizeof(T)) + (i % NV) * 16);
@@ -214,11 +245,12 @@ void rows_kernel(RowsArgs a) {
       }
       __builtin_amdgcn_sched_barrier(0);
     }
+    kb_c = kb_n;
   };
 
   if (rows_valid > 0) {
 #pragma unroll
-    for (int c = 0; c < R; ++c) issue_tile(0, c, ld[c]);
+    for (int c = 0; c < R; ++c) issue_tile(kb_c, c, ld[c]);
 #pragma unroll
     for (int part = 0; part < KSTEPS; ++part) produce(0, part);
     for (int t = 0; t + 1 < T_stages; ++t) stage(t, std::false_type{});
@@ -226,10 +258,25 @@ void rows_kernel(RowsArgs a) {
   }
 
   // ---- epilogue: accumulator v of tile (c, rt) is example ex0 + 32 c + 8 (v/4) + 4 kg + v%4,
-  // stacked row 32 rt + m.  The partial results are stored as [z][example][input block][stacked
-  // row]: a wave's 32*MT stacked rows of one example are contiguous, so every store instruction
-  // writes whole 128-byte lines (stored by destination block they were 32-byte runs for Br = 8,
-  // and the stores cost 15 % of the kernel).  The reduction gathers them by output block.
+  // stacked row 32 rt + m.
+  if constexpr (OUT) {  // the finished block: scale, convert, 32 consecutive columns per half-wave
+    T* base = reinterpret_cast<T*>(a.out) + (int64_t)ex0 * a.ldo + (int64_t)blk * p.Br + m;
+#pragma unroll
+    for (int c = 0; c < ET; ++c)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int ex = c * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
+        if (ex < rows_valid) {
+#pragma unroll
+          for (int rt = 0; rt < MT; ++rt) Elt<T>::store(base + (int64_t)ex * a.ldo + rt * 32, acc[c][rt][v] * p.scale);
+        }
+      }
+    return;
+  }
+  // IN: the partial results are stored as [z][example][record][stacked row]: a wave's 32*MT
+  // stacked rows of one example are contiguous, so every store instruction writes whole 128-byte
+  // lines (stored by destination block they were 32-byte runs for Br = 8, and the stores cost
+  // 15 % of the kernel).  The reduction gathers them by output block.
   // Records are ordered by the ORBIT POSITION of the input block when the orbit table exists:
   // the kappa records an output block needs are then adjacent (positions p+1 .. p+kappa of the
   // output's position p), and neighbouring outputs read neighbouring records.
@@ -311,8 +358,7 @@ __global__ __launch_bounds__(256) void reduce_rows_kernel(const float* __restric
 struct RowsPlan {
   bool ok = false;
   int mt = 0, et = 0, zsplit = 1, stages = 0, planes = 0;
-  bool staged = false;
-  int64_t ldw = 0;
+  bool staged = false, out_stat = false;
   size_t lds = 0;
 };
 
@@ -324,7 +370,11 @@ RowsPlan make_rows_plan(const SketchParams& p, const void* G, int64_t ldg, int64
   if (rw == 32) { pl.mt = 1; pl.et = 4; }
   else if (rw == 64) { pl.mt = 2; pl.et = 4; }
   else if (rw == 128) { pl.mt = 4; pl.et = 2; }
-  else return pl;
+  else if (p.Br == 32 || p.Br == 64 || p.Br == 128) {  // too many stacked rows: output-stationary
+    pl.out_stat = true;
+    pl.mt = (int)p.Br / 32;
+    pl.et = pl.mt == 4 ? 2 : 4;
+  } else return pl;
   if ((uintptr_t)G % 16 || (ldg * (int64_t)esz) % 16) return pl;         // 128-bit loads
   if (128 * ldg * (int64_t)esz >= ((int64_t)1 << 31)) return pl;          // 32-bit lane offsets and range
   const int64_t ex_tiles = (n + 32 * pl.et - 1) / (32 * pl.et);
@@ -341,9 +391,9 @@ RowsPlan make_rows_plan(const SketchParams& p, const void* G, int64_t ldg, int64
                      plane_bytes / 6e12;
     if (zc == 1 || t < best) { best = t; pl.zsplit = zc; }
   }
-  pl.stages = (int)(p.Bc / pl.zsplit / KC);
-  pl.planes = pl.zsplit * (int)p.kappa;
-  pl.ldw = (p.k + 3) & ~(int64_t)3;
+  if (pl.out_stat) pl.zsplit = 1;
+  pl.stages = pl.out_stat ? (int)(p.kappa * (p.Bc / KC)) : (int)(p.Bc / pl.zsplit / KC);
+  pl.planes = pl.out_stat ? 0 : pl.zsplit * (int)p.kappa;
   // measured: the LDS-staged loads win for bf16 (4.9 against 4.8 TB/s with a padded row stride,
   // 4.4 against 2.6 at a power-of-two stride) and for 32 stacked rows; fp32 with 64 or 128
   // stacked rows is short of registers and LDS and is faster with the direct loads
@@ -377,8 +427,8 @@ hipError_t launch_rows(const SketchParams& p, const void* G, int64_t ldg, int64_
   const RowsPlan pl = make_rows_plan(p, G, ldg, n, dt);
   if (!pl.ok) return hipErrorInvalidValue;
   RowsArgs a;
-  a.p = p; a.G = G; a.ws = (float*)ws; a.orbit = orbit;
-  a.ldg = ldg; a.ldw = pl.ldw; a.n = (int)n;
+  a.p = p; a.G = G; a.ws = (float*)ws; a.orbit = orbit; a.out = out;
+  a.ldg = ldg; a.ldo = ldo; a.n = (int)n;
   a.stages = pl.stages;
   a.log2_br = 0;
   while ((1u << a.log2_br) < p.Br) ++a.log2_br;
@@ -386,15 +436,18 @@ hipError_t launch_rows(const SketchParams& p, const void* G, int64_t ldg, int64_
 
   if (ev.start) (void)hipEventRecord(ev.start, st);
   hipError_t e;
-#define FS_ROWS(T, MT, ET) \
-  (pl.staged ? go(rows_kernel<T, MT, ET, true>, grid, pl.lds, st, a) : go(rows_kernel<T, MT, ET, false>, grid, pl.lds, st, a))
+#define FS_ROWS(T, MT, ET)                                                                        \
+  (pl.out_stat ? (pl.staged ? go(rows_kernel<T, MT, ET, true, true>, grid, pl.lds, st, a)           \
+                            : go(rows_kernel<T, MT, ET, false, true>, grid, pl.lds, st, a))         \
+               : (pl.staged ? go(rows_kernel<T, MT, ET, true, false>, grid, pl.lds, st, a)          \
+                            : go(rows_kernel<T, MT, ET, false, false>, grid, pl.lds, st, a)))
   if (dt == FS_BF16)
     e = pl.mt == 1 ? FS_ROWS(uint16_t, 1, 4) : pl.mt == 2 ? FS_ROWS(uint16_t, 2, 4) : FS_ROWS(uint16_t, 4, 2);
   else
     e = pl.mt == 1 ? FS_ROWS(float, 1, 4) : pl.mt == 2 ? FS_ROWS(float, 2, 4) : FS_ROWS(float, 4, 2);
 #undef FS_ROWS
   if (ev.stop) (void)hipEventRecord(ev.stop, st);
-  if (e != hipSuccess) return e;
+  if (e != hipSuccess || pl.out_stat) return e;
   const int vec = p.Br % 4 == 0 ? 4 : 1;
   const int64_t work = n * (p.k / vec);
   const dim3 rgrid((unsigned)((work + 255) / 256));

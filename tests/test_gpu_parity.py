@@ -437,6 +437,10 @@ ROWS = [
     ((8192, 512, 1024, 64, 2, 8), 130, 0, 0),       # mid-config blocks, kappa = 2
     ((2048, 1024, 64, 32, 1, 1), 33, 0, 0),         # kappa = 1, one stage per block, s = 1
     ((65536, 8192, 64, 8, 8, 2), 64, 0, 0),         # M = 1024
+    ((8192, 1024, 512, 64, 4, 8), 200, 0, 0),       # kappa*Br = 256: output-stationary, mid-config blocks
+    ((16384, 1024, 2048, 128, 4, 8), 130, 8, 0),    # wide-config blocks, Br = 128
+    ((4096, 1024, 128, 32, 8, 1), 64, 0, 4),        # Br = 32, kappa = 8, two stages per block
+    ((2048, 4096, 64, 128, 3, 32), 40, 0, 0),       # one stage per block, s = 32
 ]
 
 
@@ -484,8 +488,8 @@ def test_apply_rows_one_hot_rows_reproduce_columns_exactly():
 
 def test_apply_rows_unsupported_shapes_report_unsupported():
     G = torch.zeros((4, 8192), device=DEV)
-    for params in [(8192, 1024, 512, 64, 4, 8),      # kappa*Br = 256
-                   (8192, 512, 96 * 0 + 1024, 64, 1, 8)]:   # fine shape, checked below with a bad stride
+    for params in [(8192, 2048, 64, 16, 16, 2),      # kappa*Br = 256 with Br = 16: no kernel
+                   (8192, 512, 1024, 64, 1, 8)]:     # fine shape, checked below with a bad stride
         sk = B.Sketch(*params, seed=0)
         if params[4] * params[3] > 128:
             with pytest.raises(B.FlashSketchError) as e:
