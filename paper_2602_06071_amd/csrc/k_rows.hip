@@ -76,8 +76,23 @@ void rows_kernel(RowsArgs a) {
   uint16_t* s_phi = reinterpret_cast<uint16_t*>(smem + 2 * MAX_KAPPA * 4);
   unsigned char* s_g = smem + 2 * MAX_KAPPA * 4 + TILE * 2;  // STAGED: [32][GLD] bytes
 
-  const uint32_t blk = blockIdx.x;  // input block h (OUT: output block g)
-  const int ex0 = (int)blockIdx.y * (32 * ET);
+  // Which (block, example tile) this wave takes.  OUT with an orbit table: work-groups are
+  // renumbered so that the ones an XCD runs side by side (the hardware deals linear ids
+  // round-robin over the 8 XCDs) are consecutive orbit positions of one example tile, and each
+  // visits its kappa neighbours in the order of their orbit position modulo kappa: the kappa
+  // readers of an input block then touch it at the same time and the re-reads hit that XCD's L2.
+  uint32_t blk = blockIdx.x;  // input block h (OUT: output block g)
+  uint32_t ey = blockIdx.y, opos = 0;
+  const bool remap = OUT && a.orbit != nullptr;
+  if (remap) {
+    const uint32_t total = gridDim.x * gridDim.y;
+    uint32_t id = blockIdx.y * gridDim.x + blockIdx.x;
+    if (total % 8 == 0) id = (id % 8) * (total / 8) + id / 8;
+    opos = id % gridDim.x;
+    ey = id / gridDim.x;
+    blk = __builtin_amdgcn_readfirstlane(a.orbit[opos]);
+  }
+  const int ex0 = (int)ey * (32 * ET);
   const int z = (int)blockIdx.z;
   const int T_stages = a.stages;
   const uint32_t lbr = a.log2_br;
@@ -85,7 +100,12 @@ void rows_kernel(RowsArgs a) {
   // slot tables and an empty tile
   for (int sl = lane; sl < (int)p.kappa; sl += 64) {
     uint32_t x = blk;
-    for (int l = 0; l <= sl; ++l) x = OUT ? wire_next(x, p.a, p.b, p.M) : wire_prev(x, p.a_inv, p.b, p.M);
+    if (remap) {
+      const uint32_t l = (sl + p.kappa - (opos + 1) % p.kappa) % p.kappa;  // 0 .. kappa-1
+      x = a.orbit[(opos + 1 + l) % p.M];
+    } else {
+      for (int l = 0; l <= sl; ++l) x = OUT ? wire_next(x, p.a, p.b, p.M) : wire_prev(x, p.a_inv, p.b, p.M);
+    }
     s_blk[sl] = x;
     s_bk[sl] = OUT ? block_key(p.key1, blk, x, p.M) : block_key(p.key1, x, blk, p.M);
   }
