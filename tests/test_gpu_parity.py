@@ -348,6 +348,26 @@ def test_full_config_grad_rows_layout_sampled():
     check(out[idx], ref, cfg.dtype, "grad rows layout, sampled examples")
 
 
+@pytest.mark.parametrize("params,n", [
+    ((65536, 65536, 65536, 65536, 1, 2), 8),     # Br at its maximum, one block
+    ((1 << 20, 1 << 20, 1, 1, 5, 1), 3),         # Br = Bc = 1, M = 2^20 blocks
+    ((4096, 32768, 1, 8, 7, 8), 5),              # expanding sketch (k > d), s = Br
+])
+def test_extreme_shapes(params, n):
+    """Limits of the parameter ranges the header allows; these run on the generic kernel."""
+    print("extreme", params, n, flush=True)
+    A = torch.randn((params[0], n), generator=torch.Generator(device=DEV).manual_seed(4), device=DEV)
+    sk = B.Sketch(*params, seed=3)
+    out = sk.apply(A)
+    rows, signs = sk.export()
+    torch.cuda.synchronize()
+    P = O.Params(*params)
+    check(out, O.apply(O.build_csc(P, 3), host64(A)), torch.float32, "extreme shape")
+    want_r, want_s = O.build_tables(P, 3)
+    assert np.array_equal(rows.cpu().numpy().astype(np.int64), want_r)
+    assert np.array_equal(signs.cpu().numpy(), want_s)
+
+
 # ------------------------------------------------ boundary behaviour ------
 def test_caller_workspace_and_too_small_workspace():
     params, n = (65536, 8192, 64, 8, 8, 2), 256
