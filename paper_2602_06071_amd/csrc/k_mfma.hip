@@ -7,12 +7,12 @@
 // v_mfma_f32_32x32x16_bf16 into fp32 accumulators: products with 0/+-1 are
 // exact, so the result is the same sum in a different order.
 //
-//  * Phi is never stored in HBM: per 64-row stage of A, the work-group hashes the
+//  * Phi is never stored in HBM: per 64-row stage of A, every wave hashes the
 //    (block, row) pairs it needs (one lane per pair, Appendix E "Within-block
-//    hashing"), scatters the s nonzeros of each into a zeroed LDS tile
-//    [stacked row][64 + 8 pad] and every wave reads its MFMA operand from there
-//    with one 128-bit LDS read.  Three LDS tiles rotate (consume / fill / clear),
-//    one barrier per stage.
+//    hashing"), scatters the s nonzeros of each into its own zeroed LDS tile
+//    [stacked row][64 + 8 pad] and reads its MFMA operands from there with 128-bit
+//    LDS reads.  Two tiles per wave alternate (consume / clear and refill); nothing is
+//    shared between waves, so the steady state has no barrier.
 //  * A goes HBM -> registers directly: a lane loads 4 consecutive columns of 8
 //    rows (coalesced 256 B / 512 B row segments per half-wave) and transposes
 //    them in registers with v_perm_b32 into four MFMA operands, one per column
