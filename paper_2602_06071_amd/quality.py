@@ -6,7 +6,8 @@ sketch-and-solve residuals, each next to the sketch's kernel time.
 
 The sketches run in the HIP library; the downstream linear algebra (Gram products, QR,
 solves) is plain torch on the same device, in float64 so that the metric itself adds no
-error of its own.  Inputs are synthetic (Gaussian, low-rank + noise) at the paper's shapes.
+error of its own.  Inputs are synthetic (Gaussian, low-rank + noise, and a localized one whose energy sits in
+a single input block: the case the wiring parameter kappa exists for) at the paper's shapes.
 """
 from __future__ import annotations
 
@@ -61,6 +62,9 @@ def make_data(kind: str, d: int, n: int, seed: int, device):
         r = min(32, n)
         A = torch.randn((d, r), generator=g, device=device) @ torch.randn((r, n), generator=g, device=device)
         A = A / r ** 0.5 + 0.01 * torch.randn((d, n), generator=g, device=device)
+    elif kind == "oneblock":  # all energy in the first d/128 rows: one input block at the default k and Br
+        A = torch.zeros((d, n), device=device)
+        A[: d // 128] = torch.randn((d // 128, n), generator=g, device=device)
     else:
         raise KeyError(kind)
     x_true = torch.randn((n, 1), generator=g, device=device)
@@ -115,7 +119,8 @@ def sweep(d, n, k, data, Bc=None, Br=None, s=2, kappas=(1, 2, 4), seed=0, device
             sk = B.Sketch(d, k, Bc, Br, kappa, s, seed=seed)
             res[f"blockperm_kappa{kappa}_s{s}"] = evaluate(sk, A, b)
     for name, kind, args in (
-        ("plain_sjlt_scatter_s%d" % (s * max(kappas)), B.KIND_SJLT_SCATTER, (d, k, d, k, 1, s * max(kappas))),
+        ("plain_sjlt_scatter_s%d" % min(32, s * max(kappas)), B.KIND_SJLT_SCATTER,
+         (d, k, d, k, 1, min(32, s * max(kappas)))),
         ("blockrow_kappa%d_s%d" % (max(kappas), s), B.KIND_BLOCKROW, (d, k, Bc, Br, min(max(kappas), M), s)),
         ("dense_gaussian", B.KIND_GAUSS_DENSE, (d, k, d, k, 1, 1)),
     ):
@@ -131,9 +136,10 @@ def main():
     ap.add_argument("--d", type=int, default=65536)
     ap.add_argument("--n", type=int, default=1024)
     ap.add_argument("--k", type=int, default=4096)
-    ap.add_argument("--data", default="gaussian", choices=["gaussian", "lowrank"])
+    ap.add_argument("--data", default="gaussian", choices=["gaussian", "lowrank", "oneblock"])
+    ap.add_argument("--kappas", default="1,2,4", help="comma-separated wiring parameters to sweep")
     a = ap.parse_args()
-    print(json.dumps(sweep(a.d, a.n, a.k, a.data), indent=1))
+    print(json.dumps(sweep(a.d, a.n, a.k, a.data, kappas=tuple(int(x) for x in a.kappas.split(","))), indent=1))
 
 
 if __name__ == "__main__":

@@ -309,6 +309,29 @@ def test_rows_layout_is_the_same_map_row_by_row():
     np.testing.assert_array_equal(O.apply_rows(S, E), D[:, [0, 40, 95]].T)
 
 
+def test_kappa_buys_robustness_to_localized_inputs():
+    """Section 4 / Section 6: an input whose energy sits in one input block reaches only kappa
+    output blocks, i.e. kappa*Br rows of S A.  With more columns than that the sketch cannot be
+    an embedding (rank argument: the OSE error is at least 1 exactly); a larger kappa spreads
+    the block over enough rows.  A dense (non-localized) input does not care."""
+    d, k, Bc, Br, s, n = 4096, 512, 256, 32, 4, 48     # M = 16
+    rng = np.random.default_rng(0)
+    A = np.zeros((d, n))
+    A[:Bc] = rng.standard_normal((Bc, n))              # all energy in input block 0
+    Q = np.linalg.qr(A)[0]
+    errs = {}
+    for kappa in (1, 2, 4, 8, 16):
+        S = O.build_csc(O.Params(d, k, Bc, Br, kappa, s), 1)
+        SQ = O.apply(S, Q)
+        assert (np.abs(SQ).sum(1) > 0).sum() <= kappa * Br      # only kappa output blocks are reached
+        errs[kappa] = O.ose_error(SQ)
+    assert errs[1] >= 1 - 1e-9                          # 32 rows cannot embed 48 dimensions
+    assert errs[1] > errs[2] > errs[4] > errs[8] > errs[16]   # more neighbours, less distortion
+    assert errs[16] < 0.9                               # M = 16 neighbours: the whole sketch is used
+    Qd = np.linalg.qr(rng.standard_normal((d, n)))[0]   # dense input: kappa = 1 is already fine
+    assert O.ose_error(O.apply(O.build_csc(O.Params(d, k, Bc, Br, 1, s), 1), Qd)) < 0.9
+
+
 # ---------------------------------------------------------------- P10 -----
 @pytest.mark.parametrize("kappa", [1, 2, 4, 8])
 def test_coherence_bounds(kappa):
