@@ -1,0 +1,48 @@
+"""Choosing the block sizes (Br, Bc) of a BlockPerm-SJLT for given (d, k, kappa).
+
+The paper treats (Br, Bc) as tuned template parameters (Appendix C, "Tuning").  This helper
+encodes what the kernels of this library prefer, in that order:
+
+  1. kappa*Br in {128, 64, 32}: the input-stationary matrix-core path, which reads A once;
+  2. Br in {128, 64, 32}: the output-stationary matrix-core path (A read kappa times);
+  3. any Br dividing k (generic kernel).
+
+subject to the sketch's own constraints: Br | k, M = k/Br = ceil(d/Bc), kappa <= M, s <= Br,
+and for the matrix-core paths Bc a multiple of 64.  It only does integer arithmetic on shapes;
+nothing here touches the sketch's hash or values.
+"""
+from __future__ import annotations
+
+
+def _bc_for(d: int, M: int, multiple: int):
+    """Smallest Bc that is a multiple of `multiple` with ceil(d / Bc) == M, or None."""
+    bc = -(-d // M)                      # ceil(d / M): the smallest Bc with ceil(d/Bc) <= M
+    bc = -(-bc // multiple) * multiple   # round up
+    return bc if -(-d // bc) == M else None
+
+
+def suggest_blocks(d: int, k: int, kappa: int, s: int = 2):
+    """Return (Bc, Br, path) with path in {"in", "out", "generic"}, or raise ValueError when no
+    block grid satisfies the constraints (e.g. kappa > k)."""
+    if min(d, k, kappa, s) < 1:
+        raise ValueError("d, k, kappa, s must be positive")
+
+    def ok(br):
+        if br < s or br > 65536 or k % br:
+            return False
+        M = k // br
+        return kappa <= M <= (1 << 24) and M <= d
+
+    for path, cands in (("in", [r // kappa for r in (128, 64, 32) if r % kappa == 0]),
+                        ("out", [128, 64, 32])):
+        for br in cands:
+            if br >= 1 and (br & (br - 1)) == 0 and ok(br):
+                bc = _bc_for(d, k // br, 64)
+                if bc is not None:
+                    return bc, br, path
+    for br in sorted((b for b in range(1, min(k, 65536) + 1) if k % b == 0), key=lambda b: abs(b - 32)):
+        if ok(br):
+            bc = _bc_for(d, k // br, 1)
+            if bc is not None:
+                return bc, br, "generic"
+    raise ValueError(f"no block grid for d={d}, k={k}, kappa={kappa}, s={s}")
