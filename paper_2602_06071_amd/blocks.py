@@ -3,7 +3,9 @@
 The paper treats (Br, Bc) as tuned template parameters (Appendix C, "Tuning").  This helper
 encodes what the kernels of this library prefer, in that order:
 
-  1. kappa*Br in {128, 64, 32}: the input-stationary matrix-core path, which reads A once;
+  1. kappa*Br in {64, 32, 128} (in this order: measured 5-10 % apart on HBM-bound shapes, 64 also
+     being the shape with the orbit-run merge): the input-stationary matrix-core path, which
+     reads A once;
   2. Br in {128, 64, 32}: the output-stationary matrix-core path (A read kappa times);
   3. any Br dividing k (generic kernel).
 
@@ -33,7 +35,7 @@ def suggest_blocks(d: int, k: int, kappa: int, s: int = 2):
         M = k // br
         return kappa <= M <= (1 << 24) and M <= d
 
-    for path, cands in (("in", [r // kappa for r in (128, 64, 32) if r % kappa == 0]),
+    for path, cands in (("in", [r // kappa for r in (64, 32, 128) if r % kappa == 0]),
                         ("out", [128, 64, 32])):
         for br in cands:
             if br >= 1 and (br & (br - 1)) == 0 and ok(br):
