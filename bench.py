@@ -203,10 +203,30 @@ def extra_measurements(torch, B, W, dev, skip, with_oracle):
         return {"kernel_ms": t * 1e3, "GBps_A": cfg.a_bytes / len(chunks_of(cfg)) / t / 1e9,
                 "variant": used}
 
+    def cold(cfg, A, reps=5):
+        """Kernel time of single applies, each after 2 GiB of unrelated writes have gone through the
+        caches (L2 and the 256 MB Infinity Cache hold nothing of A or of the workspace)."""
+        sk = B.Sketch(*cfg.params, seed=cfg.sketch_seed)
+        out = sk.apply(A)
+        junk = torch.empty(1 << 29, device=dev, dtype=torch.float32)
+        ms = []
+        for i in range(reps):
+            junk.fill_(float(i))
+            sk.profile_begin(1)
+            sk.apply(A, out)
+            ms += sk.profile_end()
+        sk.close()
+        t = sum(ms) / len(ms) / 1e3
+        return {"kernel_ms": t * 1e3, "GBps_A": cfg.a_bytes / t / 1e9}
+
     for name in ("tiny", "tall"):
         if name != skip:
             cfg = W.CONFIGS[name]
-            res[name] = one(cfg, W.make_input(cfg, dev))
+            A = W.make_input(cfg, dev)
+            res[name] = one(cfg, A)
+            if name == "tall":  # 256 MiB: about the size of the Infinity Cache, so also time it cold
+                res["tall_cold"] = cold(cfg, A)
+            del A
     if skip != "tall":
         res["tall_ose"] = tall_distortion(torch, B, W, dev, with_oracle)
     if skip != "mid":
