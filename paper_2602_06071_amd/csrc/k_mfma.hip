@@ -736,7 +736,10 @@ Plan make_plan(const SketchParams& p, const void* A, int64_t lda, int64_t n, fs_
   // workspace traffic (write + read of the partial planes) relative to reading A once
   const double rho = 2.0 * zs * p.kappa * (double)p.k * 4.0 / ((double)p.d * esz);
   const bool out_starved = (int64_t)p.M * col_tiles < 256;  // fewer output tiles than CUs
-  pl.in_stat = can_in && (!can_out || rho <= 0.6 || out_starved);
+  // IN pays for its partial planes (rho, written at about half the read rate), OUT for kappa-1
+  // re-reads of A that mostly hit L2 (about 0.3 of an HBM read each): measured cross-over
+  // rho ~ 0.23 (kappa - 1).  With kappa = 1 there is nothing to re-read and OUT stores directly.
+  pl.in_stat = can_in && (!can_out || (p.kappa > 1 && (out_starved || rho <= 0.23 * (p.kappa - 1))));
   if (pl.in_stat) {
     pl.mt = mt_i; pl.nrg = nrg_i; pl.zsplit = zs;
     pl.stages = (int)(p.Bc / zs / KC);
