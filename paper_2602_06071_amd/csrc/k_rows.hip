@@ -387,10 +387,15 @@ RowsPlan make_rows_plan(const SketchParams& p, const void* G, int64_t ldg, int64
   const size_t esz = dt == FS_F32 ? 4 : 2;
   if (!p.br_pow2 || p.Bc % KC || p.d % p.Bc || p.kappa > (uint32_t)MAX_KAPPA || n < 1) return pl;
   const uint64_t rw = (uint64_t)p.kappa * p.Br;
-  if (rw == 32) { pl.mt = 1; pl.et = 4; }
+  const bool br_tile = p.Br == 32 || p.Br == 64 || p.Br == 128;
+  if (p.kappa == 1 && br_tile) {  // nothing is re-read: output-stationary stores the result directly
+    pl.out_stat = true;
+    pl.mt = (int)p.Br / 32;
+    pl.et = pl.mt == 4 ? 2 : 4;
+  } else if (rw == 32) { pl.mt = 1; pl.et = 4; }
   else if (rw == 64) { pl.mt = 2; pl.et = 4; }
   else if (rw == 128) { pl.mt = 4; pl.et = 2; }
-  else if (p.Br == 32 || p.Br == 64 || p.Br == 128) {  // too many stacked rows: output-stationary
+  else if (br_tile) {  // too many stacked rows: output-stationary
     pl.out_stat = true;
     pl.mt = (int)p.Br / 32;
     pl.et = pl.mt == 4 ? 2 : 4;
