@@ -486,6 +486,9 @@ def test_apply_rows_matches_oracle(case, dtype):
     tol = (2e-5 if dtype == torch.float32 else 8e-3)
     diff = np.abs(host64(obuf[:, :k]) - ref)
     assert (diff <= tol * (np.abs(ref) + np.sqrt((ref ** 2).mean()))).all()
+    again = sk.apply_rows(G)                      # no atomics on data: bit-identical run to run
+    torch.cuda.synchronize()
+    assert torch.equal(again, obuf[:, :k])
     # and it is the transpose of the column-layout apply, to rounding
     colwise = sk.apply(G.t().contiguous())
     torch.cuda.synchronize()
