@@ -56,14 +56,16 @@ struct GaussArgs {
   int n, stages, out_vec;
 };
 
-// Work-group: RW = 32*MT*NRG rows of S x 256 columns of A; wave: 32*MT rows x 128 columns.
-template <typename T, int MT, int NRG>
-__global__ __launch_bounds__(64 * NRG * 2) __attribute__((amdgpu_waves_per_eu(2)))
+// Work-group: RW = 32*MT*NRG rows of S x 128*NCG columns of A; wave: 32*MT rows x 128 columns.
+// MT = 4 keeps the 256 accumulators in AGPRs with one wave per SIMD: four times the MFMA work per
+// loaded (and, for fp32, per split) element of A than MT = 1.
+template <typename T, int MT, int NRG, int NCG>
+__global__ __launch_bounds__(64 * NRG * NCG) __attribute__((amdgpu_waves_per_eu(MT > 2 ? 1 : 2)))
 void gauss_kernel(GaussArgs a) {
   using V = typename Ld<T>::V;
   constexpr int PFD = Ld<T>::PFD;
   constexpr int PARTS = sizeof(T) == 4 ? 3 : 1;
-  constexpr int NCG = 2, NW = NRG * NCG, NT = 64 * NW;
+  constexpr int NW = NRG * NCG, NT = 64 * NW;
   constexpr int RW = 32 * MT * NRG;
   constexpr int TILE = RW * PHI_LD;
   constexpr int SREG = RW * 8 / NT;  // 16-byte pieces of one S tile per thread
@@ -165,15 +167,20 @@ void gauss_kernel(GaussArgs a) {
               xs[j] = c == 0 ? cur[j].x : c == 1 ? cur[j].y : c == 2 ? cur[j].z : cur[j].w;
             uint4 hi, mid, lo;
             split_ops(xs, hi, mid, lo);
+            // product by product over the row tiles: with MT = 4 an accumulator is reused only
+            // after three other MFMAs (back-to-back dependent MFMAs stall the matrix pipe)
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-              acc[mt][c] = mfma(pa[0][mt], hi, acc[mt][c]);
-              acc[mt][c] = mfma(pa[0][mt], mid, acc[mt][c]);
-              acc[mt][c] = mfma(pa[1][mt], hi, acc[mt][c]);
-              acc[mt][c] = mfma(pa[0][mt], lo, acc[mt][c]);
-              acc[mt][c] = mfma(pa[2][mt], hi, acc[mt][c]);
-              acc[mt][c] = mfma(pa[1][mt], mid, acc[mt][c]);
-            }
+            for (int mt = 0; mt < MT; ++mt) acc[mt][c] = mfma(pa[0][mt], hi, acc[mt][c]);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) acc[mt][c] = mfma(pa[0][mt], mid, acc[mt][c]);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) acc[mt][c] = mfma(pa[1][mt], hi, acc[mt][c]);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) acc[mt][c] = mfma(pa[0][mt], lo, acc[mt][c]);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) acc[mt][c] = mfma(pa[2][mt], hi, acc[mt][c]);
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) acc[mt][c] = mfma(pa[1][mt], mid, acc[mt][c]);
           }
           if (fetch) issue(t * KSTEPS + ks + PFD, cur);
         }
@@ -248,7 +255,7 @@ bool gauss_supported(int64_t k, int64_t d, const void* A, int64_t lda, int64_t n
   if (d % KC || k % 128 || n < 1) return false;
   if ((uintptr_t)A % (4 * esz) || lda % 4) return false;
   if (d * lda * esz >= ((int64_t)1 << 31)) return false;  // 32-bit buffer offsets over all of A
-  return (n + 255) / 256 <= 65535;
+  return (n + 255) / 256 <= 65535;  // (the widest column tile is 512)
 }
 
 hipError_t launch_gauss(const void* storage, int64_t k, int64_t d, const void* A, int64_t lda,
@@ -266,11 +273,19 @@ hipError_t launch_gauss(const void* storage, int64_t k, int64_t d, const void* A
   if (dt == FS_BF16) {
     a.S[0] = b; a.S[1] = a.S[2] = nullptr;
     constexpr int RW = 128;
-    e = go(gauss_kernel<uint16_t, 2, 2>, dim3((unsigned)(k / RW), col_tiles), 256, 2 * RW * PHI_LD * 2, st, a);
+    e = go(gauss_kernel<uint16_t, 2, 2, 2>, dim3((unsigned)(k / RW), col_tiles), 256, 2 * RW * PHI_LD * 2, st, a);
   } else {
     a.S[0] = b + k * d; a.S[1] = b + 2 * k * d; a.S[2] = b + 3 * k * d;
-    constexpr int RW = 64;
-    e = go(gauss_kernel<float, 1, 2>, dim3((unsigned)(k / RW), col_tiles), 256, 2 * 3 * RW * PHI_LD * 2, st, a);
+    // 128-row x 512-column work-groups when they still fill most of the chip, else 64 x 256
+    const int64_t wide_tiles = (n + 511) / 512;
+    if ((k / 128) * wide_tiles >= 192) {
+      constexpr int RW = 128;
+      e = go(gauss_kernel<float, 4, 1, 4>, dim3((unsigned)(k / RW), (unsigned)wide_tiles), 256,
+             2 * 3 * RW * PHI_LD * 2, st, a);
+    } else {
+      constexpr int RW = 64;
+      e = go(gauss_kernel<float, 1, 2, 2>, dim3((unsigned)(k / RW), col_tiles), 256, 2 * 3 * RW * PHI_LD * 2, st, a);
+    }
   }
   if (ev.stop) (void)hipEventRecord(ev.stop, st);
   return e;

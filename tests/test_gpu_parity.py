@@ -248,7 +248,8 @@ def test_plain_sjlt_scatter_matches_oracle(d, k, s, n, dtype):
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
-@pytest.mark.parametrize("k,d,n,pad", [(128, 1024, 256, 0), (256, 4096, 300, 4), (1024, 2048, 1000, 0)])
+@pytest.mark.parametrize("k,d,n,pad", [(128, 1024, 256, 0), (256, 4096, 300, 4), (1024, 2048, 1000, 0),
+                                       (1024, 256, 12328, 0)])  # enough tiles for the 128 x 512 fp32 work-groups
 def test_dense_gaussian_matches_oracle(k, d, n, pad, dtype):
     from oracle import gaussian as G
     print("gauss", k, d, n, dtype, flush=True)
