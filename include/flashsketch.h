@@ -195,7 +195,9 @@ fs_status fs_sketch_set_variant(fs_sketch_t h, fs_variant v);
 fs_status fs_sketch_profile_begin(fs_sketch_t h, int32_t max_launches);
 fs_status fs_sketch_profile_end(fs_sketch_t h, float* ms, int32_t* count);
 
-/* Frees the handle and any device memory it owns (not caller workspaces). */
+/* Frees the handle and any device memory it owns (not caller workspaces).  Like every call
+ * that frees device memory it must not run while a stream is being captured into a HIP graph
+ * (HIP invalidates the capture). */
 fs_status fs_sketch_destroy(fs_sketch_t h);
 
 const char* fs_status_string(fs_status st);

@@ -96,22 +96,54 @@ def _stream_ptr(stream) -> int:
     return int(stream.cuda_stream)
 
 
+_deferred: list = []  # handles whose destruction was postponed (see Sketch.__del__)
+
+
+def _capturing() -> bool:
+    try:
+        return torch.cuda.is_available() and torch.cuda.is_current_stream_capturing()
+    except Exception:
+        return False
+
+
+def _flush_deferred() -> None:
+    if _deferred and not _capturing():
+        while _deferred:
+            lib.fs_sketch_destroy(_deferred.pop())
+
+
 class Sketch:
     """Owns one fs_sketch_t.  Methods map one-to-one onto the C entry points."""
 
     def __init__(self, d, k, Bc, Br, kappa, s, seed=0, kind=KIND_BLOCKPERM):
         self._h = C.c_void_p()
+        _flush_deferred()
         _check(lib.fs_sketch_create_kind(C.byref(self._h), kind, d, k, Bc, Br, kappa, s, seed),
                "fs_sketch_create_kind")
         self.d, self.k = d, k
         self._ws_keepalive = None
 
     def close(self) -> None:
+        """Destroy the handle (frees its device memory).  Also flushes handles whose destruction
+        the garbage collector had to postpone."""
+        _flush_deferred()
         if self._h:
             lib.fs_sketch_destroy(self._h)
             self._h = C.c_void_p()
 
-    __del__ = close
+    def __del__(self):
+        # Freeing device memory is not allowed while a stream is being captured into a HIP graph
+        # (it invalidates the capture), and the garbage collector may run at any time: if a
+        # capture is under way the handle is parked and destroyed by the next close() / Sketch().
+        try:
+            if self._h:
+                if _capturing():
+                    _deferred.append(self._h)
+                    self._h = C.c_void_p()
+                else:
+                    self.close()
+        except Exception:  # interpreter shutdown: modules may already be gone
+            pass
 
     def info(self) -> fs_info:
         out = fs_info()

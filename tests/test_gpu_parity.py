@@ -5,6 +5,7 @@ Bars: indices and signs bit-exact; relative Frobenius error <= 1e-5 for fp32
 inputs and <= 4e-3 for bf16 inputs/outputs with fp32 accumulation.
 """
 import functools
+import gc
 
 import numpy as np
 import pytest
@@ -432,6 +433,7 @@ def test_chunked_apply_replays_from_a_hip_graph(params, n, chunk):
     torch.cuda.synchronize()
     out = torch.zeros_like(eager)
     graph = torch.cuda.CUDAGraph()
+    gc.collect()  # nothing that frees device memory may run during the capture (HIP rule)
     with torch.cuda.graph(graph):
         for c in range(0, n, chunk):
             sk.apply(A[:, c:c + chunk], out[:, c:c + chunk])
@@ -526,6 +528,35 @@ def test_apply_rows_unsupported_shapes_report_unsupported():
                 sk.apply_rows(odd)
             assert e.value.status == 2
     torch.cuda.synchronize()
+
+
+def test_handle_collected_during_a_capture_does_not_break_it():
+    """Destroying a handle frees device memory, which HIP forbids while a stream is capturing.  A
+    handle that the garbage collector finds during a capture is parked by the binding and
+    destroyed later; the capture stays valid."""
+    params, n = (32768, 64, 4096, 8, 8, 2), 256
+    A = torch.randn((params[0], n), device=DEV).to(torch.bfloat16)
+    sk = B.Sketch(*params, seed=2)
+    eager = sk.apply(A)
+
+    class Cycle:  # a dead reference cycle holding a used handle: only the cyclic collector frees it
+        pass
+    c = Cycle()
+    c.me, c.sk = c, B.Sketch(*params, seed=3)
+    c.sk.apply(A)
+    torch.cuda.synchronize()
+    del c
+    out = torch.zeros_like(eager)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        gc.collect()          # the cycle dies here, inside the capture
+        sk.apply(A, out)
+    assert len(B._deferred) >= 1  # (dead handles of earlier tests may have been found as well)
+    graph.replay()
+    torch.cuda.synchronize()
+    assert torch.equal(out, eager)
+    sk.close()                # flushes the parked handle
+    assert len(B._deferred) == 0
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
