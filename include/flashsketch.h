@@ -38,7 +38,7 @@
  *              A handle must not be used from two streams at the same time
  *              (its workspace is shared).
  *   Precision  accumulation is always fp32; one fp32 multiply by
- *              (float)(1/sqrt(kappa*s)) follows; bf16 outputs are rounded to
+ *              (float)(1/sqrt(kappa*s)) follows; bf16 and half outputs are rounded to
  *              nearest-even.
  *   Errors     every call returns fs_status; nothing throws, aborts or prints.
  *              Argument errors are detected before any HIP call is made.
@@ -66,7 +66,11 @@ typedef enum {
   FS_ERR_HIP = 4          /* a HIP runtime call failed (see fs_info)       */
 } fs_status;
 
-typedef enum { FS_F32 = 0, FS_BF16 = 1 } fs_dtype; /* dtype of A and of out */
+/* dtype of A and of out.  The paper's kernels are fp32 only (Section 6 names other precisions
+ * as future work); the 16-bit types here accumulate in fp32 and round the result once, to
+ * nearest even.  FS_F16 is IEEE binary16: subnormal inputs count with their value, results
+ * beyond +-65504 become infinities. */
+typedef enum { FS_F32 = 0, FS_BF16 = 1, FS_F16 = 2 } fs_dtype;
 
 typedef enum {
   FS_KIND_BLOCKPERM = 0,    /* the paper's sketch (Section 4)                              */
@@ -77,7 +81,7 @@ typedef enum {
   FS_KIND_GAUSS_DENSE = 2,  /* dense Gaussian sketch S_ij ~ N(0, 1/k) (Section 1) applied
                                by an MFMA GEMM; Bc, Br, kappa, s are ignored.  Reference
                                point only: needs 64 | d, 128 | k, 4 | lda, a 16-byte (fp32)
-                               or 8-byte (bf16) aligned A and d*lda*sizeof(elt) < 2^31,
+                               or 8-byte (bf16, half) aligned A and d*lda*sizeof(elt) < 2^31,
                                else apply returns FS_ERR_UNSUPPORTED.                      */
   FS_KIND_BLOCKROW = 3      /* FlashBlockRow (Appendix D, Alg. 2): gather-only block-row
                                sampling.  Same parameters as BLOCKPERM; output row (g, r)

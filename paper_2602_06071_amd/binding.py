@@ -13,7 +13,7 @@ import torch  # must precede the CDLL: the library binds to the HIP runtime torc
 _HERE = os.path.dirname(os.path.abspath(__file__))
 lib_path = os.environ.get("FLASHSKETCH_LIB") or os.path.join(_HERE, "libflashsketch.so")
 
-FS_F32, FS_BF16 = 0, 1
+FS_F32, FS_BF16, FS_F16 = 0, 1, 2
 KIND_BLOCKPERM, KIND_SJLT_SCATTER, KIND_GAUSS_DENSE, KIND_BLOCKROW = 0, 1, 2, 3
 VARIANT_AUTO, VARIANT_GENERIC, VARIANT_MFMA = 0, 1, 2
 
@@ -82,11 +82,16 @@ def _check(st: int, what: str) -> None:
         raise FlashSketchError(st, what)
 
 
+_DTYPE_CODES = {torch.float32: 0, torch.bfloat16: 1, torch.float16: 2}
+
+
 def _dtype_code(t: torch.Tensor) -> int:
     if t.dtype == torch.float32:
         return FS_F32
     if t.dtype == torch.bfloat16:
         return FS_BF16
+    if t.dtype == torch.float16:
+        return FS_F16
     raise TypeError(f"unsupported dtype {t.dtype}")
 
 
@@ -155,7 +160,7 @@ class Sketch:
 
     def workspace_bytes(self, n: int, dtype: torch.dtype) -> int:
         out = C.c_size_t()
-        code = FS_F32 if dtype == torch.float32 else FS_BF16
+        code = _DTYPE_CODES[dtype]
         _check(lib.fs_sketch_workspace_bytes(self._h, n, code, C.byref(out)), "fs_sketch_workspace_bytes")
         return out.value
 
@@ -210,7 +215,7 @@ class Sketch:
 
     def rows_workspace_bytes(self, n: int, dtype: torch.dtype) -> int:
         out = C.c_size_t()
-        code = FS_F32 if dtype == torch.float32 else FS_BF16
+        code = _DTYPE_CODES[dtype]
         _check(lib.fs_sketch_rows_workspace_bytes(self._h, n, code, C.byref(out)),
                "fs_sketch_rows_workspace_bytes")
         return out.value

@@ -50,6 +50,8 @@ void derive_wiring(uint32_t M, uint32_t key1, uint32_t* a, uint32_t* b, uint32_t
 
 bool is_pow2(uint32_t x) { return x && !(x & (x - 1)); }
 
+bool valid_dtype(fs_dtype dt) { return dt == FS_F32 || dt == FS_BF16 || dt == FS_F16; }
+
 fs_status hip_fail(fs_sketch_t h, hipError_t e) {
   if (h) h->last_hip_error = (int)e;
   (void)hipGetLastError();  // clear the sticky launch error
@@ -266,7 +268,7 @@ fs_status fs_sketch_set_variant(fs_sketch_t h, fs_variant v) {
 }
 
 fs_status fs_sketch_workspace_bytes(fs_sketch_t h, int64_t n, fs_dtype dt, size_t* bytes) {
-  if (!h || !bytes || n < 0 || (dt != FS_F32 && dt != FS_BF16)) return FS_ERR_INVALID_ARG;
+  if (!h || !bytes || n < 0 || !valid_dtype(dt)) return FS_ERR_INVALID_ARG;
   *bytes = 0;
   if (n == 0) return FS_OK;
   // Size for the best case of a well-aligned call: an aligned dummy pointer
@@ -294,7 +296,7 @@ fs_status fs_sketch_set_workspace(fs_sketch_t h, void* dev_ptr, size_t bytes) {
 
 fs_status fs_sketch_apply_ld(fs_sketch_t h, const void* A, int64_t lda, int64_t n, void* out,
                              int64_t ldo, fs_dtype dt, void* stream) {
-  if (!h || n < 0 || (dt != FS_F32 && dt != FS_BF16)) return FS_ERR_INVALID_ARG;
+  if (!h || n < 0 || !valid_dtype(dt)) return FS_ERR_INVALID_ARG;
   if (n == 0) return FS_OK;
   if (!A || !out || lda < n || ldo < n) return FS_ERR_INVALID_ARG;
   if (n > 0x7fffffff || lda > ((int64_t)1 << 40) || ldo > ((int64_t)1 << 40)) return FS_ERR_INVALID_ARG;
@@ -340,7 +342,7 @@ fs_status fs_sketch_apply_ld(fs_sketch_t h, const void* A, int64_t lda, int64_t 
 
 fs_status fs_sketch_apply_rows(fs_sketch_t h, const void* G, int64_t ldg, int64_t n, void* out,
                                int64_t ldo, fs_dtype dt, void* stream) {
-  if (!h || n < 0 || (dt != FS_F32 && dt != FS_BF16)) return FS_ERR_INVALID_ARG;
+  if (!h || n < 0 || !valid_dtype(dt)) return FS_ERR_INVALID_ARG;
   if (n == 0) return FS_OK;
   if (!G || !out || ldg < h->p.d || ldo < h->p.k) return FS_ERR_INVALID_ARG;
   if (n > 0x7fffffff || ldg > ((int64_t)1 << 40) || ldo > ((int64_t)1 << 40)) return FS_ERR_INVALID_ARG;
@@ -367,7 +369,7 @@ fs_status fs_sketch_apply_rows(fs_sketch_t h, const void* G, int64_t ldg, int64_
 }
 
 fs_status fs_sketch_rows_workspace_bytes(fs_sketch_t h, int64_t n, fs_dtype dt, size_t* bytes) {
-  if (!h || !bytes || n < 0 || (dt != FS_F32 && dt != FS_BF16)) return FS_ERR_INVALID_ARG;
+  if (!h || !bytes || n < 0 || !valid_dtype(dt)) return FS_ERR_INVALID_ARG;
   *bytes = 0;
   if (n == 0 || h->kind != FS_KIND_BLOCKPERM) return FS_OK;
   const size_t esz = dt == FS_F32 ? 4 : 2;

@@ -54,9 +54,7 @@ __global__ __launch_bounds__(256) void blockrow_kernel(SketchParams p, const T* 
       if constexpr (VEC) {
         if (full) {
           if constexpr (sizeof(T) == 2) {
-            const uint2 w = *reinterpret_cast<const uint2*>(sp);
-            v[0] = __uint_as_float(w.x << 16); v[1] = __uint_as_float(w.x & 0xFFFF0000u);
-            v[2] = __uint_as_float(w.y << 16); v[3] = __uint_as_float(w.y & 0xFFFF0000u);
+            unpack4<T>(*reinterpret_cast<const uint2*>(sp), v);
           } else {
             const float4 w = *reinterpret_cast<const float4*>(sp);
             v[0] = w.x; v[1] = w.y; v[2] = w.z; v[3] = w.w;
@@ -76,10 +74,9 @@ __global__ __launch_bounds__(256) void blockrow_kernel(SketchParams p, const T* 
   T* dst = out + row * ldo + col0;
   if (VEC && full && out_vec) {
     if constexpr (sizeof(T) == 2) {
-      uint2 w;
-      w.x = (uint32_t)f32_to_bf16_rne(acc[0] * p.scale) | ((uint32_t)f32_to_bf16_rne(acc[CPL > 1 ? 1 : 0] * p.scale) << 16);
-      w.y = (uint32_t)f32_to_bf16_rne(acc[CPL > 2 ? 2 : 0] * p.scale) | ((uint32_t)f32_to_bf16_rne(acc[CPL > 3 ? 3 : 0] * p.scale) << 16);
-      *reinterpret_cast<uint2*>(dst) = w;
+      const float sc[4] = {acc[0] * p.scale, acc[CPL > 1 ? 1 : 0] * p.scale, acc[CPL > 2 ? 2 : 0] * p.scale,
+                           acc[CPL > 3 ? 3 : 0] * p.scale};
+      *reinterpret_cast<uint2*>(dst) = pack4<T>(sc);
     } else {
       *reinterpret_cast<float4*>(dst) = make_float4(acc[0] * p.scale, acc[CPL > 1 ? 1 : 0] * p.scale,
                                                     acc[CPL > 2 ? 2 : 0] * p.scale, acc[CPL > 3 ? 3 : 0] * p.scale);
@@ -123,8 +120,9 @@ hipError_t launch_blockrow(const SketchParams& p, const void* A, int64_t lda, in
   dim3 grid((unsigned)row_groups, (unsigned)col_tiles), block(256);
   if (ev.start) (void)hipEventRecord(ev.start, st);
 #define FS_GO(T, V) hipLaunchKernelGGL((blockrow_kernel<T, V>), grid, block, 0, st, p, (const T*)A, lda, (int)n, (T*)out, ldo, out_vec)
-  if (dt == FS_F32) { if (vec) FS_GO(float, true); else FS_GO(float, false); }
-  else              { if (vec) FS_GO(uint16_t, true); else FS_GO(uint16_t, false); }
+  if (dt == FS_F32)       { if (vec) FS_GO(float, true); else FS_GO(float, false); }
+  else if (dt == FS_BF16) { if (vec) FS_GO(uint16_t, true); else FS_GO(uint16_t, false); }
+  else                    { if (vec) FS_GO(f16, true); else FS_GO(f16, false); }
 #undef FS_GO
   if (ev.stop) (void)hipEventRecord(ev.stop, st);
   return hipGetLastError();

@@ -6,8 +6,8 @@
 //   c  = mix32(lo32(i*d+j) ^ mix32(hi32(i*d+j) ^ key1 ^ C1))
 //   u1 = ((mix32(c ^ 0x9E3779B9) >> 8) + 1) / 2^24,  u2 = (mix32(c ^ 0x85EBCA6B) >> 8) / 2^24
 //   S_ij = (float)( sqrt(-2 ln u1) cos(2 pi u2) / sqrt(k) )          (Box-Muller, in fp64)
-// and kept as fp32 (export), as bf16 rounded to nearest (bf16 applies) and as an
-// exact three-way bf16 split hi+mid+lo (fp32 applies).
+// and kept as fp32 (export), as bf16 and as half, each rounded to nearest (bf16 and half
+// applies), and as an exact three-way bf16 split hi+mid+lo (fp32 applies).
 //
 // The GEMM reuses the data path of the sparse kernel: A goes HBM -> registers ->
 // MFMA operand (4 columns x 8 rows per lane, transposed with v_perm_b32), S tiles of
@@ -28,8 +28,8 @@ using namespace mm;
 
 __global__ __launch_bounds__(256) void gauss_fill_kernel(float* __restrict__ S32, uint16_t* __restrict__ Sbf,
                                                          uint16_t* __restrict__ Shi, uint16_t* __restrict__ Smid,
-                                                         uint16_t* __restrict__ Slo, int64_t k, int64_t d,
-                                                         uint32_t key1) {
+                                                         uint16_t* __restrict__ Slo, uint16_t* __restrict__ Sh,
+                                                         int64_t k, int64_t d, uint32_t key1) {
   const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (idx >= k * d) return;
   const uint32_t c = mix32((uint32_t)idx ^ mix32((uint32_t)((uint64_t)idx >> 32) ^ key1 ^ kC1));
@@ -39,6 +39,7 @@ __global__ __launch_bounds__(256) void gauss_fill_kernel(float* __restrict__ S32
   const float s = (float)(z / sqrt((double)k));
   S32[idx] = s;
   Sbf[idx] = f32_to_bf16_rne(s);
+  Sh[idx] = f32_to_f16_bits(s);
   const uint32_t sb = __float_as_uint(s);
   const float r1 = s - __uint_as_float(sb & 0xFFFF0000u);
   const uint32_t r1b = __float_as_uint(r1);
@@ -49,7 +50,7 @@ __global__ __launch_bounds__(256) void gauss_fill_kernel(float* __restrict__ S32
 }
 
 struct GaussArgs {
-  const uint16_t* S[3];  // bf16: S[0] only; fp32: hi, mid, lo
+  const uint16_t* S[3];  // bf16 and half: S[0] only; fp32: hi, mid, lo
   const void* A;
   void* out;
   int64_t k, d, lda, ldo;
@@ -157,7 +158,7 @@ void gauss_kernel(GaussArgs a) {
 #pragma unroll
           for (int c = 0; c < 4; ++c)
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) acc[mt][c] = mfma(pa[0][mt], op[c], acc[mt][c]);
+            for (int mt = 0; mt < MT; ++mt) acc[mt][c] = mfma<T>(pa[0][mt], op[c], acc[mt][c]);
         } else {
 #pragma unroll
           for (int c = 0; c < 4; ++c) {
@@ -170,17 +171,17 @@ void gauss_kernel(GaussArgs a) {
             // product by product over the row tiles: with MT = 4 an accumulator is reused only
             // after three other MFMAs (back-to-back dependent MFMAs stall the matrix pipe)
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) acc[mt][c] = mfma(pa[0][mt], hi, acc[mt][c]);
+            for (int mt = 0; mt < MT; ++mt) acc[mt][c] = mfma<T>(pa[0][mt], hi, acc[mt][c]);
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) acc[mt][c] = mfma(pa[0][mt], mid, acc[mt][c]);
+            for (int mt = 0; mt < MT; ++mt) acc[mt][c] = mfma<T>(pa[0][mt], mid, acc[mt][c]);
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) acc[mt][c] = mfma(pa[1][mt], hi, acc[mt][c]);
+            for (int mt = 0; mt < MT; ++mt) acc[mt][c] = mfma<T>(pa[1][mt], hi, acc[mt][c]);
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) acc[mt][c] = mfma(pa[0][mt], lo, acc[mt][c]);
+            for (int mt = 0; mt < MT; ++mt) acc[mt][c] = mfma<T>(pa[0][mt], lo, acc[mt][c]);
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) acc[mt][c] = mfma(pa[2][mt], hi, acc[mt][c]);
+            for (int mt = 0; mt < MT; ++mt) acc[mt][c] = mfma<T>(pa[2][mt], hi, acc[mt][c]);
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) acc[mt][c] = mfma(pa[1][mt], mid, acc[mt][c]);
+            for (int mt = 0; mt < MT; ++mt) acc[mt][c] = mfma<T>(pa[1][mt], mid, acc[mt][c]);
           }
           if (fetch) issue(t * KSTEPS + ks + PFD, cur);
         }
@@ -209,9 +210,7 @@ void gauss_kernel(GaussArgs a) {
       T* dst = reinterpret_cast<T*>(a.out) + row * a.ldo + col0;
       if (a.out_vec && col0 + 3 < a.n) {
         if constexpr (sizeof(T) == 2) {
-          uint2 w;
-          w.x = (uint32_t)f32_to_bf16_rne(v[0]) | ((uint32_t)f32_to_bf16_rne(v[1]) << 16);
-          w.y = (uint32_t)f32_to_bf16_rne(v[2]) | ((uint32_t)f32_to_bf16_rne(v[3]) << 16);
+          const uint2 w = pack4<T>(v);
           *reinterpret_cast<uint2*>(dst) = w;
         } else {
           *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
@@ -238,7 +237,7 @@ hipError_t go(K kernel, dim3 grid, unsigned threads, size_t lds, hipStream_t st,
 
 }  // namespace
 
-size_t gauss_bytes(int64_t k, int64_t d) { return (size_t)k * (size_t)d * (4 + 4 * 2); }
+size_t gauss_bytes(int64_t k, int64_t d) { return (size_t)k * (size_t)d * (4 + 5 * 2); }
 
 hipError_t gauss_fill(void* storage, int64_t k, int64_t d, uint32_t key1, hipStream_t st) {
   float* S32 = (float*)storage;
@@ -246,7 +245,7 @@ hipError_t gauss_fill(void* storage, int64_t k, int64_t d, uint32_t key1, hipStr
   const int64_t blocks = (k * d + 255) / 256;
   if (blocks > 0x7fffffff) return hipErrorInvalidValue;
   hipLaunchKernelGGL(gauss_fill_kernel, dim3((unsigned)blocks), dim3(256), 0, st, S32, b, b + k * d,
-                     b + 2 * k * d, b + 3 * k * d, k, d, key1);
+                     b + 2 * k * d, b + 3 * k * d, b + 4 * k * d, k, d, key1);
   return hipGetLastError();
 }
 
@@ -274,6 +273,10 @@ hipError_t launch_gauss(const void* storage, int64_t k, int64_t d, const void* A
     a.S[0] = b; a.S[1] = a.S[2] = nullptr;
     constexpr int RW = 128;
     e = go(gauss_kernel<uint16_t, 2, 2, 2>, dim3((unsigned)(k / RW), col_tiles), 256, 2 * RW * PHI_LD * 2, st, a);
+  } else if (dt == FS_F16) {
+    a.S[0] = b + 4 * k * d; a.S[1] = a.S[2] = nullptr;
+    constexpr int RW = 128;
+    e = go(gauss_kernel<f16, 2, 2, 2>, dim3((unsigned)(k / RW), col_tiles), 256, 2 * RW * PHI_LD * 2, st, a);
   } else {
     a.S[0] = b + k * d; a.S[1] = b + 2 * k * d; a.S[2] = b + 3 * k * d;
     // 128-row x 512-column work-groups when they still fill most of the chip, else 64 x 256

@@ -83,8 +83,9 @@ hipError_t launch_generic(const SketchParams& p, const void* A, int64_t lda, int
 #define FS_GO(T, P2) \
   hipLaunchKernelGGL((generic_kernel<T, P2>), grid, block, lds, st, p, (const T*)A, lda, (int)n, (T*)out, ldo, rows_per_pass)
   if (ev.start) (void)hipEventRecord(ev.start, st);
-  if (dt == FS_F32) { if (p.br_pow2) FS_GO(float, true); else FS_GO(float, false); }
-  else              { if (p.br_pow2) FS_GO(uint16_t, true); else FS_GO(uint16_t, false); }
+  if (dt == FS_F32)       { if (p.br_pow2) FS_GO(float, true); else FS_GO(float, false); }
+  else if (dt == FS_BF16) { if (p.br_pow2) FS_GO(uint16_t, true); else FS_GO(uint16_t, false); }
+  else                    { if (p.br_pow2) FS_GO(f16, true); else FS_GO(f16, false); }
 #undef FS_GO
   if (ev.stop) (void)hipEventRecord(ev.stop, st);
   return hipGetLastError();

@@ -177,7 +177,7 @@ void mfma_kernel(MfmaArgs a) {
     // the 32-bit value are dropped by the 16-bit store)
     const uint32_t base = slot_row0 - row_lo;
     auto put = [&](uint32_t local, uint32_t i) {
-      phi[__umul24(local, (uint32_t)PHI_LD) + lane] = (uint16_t)(((rh.signs >> i) << 15) | kOne);
+      phi[__umul24(local, (uint32_t)PHI_LD) + lane] = (uint16_t)(((rh.signs >> i) << 15) | Fmt<T>::one);
     };
     if (whole) {
       // s >= 1; the first two updates are peeled (s = 2 and 4 are the common cases)
@@ -339,7 +339,7 @@ void mfma_kernel(MfmaArgs a) {
 #pragma unroll
           for (int c = 0; c < 4; ++c)
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) acc[mt][c] = mfma(pa[mt], op[c], acc[mt][c]);
+            for (int mt = 0; mt < MT; ++mt) acc[mt][c] = mfma<T>(pa[mt], op[c], acc[mt][c]);
         } else {
           // two columns at a time, piece by piece: an accumulator is reused only after
           // 2*MT other MFMAs (back-to-back dependent MFMAs stall the matrix pipe)
@@ -360,7 +360,7 @@ void mfma_kernel(MfmaArgs a) {
               for (int cc = 0; cc < 2; ++cc)
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt)
-                  acc[mt][c + cc] = mfma(pa[mt], pc[cc][piece], acc[mt][c + cc]);
+                  acc[mt][c + cc] = mfma<T>(pa[mt], pc[cc][piece], acc[mt][c + cc]);
           }
           if (fetch) issue(t * KSTEPS + ks + PFD, cur);
         }
@@ -390,7 +390,7 @@ void mfma_kernel(MfmaArgs a) {
         dst[mt] = *reinterpret_cast<const uint4*>(tile + (mt * 32 + (lane & 31)) * PHI_LD + ks * 16 + kg * 8);
     };
     auto put_one = [&](uint16_t* tile, uint32_t i, bool real) {
-      tile[real ? __umul24(pr, (uint32_t)PHI_LD) + lane : pad_at] = (uint16_t)(((prh.signs >> i) << 15) | kOne);
+      tile[real ? __umul24(pr, (uint32_t)PHI_LD) + lane : pad_at] = (uint16_t)(((prh.signs >> i) << 15) | Fmt<T>::one);
       pr = (pr + prh.stride) & (p.Br - 1);
     };
     auto fill_part = [&](int t1, uint16_t* tile, int ks) {
@@ -436,7 +436,7 @@ void mfma_kernel(MfmaArgs a) {
 #pragma unroll
           for (int c = 0; c < 4; ++c)
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) acc[mt][c] = mfma(pa[mt], op[c], acc[mt][c]);
+            for (int mt = 0; mt < MT; ++mt) acc[mt][c] = mfma<T>(pa[mt], op[c], acc[mt][c]);
           if constexpr (MT == 4) {  // one wave per SIMD: spread the rest between the MFMAs
             __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
 #pragma unroll
@@ -466,7 +466,7 @@ void mfma_kernel(MfmaArgs a) {
               for (int cc = 0; cc < 2; ++cc)
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt)
-                  acc[mt][c + cc] = mfma(pa[mt], pc[cc][piece], acc[mt][c + cc]);
+                  acc[mt][c + cc] = mfma<T>(pa[mt], pc[cc][piece], acc[mt][c + cc]);
           }
           if (fetch) issue(t * KSTEPS + ks + PFD, cur);
         }
@@ -611,9 +611,7 @@ void mfma_kernel(MfmaArgs a) {
           for (int c = 0; c < 4; ++c) v[c] *= p.scale;
           if (a.out_vec && colq + 3 < a.n) {
             if constexpr (sizeof(T) == 2) {
-              uint2 w;
-              w.x = (uint32_t)f32_to_bf16_rne(v[0]) | ((uint32_t)f32_to_bf16_rne(v[1]) << 16);
-              w.y = (uint32_t)f32_to_bf16_rne(v[2]) | ((uint32_t)f32_to_bf16_rne(v[3]) << 16);
+              const uint2 w = pack4<T>(v);
               *reinterpret_cast<uint2*>(dst) = w;
             } else {
               *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
@@ -658,9 +656,7 @@ __global__ __launch_bounds__(256) void reduce_planes_kernel(const float* __restr
   T* dst = out + row * ldo + col0;
   if (out_vec && col0 + 3 < n) {
     if constexpr (sizeof(T) == 2) {
-      uint2 w;
-      w.x = (uint32_t)f32_to_bf16_rne(v[0]) | ((uint32_t)f32_to_bf16_rne(v[1]) << 16);
-      w.y = (uint32_t)f32_to_bf16_rne(v[2]) | ((uint32_t)f32_to_bf16_rne(v[3]) << 16);
+      const uint2 w = pack4<T>(v);
       *reinterpret_cast<uint2*>(dst) = w;
     } else {
       *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
@@ -770,7 +766,7 @@ Plan make_plan(const SketchParams& p, const void* A, int64_t lda, int64_t n, fs_
   // bf16 with one wave per SIMD (128-row tiles) has the registers for a ring twice as deep, and
   // with a single wave nothing else hides the latency of A; the two-stage ring needs an even
   // stage count.  (For fp32 the deeper ring measured no gain.)
-  if (pl.mt == 4 && dt == FS_BF16 && pl.stages % 2 == 0) pl.pfx = 2;
+  if (pl.mt == 4 && dt != FS_F32 && pl.stages % 2 == 0) pl.pfx = 2;
   pl.lds = lds_bytes(pl.mt, pl.nrg, pl.ncg, pl.run,
                      pl.run > 1 ? (size_t)(p.kappa + pl.run - 1) * p.Br * 256 * 4 : 0);
   pl.ok = pl.lds <= kLdsBudget;
@@ -857,6 +853,8 @@ hipError_t launch_mfma(const SketchParams& p, const void* A, int64_t lda, int64_
   hipError_t e;
   if (dt == FS_BF16)
     e = pl.in_stat ? launch_shape<uint16_t, true>(pl, a, grid, st) : launch_shape<uint16_t, false>(pl, a, grid, st);
+  else if (dt == FS_F16)
+    e = pl.in_stat ? launch_shape<f16, true>(pl, a, grid, st) : launch_shape<f16, false>(pl, a, grid, st);
   else
     e = pl.in_stat ? launch_shape<float, true>(pl, a, grid, st) : launch_shape<float, false>(pl, a, grid, st);
   if (ev.stop) (void)hipEventRecord(ev.stop, st);
@@ -868,6 +866,10 @@ hipError_t launch_mfma(const SketchParams& p, const void* A, int64_t lda, int64_
   if (dt == FS_BF16)
     hipLaunchKernelGGL(reduce_planes_kernel<uint16_t>, dim3(blocks), dim3(256), 0, st, a.ws, pl.planes,
                        p.k, pl.ldw, (int)n, (uint16_t*)out, ldo, p.scale, a.out_vec, pl.run, blk2pos,
+                       p.Br, p.kappa);
+  else if (dt == FS_F16)
+    hipLaunchKernelGGL(reduce_planes_kernel<f16>, dim3(blocks), dim3(256), 0, st, a.ws, pl.planes,
+                       p.k, pl.ldw, (int)n, (f16*)out, ldo, p.scale, a.out_vec, pl.run, blk2pos,
                        p.Br, p.kappa);
   else
     hipLaunchKernelGGL(reduce_planes_kernel<float>, dim3(blocks), dim3(256), 0, st, a.ws, pl.planes,

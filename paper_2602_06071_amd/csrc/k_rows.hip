@@ -186,7 +186,7 @@ void rows_kernel(RowsArgs a) {
       const RowHash rh = row_hash_pow2(s_bk[sl_n], st_n * KC + lane, p.Br);
       uint32_t r = rh.shift;
       for (uint32_t i = 0; i < p.s; ++i) {
-        s_phi[__umul24(r, (uint32_t)PHI_LD) + lane] = (uint16_t)(((rh.signs >> i) << 15) | kOne);
+        s_phi[__umul24(r, (uint32_t)PHI_LD) + lane] = (uint16_t)(((rh.signs >> i) << 15) | Fmt<T>::one);
         r = (r + rh.stride) & (p.Br - 1);
       }
       return;
@@ -197,7 +197,7 @@ void rows_kernel(RowsArgs a) {
       uint32_t r = rh.shift;
       const uint32_t base = slot << lbr;
       for (uint32_t i = 0; i < p.s; ++i) {
-        s_phi[__umul24(base + r, (uint32_t)PHI_LD) + lane] = (uint16_t)(((rh.signs >> i) << 15) | kOne);
+        s_phi[__umul24(base + r, (uint32_t)PHI_LD) + lane] = (uint16_t)(((rh.signs >> i) << 15) | Fmt<T>::one);
         r = (r + rh.stride) & (p.Br - 1);
       }
     }
@@ -243,7 +243,7 @@ void rows_kernel(RowsArgs a) {
 #pragma unroll
         for (int j = 0; j < KSTEPS; ++j)
 #pragma unroll
-          for (int rt = 0; rt < MT; ++rt) acc[c][rt] = mfma(g[j], pb[j][rt], acc[c][rt]);
+          for (int rt = 0; rt < MT; ++rt) acc[c][rt] = mfma<T>(g[j], pb[j][rt], acc[c][rt]);
       } else {
 #pragma unroll
         for (int jj = 0; jj < KSTEPS; jj += 2) {
@@ -260,7 +260,7 @@ void rows_kernel(RowsArgs a) {
             for (int cc = 0; cc < 2; ++cc)
 #pragma unroll
               for (int rt = 0; rt < MT; ++rt)
-                acc[c][rt] = mfma(pc[cc][piece], pb[jj + cc][rt], acc[c][rt]);
+                acc[c][rt] = mfma<T>(pc[cc][piece], pb[jj + cc][rt], acc[c][rt]);
         }
       }
       __builtin_amdgcn_sched_barrier(0);
@@ -361,9 +361,7 @@ __global__ __launch_bounds__(256) void reduce_rows_kernel(const float* __restric
   if constexpr (VEC == 4) {
     if ((uintptr_t)dst % (4 * sizeof(T)) == 0) {  // one 8- or 16-byte store
       if constexpr (sizeof(T) == 2) {
-        uint2 w;
-        w.x = (uint32_t)f32_to_bf16_rne(s[0]) | ((uint32_t)f32_to_bf16_rne(s[1]) << 16);
-        w.y = (uint32_t)f32_to_bf16_rne(s[2]) | ((uint32_t)f32_to_bf16_rne(s[3]) << 16);
+        const uint2 w = pack4<T>(s);
         *reinterpret_cast<uint2*>(dst) = w;
       } else {
         *reinterpret_cast<float4*>(dst) = make_float4(s[0], s[1], s[2], s[3]);
@@ -422,7 +420,7 @@ RowsPlan make_rows_plan(const SketchParams& p, const void* G, int64_t ldg, int64
   // measured: the LDS-staged loads win for bf16 (4.9 against 4.8 TB/s with a padded row stride,
   // 4.4 against 2.6 at a power-of-two stride) and for 32 stacked rows; fp32 with 64 or 128
   // stacked rows is short of registers and LDS and is faster with the direct loads
-  pl.staged = dt == FS_BF16 || pl.mt == 1;
+  pl.staged = dt != FS_F32 || pl.mt == 1;
   pl.lds = 2 * MAX_KAPPA * 4 + (size_t)(32 * pl.mt) * PHI_LD * 2 + (pl.staged ? 32 * (KC * esz + 16) : 0);
   pl.ok = true;
   return pl;
@@ -468,6 +466,8 @@ hipError_t launch_rows(const SketchParams& p, const void* G, int64_t ldg, int64_
                             : go(rows_kernel<T, MT, ET, false, false>, grid, pl.lds, st, a)))
   if (dt == FS_BF16)
     e = pl.mt == 1 ? FS_ROWS(uint16_t, 1, 4) : pl.mt == 2 ? FS_ROWS(uint16_t, 2, 4) : FS_ROWS(uint16_t, 4, 2);
+  else if (dt == FS_F16)
+    e = pl.mt == 1 ? FS_ROWS(f16, 1, 4) : pl.mt == 2 ? FS_ROWS(f16, 2, 4) : FS_ROWS(f16, 4, 2);
   else
     e = pl.mt == 1 ? FS_ROWS(float, 1, 4) : pl.mt == 2 ? FS_ROWS(float, 2, 4) : FS_ROWS(float, 4, 2);
 #undef FS_ROWS
@@ -479,8 +479,9 @@ hipError_t launch_rows(const SketchParams& p, const void* G, int64_t ldg, int64_
 #define FS_RED(T, VEC)                                                                                   \
   hipLaunchKernelGGL((reduce_rows_kernel<T, VEC>), rgrid, dim3(256), 0, st, a.ws, pl.zsplit, (int)n, p, \
                      a.log2_br, orbit, (T*)out, ldo)
-  if (dt == FS_BF16) { if (vec == 4) FS_RED(uint16_t, 4); else FS_RED(uint16_t, 1); }
-  else               { if (vec == 4) FS_RED(float, 4); else FS_RED(float, 1); }
+  if (dt == FS_BF16)     { if (vec == 4) FS_RED(uint16_t, 4); else FS_RED(uint16_t, 1); }
+  else if (dt == FS_F16) { if (vec == 4) FS_RED(f16, 4); else FS_RED(f16, 1); }
+  else                   { if (vec == 4) FS_RED(float, 4); else FS_RED(float, 1); }
 #undef FS_RED
   return hipGetLastError();
 }

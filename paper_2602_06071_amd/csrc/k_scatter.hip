@@ -39,17 +39,17 @@ __global__ __launch_bounds__(256) void scatter_kernel(SketchParams p, const T* _
   }
 }
 
-__global__ __launch_bounds__(256) void scatter_finalize_bf16(const float* __restrict__ acc, int64_t rows,
-                                                             int n, uint16_t* __restrict__ out,
-                                                             int64_t ldo) {
+template <typename T>
+__global__ __launch_bounds__(256) void scatter_finalize(const float* __restrict__ acc, int64_t rows, int n,
+                                                        T* __restrict__ out, int64_t ldo) {
   const int col = blockIdx.x * 256 + threadIdx.x;
   if (col >= n) return;
   for (int64_t r = blockIdx.y; r < rows; r += gridDim.y)
-    out[r * ldo + col] = f32_to_bf16_rne(acc[r * (int64_t)n + col]);
+    Elt<T>::store(out + r * ldo + col, acc[r * (int64_t)n + col]);
 }
 
 size_t scatter_workspace_bytes(const SketchParams& p, int64_t n, fs_dtype dt) {
-  return dt == FS_BF16 ? (size_t)p.k * (size_t)n * sizeof(float) : 0;
+  return dt != FS_F32 ? (size_t)p.k * (size_t)n * sizeof(float) : 0;
 }
 
 hipError_t launch_scatter(const SketchParams& p, const void* A, int64_t lda, int64_t n, void* out,
@@ -65,13 +65,16 @@ hipError_t launch_scatter(const SketchParams& p, const void* A, int64_t lda, int
 #define FS_GO(T, P2) \
   hipLaunchKernelGGL((scatter_kernel<T, P2>), grid, block, 0, st, p, (const T*)A, lda, (int)n, acc, ldacc)
   if (ev.start) (void)hipEventRecord(ev.start, st);
-  if (dt == FS_F32) { if (p.br_pow2) FS_GO(float, true); else FS_GO(float, false); }
-  else              { if (p.br_pow2) FS_GO(uint16_t, true); else FS_GO(uint16_t, false); }
+  if (dt == FS_F32)       { if (p.br_pow2) FS_GO(float, true); else FS_GO(float, false); }
+  else if (dt == FS_BF16) { if (p.br_pow2) FS_GO(uint16_t, true); else FS_GO(uint16_t, false); }
+  else                    { if (p.br_pow2) FS_GO(f16, true); else FS_GO(f16, false); }
 #undef FS_GO
   if (ev.stop) (void)hipEventRecord(ev.stop, st);
   if (dt == FS_BF16)
-    hipLaunchKernelGGL(scatter_finalize_bf16, dim3(jt, zrows), dim3(256), 0, st, acc, p.k, (int)n,
+    hipLaunchKernelGGL(scatter_finalize<uint16_t>, dim3(jt, zrows), dim3(256), 0, st, acc, p.k, (int)n,
                        (uint16_t*)out, ldo);
+  else if (dt == FS_F16)
+    hipLaunchKernelGGL(scatter_finalize<f16>, dim3(jt, zrows), dim3(256), 0, st, acc, p.k, (int)n, (f16*)out, ldo);
   return hipGetLastError();
 }
 

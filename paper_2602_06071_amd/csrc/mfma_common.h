@@ -15,15 +15,16 @@ constexpr int KSTEPS = KC / 16;  // MFMA k-steps per stage
 constexpr int PHI_LD = KC + 8;   // bf16 per LDS row of Phi (144 B: conflict-free b128 reads)
 constexpr int WCOLS = 128;       // columns per wave (4 per lane x 32 lanes)
 constexpr int MAX_KAPPA = 128;
-constexpr uint16_t kOne = 0x3F80, kMinusOne = 0xBF80;
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 // What one lane loads from one row: CPL consecutive columns as one vector V; PFD = depth
 // (in k-steps) of the register prefetch ring, sized to 64 VGPRs per wave.
 template <typename T, int CPL> struct LdN;
 template <> struct LdN<uint16_t, 4> { using V = uint2; static constexpr int PFD = 4; };
+template <> struct LdN<f16, 4>      { using V = uint2; static constexpr int PFD = 4; };
 template <> struct LdN<float, 4>    { using V = uint4; static constexpr int PFD = 2; };
 template <typename T> using Ld = LdN<T, 4>;
 
@@ -79,9 +80,27 @@ __device__ __forceinline__ void split_ops(const uint32_t (&x)[8], uint4& hi, uin
   }
 }
 
+// The 16-bit format of the MFMA operands for element type T: half for half inputs, bf16 for
+// bf16 inputs and for the bf16 pieces that fp32 inputs are split into.  `one` is +1 in that
+// format (the sign is bit 15 in both); op() is D = A*B + C on 32 x 32 x 16 tiles, fp32 accumulate.
+template <typename T> struct Fmt {
+  static constexpr uint16_t one = 0x3F80;
+  static __device__ __forceinline__ f32x16 op(uint4 a, uint4 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
+                                                   __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+  }
+};
+template <> struct Fmt<f16> {
+  static constexpr uint16_t one = 0x3C00;
+  static __device__ __forceinline__ f32x16 op(uint4 a, uint4 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a),
+                                                  __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+  }
+};
+
+template <typename T>
 __device__ __forceinline__ f32x16 mfma(uint4 a, uint4 b, f32x16 c) {
-  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
-                                                 __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+  return Fmt<T>::op(a, b, c);
 }
 
 }  // namespace mm

@@ -2,7 +2,9 @@
 the float64 oracle on the same seeded inputs.
 
 Bars: indices and signs bit-exact; relative Frobenius error <= 1e-5 for fp32
-inputs and <= 4e-3 for bf16 inputs/outputs with fp32 accumulation.
+inputs, <= 4e-3 for bf16 and <= 5e-4 for half inputs/outputs with fp32
+accumulation (the one rounding of the result to 8 resp. 11 significant bits
+bounds it by 2^-8 resp. 2^-11 = 4.9e-4; the fp32 sum adds about 1e-6).
 """
 import functools
 import gc
@@ -17,7 +19,9 @@ from paper_2602_06071_amd import workloads as W
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda"
-TOL = {torch.float32: 1e-5, torch.bfloat16: 4e-3}
+TOL = {torch.float32: 1e-5, torch.bfloat16: 4e-3, torch.float16: 5e-4}
+ETOL = {torch.float32: 2e-5, torch.bfloat16: 8e-3, torch.float16: 1e-3}   # element-wise, see the uses
+DTYPES = pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16], ids=["f32", "bf16", "f16"])
 VARIANTS = [B.VARIANT_GENERIC, B.VARIANT_MFMA]
 VNAME = {B.VARIANT_GENERIC: "generic", B.VARIANT_MFMA: "mfma", B.VARIANT_AUTO: "auto"}
 
@@ -117,7 +121,7 @@ SMALL = [
 
 
 @pytest.mark.parametrize("variant", VARIANTS, ids=lambda v: VNAME[v])
-@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@DTYPES
 @pytest.mark.parametrize("case", SMALL, ids=lambda c: f"{c[0]}-n{c[1]}")
 def test_apply_matches_oracle(case, dtype, variant):
     params, n, pa, po = case
@@ -138,14 +142,14 @@ def test_apply_matches_oracle(case, dtype, variant):
     if po:
         assert torch.isnan(obuf[:, n:].float()).all(), "wrote outside the n output columns"
     # element-wise, scaled by the typical magnitude of an output entry
-    tol = (2e-5 if dtype == torch.float32 else 8e-3)
+    tol = ETOL[dtype]
     diff = np.abs(host64(obuf[:, :n]) - ref)
     assert (diff <= tol * (np.abs(ref) + np.sqrt((ref ** 2).mean()))).all()
 
 
 # ---------------------------------------------------------- one-hot -------
 @pytest.mark.parametrize("variant", VARIANTS, ids=lambda v: VNAME[v])
-@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@DTYPES
 @pytest.mark.parametrize("params", [(4096, 256, 512, 32, 4, 4), (32768, 64, 4096, 8, 8, 2),
                                     (8192, 512, 1024, 64, 4, 4), (4096, 256, 512, 32, 2, 2),
                                     (65536, 8192, 64, 8, 8, 2)])
@@ -166,9 +170,44 @@ def test_one_hot_probes_reproduce_columns_exactly(params, dtype, variant):
     assert np.array_equal(host64(out), want)
 
 
+# ------------------------------------------ half: the ends of its range ---
+@pytest.mark.parametrize("variant", VARIANTS, ids=lambda v: VNAME[v])
+@pytest.mark.parametrize("params", [(4096, 256, 512, 32, 2, 4), (8192, 1024, 512, 64, 4, 8)])
+def test_half_subnormal_inputs_count_and_overflow_becomes_infinity(params, variant):
+    """Half inputs below 2^-14 are subnormal and must enter the sums with their value; results
+    beyond the largest half (65504) round to infinity, as IEEE round-to-nearest does."""
+    print("half range", params, VNAME[variant], flush=True)
+    d, n = params[0], 96
+    g = torch.Generator(device=DEV).manual_seed(12)
+    A = torch.randn((d, n), generator=g, device=DEV)
+    A[:, :32] *= 2.0 ** -17          # every entry subnormal or nearly so in half
+    A[:, 32:64] *= 3.0e4             # sums pass 65504 in many places
+    A = A.clamp(-65504, 65504).to(torch.float16)
+    assert (A[:, :32].abs().float() < 2.0 ** -14).float().mean() > 0.9
+    sk = make_sketch(params, 4, variant)
+    out = host64(apply_or_skip(sk, A))
+    ref = O.apply(oracle_csc(params, 4), host64(A))
+    # one rounding to half: 2^-11 relative, or half a unit of the subnormal spacing 2^-24; the
+    # fp32 sum and the fp32 scale factor add a few 2^-24 relative
+    small, big = slice(0, 32), slice(32, 64)
+    assert np.abs(ref[:, small]).max() < 2.0 ** -10 and (ref[:, small] != 0).mean() > 0.9
+    assert (np.abs(out[:, small] - ref[:, small]) <= 2.0 ** -11 * 1.01 * np.abs(ref[:, small]) + 2.0 ** -25 * 1.01).all()
+    over = np.abs(ref[:, big]) > 65520 * (1 + 1e-5)
+    under = np.abs(ref[:, big]) < 65520 * (1 - 1e-5)
+    assert over.any() and under.any()
+    assert (out[:, big][over] == np.sign(ref[:, big][over]) * np.inf).all()
+    assert np.isfinite(out[:, big][under]).all()
+    assert (np.abs(out[:, big][under] - ref[:, big][under]) <= 2.0 ** -11 * 1.01 * np.abs(ref[:, big][under])).all()
+    check(torch.from_numpy(out[:, 64:]), ref[:, 64:], torch.float16, "half, ordinary columns")
+    if variant == B.VARIANT_MFMA:    # the same vectors as rows
+        rows = host64(sk.apply_rows(A.t().contiguous())).T
+        assert (np.abs(rows[:, small] - ref[:, small]) <= 2.0 ** -11 * 1.01 * np.abs(ref[:, small]) + 2.0 ** -25 * 1.01).all()
+        assert (rows[:, big][over] == np.sign(ref[:, big][over]) * np.inf).all()
+
+
 # ------------------------------------ chunking, determinism, linearity ----
 @pytest.mark.parametrize("variant", VARIANTS, ids=lambda v: VNAME[v])
-@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@DTYPES
 def test_chunked_equals_monolithic_bitwise(dtype, variant):
     params, n, chunk = (32768, 64, 4096, 8, 8, 2), 1024, 256
     print("chunked", dtype, VNAME[variant], flush=True)
@@ -180,8 +219,8 @@ def test_chunked_equals_monolithic_bitwise(dtype, variant):
     for c in range(0, n, chunk):
         sk.apply(A[:, c:c + chunk], parts[:, c:c + chunk])
     torch.cuda.synchronize()
-    assert torch.equal(whole.view(torch.int16 if dtype == torch.bfloat16 else torch.int32),
-                       again.view(torch.int16 if dtype == torch.bfloat16 else torch.int32))
+    bits = torch.int32 if dtype == torch.float32 else torch.int16
+    assert torch.equal(whole.view(bits), again.view(bits))
     assert torch.equal(whole, parts)
 
 
@@ -231,7 +270,7 @@ def test_empty_input_launches_nothing():
 
 
 # ------------------------------------------------ baselines ---------------
-@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@DTYPES
 @pytest.mark.parametrize("d,k,s,n", [(4096, 256, 4, 300), (16384, 1024, 8, 520), (1000, 48, 3, 17)])
 def test_plain_sjlt_scatter_matches_oracle(d, k, s, n, dtype):
     print("scatter", d, k, s, n, dtype, flush=True)
@@ -248,7 +287,7 @@ def test_plain_sjlt_scatter_matches_oracle(d, k, s, n, dtype):
     assert np.array_equal(signs.cpu().numpy(), want_s)
 
 
-@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@DTYPES
 @pytest.mark.parametrize("k,d,n,pad", [(128, 1024, 256, 0), (256, 4096, 300, 4), (1024, 2048, 1000, 0),
                                        (1024, 256, 12328, 0)])  # enough tiles for the 128 x 512 fp32 work-groups
 def test_dense_gaussian_matches_oracle(k, d, n, pad, dtype):
@@ -265,7 +304,9 @@ def test_dense_gaussian_matches_oracle(k, d, n, pad, dtype):
     Sd = S_dev.cpu().double().numpy()
     assert np.abs(Sd - S).max() <= 2.0 ** -22 * np.abs(S).max()
     assert (Sd != S).mean() < 1e-3
-    check(out, G.apply(S, host64(A)), dtype, "dense gaussian")
+    # (16-bit applies multiply by S rounded to the element type: one more rounding of that size)
+    err = O.rel_fro_err(host64(out), G.apply(S, host64(A)))
+    assert err <= {torch.float32: 1e-5, torch.bfloat16: 4e-3, torch.float16: 1e-3}[dtype], f"dense gaussian: {err:.3e}"
 
 
 # ------------------------------------------------ full-size configs -------
@@ -467,7 +508,7 @@ ROWS = [
 ]
 
 
-@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@DTYPES
 @pytest.mark.parametrize("case", ROWS, ids=lambda c: f"{c[0]}-n{c[1]}")
 def test_apply_rows_matches_oracle(case, dtype):
     params, n, pg, po = case
@@ -486,7 +527,7 @@ def test_apply_rows_matches_oracle(case, dtype):
     check(obuf[:, :k], ref, dtype, "apply_rows")
     if po:
         assert torch.isnan(obuf[:, k:].float()).all(), "wrote outside the k output columns"
-    tol = (2e-5 if dtype == torch.float32 else 8e-3)
+    tol = ETOL[dtype]
     diff = np.abs(host64(obuf[:, :k]) - ref)
     assert (diff <= tol * (np.abs(ref) + np.sqrt((ref ** 2).mean()))).all()
     again = sk.apply_rows(G)                      # no atomics on data: bit-identical run to run
@@ -559,7 +600,7 @@ def test_handle_collected_during_a_capture_does_not_break_it():
     assert len(B._deferred) == 0
 
 
-@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@DTYPES
 def test_variants_agree_with_each_other(dtype):
     """Generic and MFMA paths implement the same S: they agree to accumulation rounding."""
     params, n = (16384, 256, 2048, 32, 4, 4), 384
@@ -569,7 +610,7 @@ def test_variants_agree_with_each_other(dtype):
         sk = make_sketch(params, 9, v)
         outs.append(host64(apply_or_skip(sk, A)))
     torch.cuda.synchronize()
-    tol = 1e-5 if dtype == torch.float32 else 8e-3
+    tol = 1e-5 if dtype == torch.float32 else ETOL[dtype]
     assert O.rel_fro_err(outs[1], outs[0]) < tol
     assert np.array_equal(outs[1], outs[2])  # AUTO picked the MFMA path
 
@@ -592,7 +633,7 @@ def _random_cases(count, seed):
 
 
 @pytest.mark.parametrize("variant", [B.VARIANT_AUTO, B.VARIANT_GENERIC], ids=lambda v: VNAME[v])
-@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@DTYPES
 def test_random_shapes_match_oracle(dtype, variant):
     """40 seeded random parameter sets (power-of-two and odd Br, composite M, ragged n): whichever
     kernel the dispatcher (or the forced generic variant) runs must match the oracle, and the
@@ -619,7 +660,7 @@ def test_random_shapes_match_oracle(dtype, variant):
 
 
 # ------------------------------------------------ FlashBlockRow kind ------
-@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+@DTYPES
 @pytest.mark.parametrize("case", [
     ((4096, 256, 512, 32, 2, 4), 512, 0), ((4000, 256, 512, 32, 2, 4), 301, 3),
     ((1152, 72, 96, 6, 5, 3), 65, 0), ((65536, 8192, 64, 8, 8, 2), 260, 0),
