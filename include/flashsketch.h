@@ -147,16 +147,20 @@ fs_status fs_sketch_apply_ld(fs_sketch_t h, const void* A, int64_t lda, int64_t 
  * every row one vector to sketch, as a pipeline that compresses per-example gradients holds
  * them: Section 7, "End-to-end ML: GraSS for Data Attribution", and Appendix F) and
  * out (n x k, ld = ldo >= k) = G S^T, i.e. out[i, :] = S G[i, :] -- the transpose of what
- * fs_sketch_apply_ld computes on G^T.  FS_KIND_BLOCKPERM only.  This entry point has only
- * the matrix-core kernel: it needs a power-of-two Br with kappa*Br in {32, 64, 128}
- * (input-stationary: G is read once) or else Br in {32, 64, 128} (output-stationary: G is
- * read kappa times), Bc a multiple of 64 that divides d, a 16-byte aligned G with
- * ldg*sizeof(elt) a multiple of 16 and 128*ldg*sizeof(elt) < 2^31; otherwise
- * FS_ERR_UNSUPPORTED (nothing is launched).  A row stride that is a large power of two maps
- * the rows of a tile to one HBM channel: prefer ldg = d + 64 elements.
+ * fs_sketch_apply_ld computes on G^T.  FS_KIND_BLOCKPERM only.  Two kernels, chosen as for
+ * fs_sketch_apply (fs_sketch_set_variant applies here too):
+ *  - matrix cores: needs a power-of-two Br with kappa*Br in {32, 64, 128} (input-stationary:
+ *    G is read once) or else Br in {32, 64, 128} (output-stationary: G is read kappa times),
+ *    Bc a multiple of 64 that divides d, a 16-byte aligned G with ldg*sizeof(elt) a multiple
+ *    of 16 and 128*ldg*sizeof(elt) < 2^31.  A row stride that is a large power of two maps
+ *    the rows of a tile to one HBM channel: prefer ldg = d + 64 elements.
+ *  - general: every other valid sketch and alignment (any Br, partly filled last block);
+ *    tiles are turned through LDS and accumulated without atomics, G is read kappa times.
+ * Forcing FS_VARIANT_MFMA on a call the matrix-core kernel cannot take returns
+ * FS_ERR_UNSUPPORTED (nothing is launched).
  * n == 0 is FS_OK.  Errors: NULL handle/G/out, n < 0, ldg < d, ldo < k, unknown dtype.
- * Workspace (input-stationary shapes only): kappa (times a row split) sets of n x k floats,
- * grown or attached as for fs_sketch_apply; fs_sketch_rows_workspace_bytes gives its size for
+ * Workspace (matrix cores, input-stationary shapes only): kappa (times a row split) sets of
+ * n x k floats, grown or attached as for fs_sketch_apply; fs_sketch_rows_workspace_bytes gives its size for
  * a well-aligned call.  The first call of a handle also uploads the 8*M-byte orbit table. */
 fs_status fs_sketch_apply_rows(fs_sketch_t h, const void* G, int64_t ldg, int64_t n, void* out,
                                int64_t ldo, fs_dtype dtype, void* stream);

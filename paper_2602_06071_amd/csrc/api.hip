@@ -349,15 +349,24 @@ fs_status fs_sketch_apply_rows(fs_sketch_t h, const void* G, int64_t ldg, int64_
   const size_t esz = dt == FS_F32 ? 4 : 2;
   if ((uintptr_t)G % esz || (uintptr_t)out % esz) return FS_ERR_INVALID_ARG;
   if (h->kind != FS_KIND_BLOCKPERM) return FS_ERR_UNSUPPORTED;
-  if (!fs::rows_supported(h->p, G, ldg, n, dt)) return FS_ERR_UNSUPPORTED;
+  const bool can = fs::rows_supported(h->p, G, ldg, n, dt);
+  if (h->variant == FS_VARIANT_MFMA && !can) return FS_ERR_UNSUPPORTED;
+  const bool use_mfma = can && h->variant != FS_VARIANT_GENERIC;
   hipStream_t st = (hipStream_t)stream;
-  fs_status rc = ensure_workspace(h, fs::rows_workspace_bytes(h->p, G, ldg, n, dt));
+  fs_status rc = use_mfma ? ensure_workspace(h, fs::rows_workspace_bytes(h->p, G, ldg, n, dt)) : FS_OK;
   if (rc != FS_OK) return rc;
   fs::EventPair ev;
   if (h->profiling && h->prof_used < (int)h->prof_start.size()) {
     ev.start = h->prof_start[h->prof_used];
     ev.stop = h->prof_stop[h->prof_used];
     ++h->prof_used;
+  }
+  if (!use_mfma) {
+    const hipError_t e = fs::launch_generic_rows(h->p, G, ldg, n, out, ldo, dt, st, ev);
+    h->last_variant = FS_VARIANT_GENERIC;
+    h->last_mode = 0;
+    if (e != hipSuccess) return hip_fail(h, e);
+    return FS_OK;
   }
   rc = ensure_orbit(h);  // the gather-reduction walks the wiring through this table
   if (rc != FS_OK) return rc;

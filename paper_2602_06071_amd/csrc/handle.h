@@ -55,6 +55,8 @@ hipError_t launch_export(const SketchParams& p, int32_t* rows, int8_t* signs, hi
 // One lane per column, LDS-private output tile.
 hipError_t launch_generic(const SketchParams& p, const void* A, int64_t lda, int64_t n, void* out,
                           int64_t ldo, fs_dtype dt, hipStream_t st, EventPair ev);
+hipError_t launch_generic_rows(const SketchParams& p, const void* G, int64_t ldg, int64_t n, void* out,
+                               int64_t ldo, fs_dtype dt, hipStream_t st, EventPair ev);
 
 // Matrix-core path.  ws holds the per-slot partial tiles.
 bool mfma_supported(const SketchParams& p, const void* A, int64_t lda, int64_t n, const void* out,

@@ -67,6 +67,86 @@ __global__ __launch_bounds__(256) void generic_kernel(SketchParams p, const T* _
   }
 }
 
+// The same for vectors held as rows: out (n x k) = G S^T, G (n x d) row-major.  Thread e of a
+// work-group owns example ex0 + e; a chunk of kChunk consecutive entries of TE examples is
+// loaded with consecutive threads on consecutive addresses of one example, turned through LDS
+// ([entry][example], odd stride), and then walked exactly as the column kernel walks rows:
+// wave-uniform hash, lane-private accumulators, no atomics.  The output tile goes back through
+// LDS so that consecutive threads store consecutive elements of one output row.
+constexpr int kChunk = 32;
+
+template <typename T, bool POW2>
+__global__ __launch_bounds__(128) void generic_rows_kernel(SketchParams p, const T* __restrict__ G,
+                                                           int64_t ldg, int n, T* __restrict__ out,
+                                                           int64_t ldo, int rows_per_pass) {
+  extern __shared__ float smem_rows[];
+  const int te = blockDim.x, tid = threadIdx.x, ld = te + 1;
+  float* sG = smem_rows;                 // [kChunk][ld]
+  float* sY = smem_rows + kChunk * ld;   // [R][ld]
+  const uint32_t g = blockIdx.x;
+  const uint32_t r0 = blockIdx.z * (uint32_t)rows_per_pass;
+  const uint32_t R = min((uint32_t)rows_per_pass, p.Br - r0);
+  const int64_t ex0 = (int64_t)blockIdx.y * te;
+
+  for (uint32_t r = 0; r < R; ++r) sY[r * ld + tid] = 0.f;
+
+  uint32_t h = g;
+  for (uint32_t l = 0; l < p.kappa; ++l) {
+    h = wire_next(h, p.a, p.b, p.M);
+    const uint32_t bk = block_key(p.key1, g, h, p.M);
+    for (uint32_t u0 = 0; u0 < p.Bc; u0 += kChunk) {
+      __syncthreads();  // the previous chunk has been consumed
+      for (int idx = tid; idx < te * kChunk; idx += te) {
+        const int e = idx / kChunk, q = idx % kChunk;
+        const int64_t col = (int64_t)h * p.Bc + u0 + q;  // entry of the vector; padding reads as 0
+        const bool ok = ex0 + e < n && u0 + q < p.Bc && col < p.d;
+        sG[q * ld + e] = ok ? Elt<T>::load(G + (ex0 + e) * ldg + col) : 0.f;
+      }
+      __syncthreads();
+      for (int q = 0; q < kChunk; ++q) {
+        if (u0 + q >= p.Bc) break;
+        const float v = sG[q * ld + tid];
+        const RowHash rh = POW2 ? row_hash_pow2(bk, u0 + q, p.Br) : row_hash_any(bk, u0 + q, p.Br);
+        uint32_t r = rh.shift;
+        for (uint32_t i = 0; i < p.s; ++i) {
+          const uint32_t rel = r - r0;
+          if (rel < R) sY[rel * ld + tid] += ((rh.signs >> i) & 1u) ? -v : v;
+          r += rh.stride;
+          if (r >= p.Br) r -= p.Br;
+        }
+      }
+    }
+  }
+  __syncthreads();
+  for (uint32_t idx = tid; idx < (uint32_t)te * R; idx += te) {
+    const uint32_t e = idx / R, r = idx % R;
+    if (ex0 + e < n)
+      Elt<T>::store(out + (ex0 + e) * ldo + (int64_t)g * p.Br + r0 + r, sY[r * ld + e] * p.scale);
+  }
+}
+
+hipError_t launch_generic_rows(const SketchParams& p, const void* G, int64_t ldg, int64_t n, void* out,
+                               int64_t ldo, fs_dtype dt, hipStream_t st, EventPair ev) {
+  const int te = n <= 64 ? 64 : 128;
+  const int ld = te + 1;
+  const int max_rows = (kGenericLdsBytes - kChunk * ld * 4) / (ld * 4);
+  const int rows_per_pass = (int)p.Br < max_rows ? (int)p.Br : max_rows;
+  const unsigned passes = (p.Br + rows_per_pass - 1) / rows_per_pass;
+  const int64_t ex_tiles = (n + te - 1) / te;
+  if (ex_tiles > 65535 || passes > 65535u) return hipErrorInvalidValue;
+  dim3 grid(p.M, (unsigned)ex_tiles, passes), block(te);
+  const size_t lds = (size_t)(kChunk + rows_per_pass) * ld * 4;
+#define FS_GO(T, P2) \
+  hipLaunchKernelGGL((generic_rows_kernel<T, P2>), grid, block, lds, st, p, (const T*)G, ldg, (int)n, (T*)out, ldo, rows_per_pass)
+  if (ev.start) (void)hipEventRecord(ev.start, st);
+  if (dt == FS_F32)       { if (p.br_pow2) FS_GO(float, true); else FS_GO(float, false); }
+  else if (dt == FS_BF16) { if (p.br_pow2) FS_GO(uint16_t, true); else FS_GO(uint16_t, false); }
+  else                    { if (p.br_pow2) FS_GO(f16, true); else FS_GO(f16, false); }
+#undef FS_GO
+  if (ev.stop) (void)hipEventRecord(ev.stop, st);
+  return hipGetLastError();
+}
+
 hipError_t launch_generic(const SketchParams& p, const void* A, int64_t lda, int64_t n, void* out,
                           int64_t ldo, fs_dtype dt, hipStream_t st, EventPair ev) {
   int tn = 256;

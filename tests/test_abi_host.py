@@ -124,6 +124,7 @@ def test_apply_argument_errors_before_any_hip_call():
     assert L.fs_sketch_apply_rows(h, buf, 4096, 8, buf, 255, 0, None) == 1    # ldo < k
     assert L.fs_sketch_apply_rows(h, buf, 4096, -1, buf, 256, 0, None) == 1   # n < 0
     assert L.fs_sketch_apply_rows(h, buf, 4096, 8, buf, 256, 7, None) == 1    # unknown dtype
+    assert L.fs_sketch_set_variant(h, B.VARIANT_MFMA) == 0                    # (AUTO would run the general kernel)
     assert L.fs_sketch_apply_rows(h, buf, 4098, 8, buf, 256, 0, None) == 2    # rows not 16-byte aligned
     assert L.fs_sketch_rows_workspace_bytes(h, 8, 0, C.byref(out)) == 0
     one_set = 2 * 8 * 256 * 4                                                 # kappa planes of n x k floats
@@ -131,5 +132,6 @@ def test_apply_argument_errors_before_any_hip_call():
     assert L.fs_sketch_rows_workspace_bytes(h, -1, 0, C.byref(out)) == 1
     sk.close()
     big = B.Sketch(4096, 1024, 64, 16, 16, 2)                                 # kappa*Br = 256 with Br = 16
+    big.set_variant(B.VARIANT_MFMA)
     assert L.fs_sketch_apply_rows(big._h, buf, 4096, 8, buf, 1024, 0, None) == 2
     big.close()

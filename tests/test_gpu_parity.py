@@ -505,14 +505,21 @@ ROWS = [
     ((16384, 1024, 2048, 128, 4, 8), 130, 8, 0),    # wide-config blocks, Br = 128
     ((4096, 1024, 128, 32, 8, 1), 64, 0, 4),        # Br = 32, kappa = 8, two stages per block
     ((2048, 4096, 64, 128, 3, 32), 40, 0, 0),       # one stage per block, s = 32
+    # shapes only the general kernel takes
+    ((1152, 72, 96, 6, 5, 3), 70, 1, 3),            # Br = 6, M = 12, odd row stride
+    ((4000, 256, 512, 32, 2, 4), 130, 0, 0),        # last input block partly filled
+    ((8192, 2048, 64, 16, 16, 2), 33, 0, 0),        # kappa*Br = 256 with Br = 16
+    ((1440, 180, 80, 10, 18, 10), 5, 0, 0),         # kappa = M, s = Br = 10
+    ((4096, 1024, 1024, 256, 2, 8), 129, 0, 0),     # Br = 256: two row passes per block at 128 examples a tile
 ]
 
 
+@pytest.mark.parametrize("variant", [B.VARIANT_AUTO, B.VARIANT_GENERIC], ids=lambda v: VNAME[v])
 @DTYPES
 @pytest.mark.parametrize("case", ROWS, ids=lambda c: f"{c[0]}-n{c[1]}")
-def test_apply_rows_matches_oracle(case, dtype):
+def test_apply_rows_matches_oracle(case, dtype, variant):
     params, n, pg, po = case
-    print("rows", params, n, dtype, flush=True)
+    print("rows", params, n, dtype, VNAME[variant], flush=True)
     d, k = params[0], params[1]
     g = torch.Generator(device=DEV).manual_seed(n + k)
     Gbuf = torch.randn((n, d + pg), generator=g, device=DEV).to(dtype)
@@ -520,7 +527,7 @@ def test_apply_rows_matches_oracle(case, dtype):
         Gbuf[:, d:] = float("nan")
     G = Gbuf[:, :d]
     obuf = torch.full((n, k + po), float("nan"), device=DEV, dtype=dtype)
-    sk = B.Sketch(*params, seed=9)
+    sk = make_sketch(params, 9, variant)
     sk.apply_rows(G, obuf[:, :k])
     torch.cuda.synchronize()
     ref = O.apply_rows(oracle_csc(params, 9), host64(G))
@@ -553,21 +560,24 @@ def test_apply_rows_one_hot_rows_reproduce_columns_exactly():
     assert np.array_equal(host64(out), want)
 
 
-def test_apply_rows_unsupported_shapes_report_unsupported():
+def test_apply_rows_forced_matrix_core_variant_reports_unsupported_shapes():
+    """Shapes the matrix-core rows kernel cannot take run on the general one; forcing the
+    matrix-core variant turns them into FS_ERR_UNSUPPORTED instead."""
     G = torch.zeros((4, 8192), device=DEV)
-    for params in [(8192, 2048, 64, 16, 16, 2),      # kappa*Br = 256 with Br = 16: no kernel
+    for params in [(8192, 2048, 64, 16, 16, 2),      # kappa*Br = 256 with Br = 16: no matrix-core kernel
                    (8192, 512, 1024, 64, 1, 8)]:     # fine shape, checked below with a bad stride
         sk = B.Sketch(*params, seed=0)
-        if params[4] * params[3] > 128:
-            with pytest.raises(B.FlashSketchError) as e:
-                sk.apply_rows(G)
-            assert e.value.status == 2
-        else:
-            sk.apply_rows(G)  # supported
-            odd = torch.zeros((4, 8192 + 2), device=DEV)[:, :8192]  # row stride not a multiple of 16 bytes
-            with pytest.raises(B.FlashSketchError) as e:
-                sk.apply_rows(odd)
-            assert e.value.status == 2
+        odd = torch.zeros((4, 8192 + 2), device=DEV)[:, :8192]  # row stride not a multiple of 16 bytes
+        bad = G if params[4] * params[3] > 128 else odd
+        sk.apply_rows(bad)
+        assert sk.info().last_variant == B.VARIANT_GENERIC
+        sk.set_variant(B.VARIANT_MFMA)
+        with pytest.raises(B.FlashSketchError) as e:
+            sk.apply_rows(bad)
+        assert e.value.status == 2
+        if bad is odd:
+            sk.apply_rows(G)
+            assert sk.info().last_variant == B.VARIANT_MFMA
     torch.cuda.synchronize()
 
 
