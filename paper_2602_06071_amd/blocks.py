@@ -5,7 +5,8 @@ encodes what the kernels of this library prefer, in that order:
 
   1. kappa*Br in {64, 32, 128} (in this order: measured 5-10 % apart on HBM-bound shapes, 64 also
      being the shape with the orbit-run merge): the input-stationary matrix-core path, which
-     reads A once;
+     reads A once; then any other power-of-two Br with kappa*Br <= 128 (the stacked rows sit in
+     a 32-, 64- or 128-row tile with its top rows idle), fullest tile first;
   2. Br in {128, 64, 32}: the output-stationary matrix-core path (A read kappa times);
   3. any Br dividing k (generic kernel).
 
@@ -35,8 +36,14 @@ def suggest_blocks(d: int, k: int, kappa: int, s: int = 2):
         M = k // br
         return kappa <= M <= (1 << 24) and M <= d
 
-    for path, cands in (("in", [r // kappa for r in (64, 32, 128) if r % kappa == 0]),
-                        ("out", [128, 64, 32])):
+    def fill(br):                        # share of the matrix-core tile the stacked rows use
+        rw = kappa * br
+        return rw / (32 if rw <= 32 else 64 if rw <= 64 else 128)
+
+    exact = [r // kappa for r in (64, 32, 128) if r % kappa == 0]
+    partial = sorted((b for b in (128, 64, 32, 16, 8, 4, 2, 1) if kappa * b <= 128 and b not in exact),
+                     key=lambda b: (-fill(b), -b))
+    for path, cands in (("in", exact + partial), ("out", [128, 64, 32])):
         for br in cands:
             if br >= 1 and (br & (br - 1)) == 0 and ok(br):
                 bc = _bc_for(d, k // br, 64)

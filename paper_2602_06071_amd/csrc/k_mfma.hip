@@ -599,6 +599,7 @@ void mfma_kernel(MfmaArgs a) {
         float v[4] = {acc[mt][4 * q][i], acc[mt][4 * q + 1][i], acc[mt][4 * q + 2][i], acc[mt][4 * q + 3][i]};
         if (IN_STAT) {
           const uint32_t slot = row_s >> lbr, r = row_s & (p.Br - 1);
+          if (slot >= p.kappa) continue;  // kappa*Br below the tile height: idle rows
           const int64_t plane = (int64_t)z * p.kappa + slot;
           float* dst = a.ws + (plane * p.k + (int64_t)s_blk[slot] * p.Br + r) * a.ldw + colq;
           *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
@@ -707,7 +708,9 @@ Plan make_plan(const SketchParams& p, const void* A, int64_t lda, int64_t n, fs_
   if (col_tiles > 65535) return pl;
 
   int mt_i = 0, nrg_i = 0, mt_o = 0, nrg_o = 0;
-  const bool can_in = (uint64_t)p.kappa * p.Br <= 128 && tile_shape(p.kappa * p.Br, &mt_i, &nrg_i);
+  // IN: the kappa*Br stacked rows sit in the smallest tile that holds them (rows above them idle)
+  const uint64_t rw = (uint64_t)p.kappa * p.Br;
+  const bool can_in = rw <= 128 && tile_shape(rw <= 32 ? 32 : rw <= 64 ? 64 : 128, &mt_i, &nrg_i);
   const bool can_out = tile_shape(p.Br, &mt_o, &nrg_o);
   if (!can_in && !can_out) return pl;
 
@@ -746,7 +749,7 @@ Plan make_plan(const SketchParams& p, const void* A, int64_t lda, int64_t n, fs_
     // per CU, and a merge buffer that fits beside nothing else in LDS
     constexpr int R = 4;
     const size_t merge = (size_t)(p.kappa + R - 1) * p.Br * (WCOLS * 2) * 4;
-    if (have_orbit && zs == 1 && pl.mt == 2 && pl.nrg == 1 && pl.ncg == 2 && p.kappa > 1 &&
+    if (have_orbit && zs == 1 && rw == 64 && pl.nrg == 1 && pl.ncg == 2 && p.kappa > 1 &&
         p.M % R == 0 && (int64_t)(p.M / R) * col_tiles >= 256 && merge <= 100 * 1024) {
       pl.run = R;
       pl.planes = (int)((p.kappa + R - 2) / R) + 1;

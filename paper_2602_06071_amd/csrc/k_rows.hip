@@ -23,7 +23,7 @@
 //  * fp32 inputs: exact three-way bf16 split of the 8 values a lane holds, three MFMAs;
 //  * the prefetch ring holds whole example tiles (all lines of a tile are requested together).
 //
-// Shapes: power-of-two Br with kappa*Br in {32, 64, 128}, Bc a multiple of 64 that divides d,
+// Shapes: power-of-two Br with kappa*Br <= 128 (tile height 32, 64 or 128; rows above kappa*Br idle), Bc a multiple of 64 that divides d,
 // 16-byte aligned rows.  Inputs must be finite (a dense product also multiplies by the zeros).
 #include <type_traits>
 
@@ -58,7 +58,7 @@ struct RowsArgs {
 template <typename T, int MT, int ET, bool STAGED, bool OUT>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2)))
 void rows_kernel(RowsArgs a) {
-  constexpr int RWV = 32 * MT;         // stacked output rows = kappa * Br
+  constexpr int RWV = 32 * MT;         // tile height: kappa * Br stacked output rows, rounded up
   constexpr int TILE = RWV * PHI_LD;   // bf16 elements of the Phi tile
   constexpr int ROWB = KC * (int)sizeof(T);   // bytes of a row per stage: 128 / 256
   constexpr int GLD = ROWB + 16;              // LDS row of the transposition tile (conflict-free b128)
@@ -325,7 +325,7 @@ void rows_kernel(RowsArgs a) {
 // of contiguous memory.  Without it records are indexed by block and f is evaluated directly.
 template <typename T, int VEC>
 __global__ __launch_bounds__(256) void reduce_rows_kernel(const float* __restrict__ part, int zsplit, int n,
-                                                          SketchParams p, uint32_t lbr,
+                                                          SketchParams p, uint32_t lbr, uint32_t rw,
                                                           const uint32_t* __restrict__ orbit,
                                                           T* __restrict__ out, int64_t ldo) {
   const int64_t q = p.k / VEC;
@@ -335,7 +335,6 @@ __global__ __launch_bounds__(256) void reduce_rows_kernel(const float* __restric
   const uint32_t col0 = (uint32_t)(idx % q) * VEC;
   const uint32_t bi = col0 >> lbr, r = col0 & (p.Br - 1);  // orbit position (or block) and row in block
   const uint32_t g = orbit ? orbit[bi] : bi;
-  const uint32_t rw = p.kappa << lbr;
   const int64_t z_stride = (int64_t)n * p.M * rw;
   const float* src = part + ex * (int64_t)p.M * rw + r;
   float s[VEC];
@@ -390,9 +389,9 @@ RowsPlan make_rows_plan(const SketchParams& p, const void* G, int64_t ldg, int64
     pl.out_stat = true;
     pl.mt = (int)p.Br / 32;
     pl.et = pl.mt == 4 ? 2 : 4;
-  } else if (rw == 32) { pl.mt = 1; pl.et = 4; }
-  else if (rw == 64) { pl.mt = 2; pl.et = 4; }
-  else if (rw == 128) { pl.mt = 4; pl.et = 2; }
+  } else if (rw <= 32) { pl.mt = 1; pl.et = 4; }   // the smallest tile that holds the stacked rows
+  else if (rw <= 64) { pl.mt = 2; pl.et = 4; }
+  else if (rw <= 128) { pl.mt = 4; pl.et = 2; }
   else if (br_tile) {  // too many stacked rows: output-stationary
     pl.out_stat = true;
     pl.mt = (int)p.Br / 32;
@@ -441,7 +440,8 @@ bool rows_supported(const SketchParams& p, const void* G, int64_t ldg, int64_t n
 size_t rows_workspace_bytes(const SketchParams& p, const void* G, int64_t ldg, int64_t n, fs_dtype dt) {
   const RowsPlan pl = make_rows_plan(p, G, ldg, n, dt);
   if (!pl.ok) return 0;
-  return (size_t)pl.planes * (size_t)n * (size_t)p.k * sizeof(float);  // [z][example][block][kappa*Br]
+  // [z][example][block][tile height]
+  return pl.out_stat ? 0 : (size_t)pl.zsplit * (size_t)n * (size_t)p.M * (size_t)(32 * pl.mt) * sizeof(float);
 }
 
 hipError_t launch_rows(const SketchParams& p, const void* G, int64_t ldg, int64_t n, void* out,
@@ -478,7 +478,7 @@ hipError_t launch_rows(const SketchParams& p, const void* G, int64_t ldg, int64_
   const dim3 rgrid((unsigned)((work + 255) / 256));
 #define FS_RED(T, VEC)                                                                                   \
   hipLaunchKernelGGL((reduce_rows_kernel<T, VEC>), rgrid, dim3(256), 0, st, a.ws, pl.zsplit, (int)n, p, \
-                     a.log2_br, orbit, (T*)out, ldo)
+                     a.log2_br, (uint32_t)(32 * pl.mt), orbit, (T*)out, ldo)
   if (dt == FS_BF16)     { if (vec == 4) FS_RED(uint16_t, 4); else FS_RED(uint16_t, 1); }
   else if (dt == FS_F16) { if (vec == 4) FS_RED(f16, 4); else FS_RED(f16, 1); }
   else                   { if (vec == 4) FS_RED(float, 4); else FS_RED(float, 1); }

@@ -17,6 +17,8 @@ from paper_2602_06071_amd.blocks import suggest_blocks
     (65536, 4096, 1, 8, "in"),
     (4000, 256, 2, 4, "in"),           # d not a multiple of the block: padded grid
     (1000, 90, 3, 5, "generic"),       # k has no power-of-two block
+    (49152, 768, 3, 4, "in"),          # kappa = 3: 96 stacked rows in a 128-row tile
+    (20480, 320, 5, 2, "in"),          # kappa = 5: Br = 16, 80 stacked rows in a 128-row tile
 ])
 def test_suggestions_are_valid_and_on_the_named_path(d, k, kappa, s, want):
     Bc, Br, path = suggest_blocks(d, k, kappa, s)
@@ -25,7 +27,7 @@ def test_suggestions_are_valid_and_on_the_named_path(d, k, kappa, s, want):
     p.check()                                        # the oracle's statement of the constraints
     assert k % Br == 0 and math.ceil(d / Bc) == k // Br and kappa <= k // Br and s <= Br
     if path == "in":
-        assert kappa * Br in (32, 64, 128) and Bc % 64 == 0
+        assert kappa * Br <= 128 and Br & (Br - 1) == 0 and Bc % 64 == 0
     if path == "out":
         assert Br in (32, 64, 128) and Bc % 64 == 0
     B.Sketch(d, k, Bc, Br, kappa, s).close()         # and the library's (host-side create)

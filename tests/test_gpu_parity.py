@@ -117,6 +117,13 @@ SMALL = [
     ((2048, 4096, 64, 128, 2, 32), 256, 0, 0),      # s = 32, one stage per block, Br = 128, two stages in all
     ((2048, 4096, 64, 128, 3, 4), 256, 0, 0),       # the same with an odd stage count (shallow prefetch ring)
     ((6144, 4096, 192, 128, 1, 4), 256, 0, 0),      # kappa = 1, 128 stacked rows, three stages
+    # kappa*Br below the tile height: the top rows of the matrix-core tile idle
+    ((6144, 768, 256, 32, 3, 4), 300, 0, 0),        # 96 stacked rows in a 128-row tile
+    ((2048, 128, 128, 8, 5, 2), 130, 6, 0),         # 40 in 64
+    ((4096, 64, 64, 1, 4, 1), 256, 0, 0),           # Br = 1: 4 in 32
+    ((4096, 128, 512, 16, 1, 4), 64, 0, 4),         # kappa = 1, Br = 16
+    ((512, 16, 64, 2, 7, 2), 33, 3, 0),             # 14 in 32, one stage per block
+    ((1024, 128, 128, 16, 7, 3), 256, 0, 0),        # 112 in 128, two stages (deep prefetch ring)
 ]
 
 
@@ -505,6 +512,12 @@ ROWS = [
     ((16384, 1024, 2048, 128, 4, 8), 130, 8, 0),    # wide-config blocks, Br = 128
     ((4096, 1024, 128, 32, 8, 1), 64, 0, 4),        # Br = 32, kappa = 8, two stages per block
     ((2048, 4096, 64, 128, 3, 32), 40, 0, 0),       # one stage per block, s = 32
+    # kappa*Br below the tile height
+    ((6144, 768, 256, 32, 3, 4), 100, 0, 0),        # 96 stacked rows in a 128-row tile
+    ((2048, 128, 128, 8, 5, 2), 130, 8, 0),         # 40 in 64
+    ((4096, 64, 64, 1, 4, 1), 70, 0, 0),            # Br = 1: 4 in 32, scalar reduction
+    ((4096, 128, 512, 16, 1, 4), 64, 0, 4),         # kappa = 1, Br = 16
+    ((512, 16, 64, 2, 7, 2), 33, 0, 0),             # 14 in 32
     # shapes only the general kernel takes
     ((1152, 72, 96, 6, 5, 3), 70, 1, 3),            # Br = 6, M = 12, odd row stride
     ((4000, 256, 512, 32, 2, 4), 130, 0, 0),        # last input block partly filled
