@@ -149,11 +149,12 @@ fs_status fs_sketch_apply_ld(fs_sketch_t h, const void* A, int64_t lda, int64_t 
  * out (n x k, ld = ldo >= k) = G S^T, i.e. out[i, :] = S G[i, :] -- the transpose of what
  * fs_sketch_apply_ld computes on G^T.  FS_KIND_BLOCKPERM only.  Two kernels, chosen as for
  * fs_sketch_apply (fs_sketch_set_variant applies here too):
- *  - matrix cores: needs a power-of-two Br with kappa*Br <= 128 (input-stationary: G is read
- *    once; fastest when kappa*Br is exactly 32, 64 or 128, the heights of its tiles) or else
- *    Br in {32, 64, 128} (output-stationary: G is read kappa times),
- *    Bc a multiple of 64 that divides d, a 16-byte aligned G with ldg*sizeof(elt) a multiple
- *    of 16 and 128*ldg*sizeof(elt) < 2^31.  A row stride that is a large power of two maps
+ *  - matrix cores: needs a power-of-two Br <= 128.  kappa*Br <= 128 is input-stationary (G is
+ *    read once; fastest when kappa*Br is exactly 32, 64 or 128, the heights of its tiles);
+ *    beyond that Br in {32, 64, 128} is output-stationary (G is read kappa times, mostly from
+ *    L2) and smaller Br input-stationary in groups of 128/Br wiring slots (G is read once per
+ *    group).  Also needs Bc a multiple of 64 that divides d, a 16-byte aligned G with
+ *    ldg*sizeof(elt) a multiple of 16, and 128*ldg*sizeof(elt) < 2^31.  A row stride that is a large power of two maps
  *    the rows of a tile to one HBM channel: prefer ldg = d + 64 elements.
  *  - general: every other valid sketch and alignment (any Br, partly filled last block);
  *    tiles are turned through LDS and accumulated without atomics, G is read kappa times.

@@ -61,6 +61,7 @@ struct MfmaArgs {
   int64_t lda, ldo, ldw;
   int n;
   int zsplit;       // IN: row splits of an input block; OUT: splits of the kappa*Bc rows
+  int group_slots;  // IN: wiring slots one work-group stacks (grid.z = zsplit * slot groups)
   int stages;       // stages per work-group
   int out_vec;      // out rows allow 4-column vector stores
   uint32_t log2_br;
@@ -115,7 +116,11 @@ void mfma_kernel(MfmaArgs a) {
   uint32_t blk = bx;
   if (RUN > 1) blk = __builtin_amdgcn_readfirstlane(a.pos2blk[blockIdx.x * RUN + sg]);
   if (remap) blk = __builtin_amdgcn_readfirstlane(a.pos2blk[opos]);
-  const int z = (int)blockIdx.z;
+  // IN with kappa*Br above the tile height: grid.z also numbers groups of `group_slots` wiring
+  // slots; a work-group then serves the slots [slot0, slot0 + kap) and A is read once per group
+  const int z = (int)(blockIdx.z % (uint32_t)a.zsplit);
+  const uint32_t slot0 = IN_STAT ? (blockIdx.z / (uint32_t)a.zsplit) * (uint32_t)a.group_slots : 0u;
+  const uint32_t kap = IN_STAT ? min(p.kappa - slot0, (uint32_t)a.group_slots) : p.kappa;
   const int T_stages = a.stages;
   const uint32_t rows_per_blk_stage = p.Bc / KC;  // stages per input block (OUT)
   const uint32_t lbr = a.log2_br;
@@ -128,7 +133,7 @@ void mfma_kernel(MfmaArgs a) {
       if (TILE / 8 % 64 == 0 || lane + i * 64 < TILE / 8) z4[lane + i * 64] = make_uint4(0, 0, 0, 0);
   };
   auto setup_tables = [&]() {
-    for (int sl = tid; sl < (int)p.kappa; sl += NT) {
+    for (int sl = tid; sl < (int)kap; sl += NT) {
       uint32_t x = blk;
       if (remap) {
         // phase sl handles the neighbour whose (unwrapped) orbit position is sl mod kappa:
@@ -136,7 +141,7 @@ void mfma_kernel(MfmaArgs a) {
         const uint32_t l = (sl + p.kappa - (opos + 1) % p.kappa) % p.kappa;  // 0 .. kappa-1
         x = a.pos2blk[(opos + 1 + l) % p.M];
       } else {
-        for (int l = 0; l <= sl; ++l)
+        for (int l = 0; l <= (int)slot0 + sl; ++l)
           x = IN_STAT ? wire_prev(x, p.a_inv, p.b, p.M) : wire_next(x, p.a, p.b, p.M);
       }
       s_blk[sl] = x;
@@ -203,7 +208,7 @@ void mfma_kernel(MfmaArgs a) {
     if (IN_STAT) {
       const uint32_t u = (uint32_t)(z * T_stages + t) * KC + lane;
       const uint32_t slot_lo = row_lo >> lbr;
-      const uint32_t slot_hi = min(p.kappa, ((row_lo + RWV - 1) >> lbr) + 1);
+      const uint32_t slot_hi = min(kap, ((row_lo + RWV - 1) >> lbr) + 1);
       const bool whole = p.Br <= (uint32_t)RWV;  // power-of-two Br: slots tile the wave's rows
       for (uint32_t slot = slot_lo + part; slot < slot_hi; slot += KSTEPS)
         scatter(phi, s_bk[slot], u, slot << lbr, whole);
@@ -599,8 +604,8 @@ void mfma_kernel(MfmaArgs a) {
         float v[4] = {acc[mt][4 * q][i], acc[mt][4 * q + 1][i], acc[mt][4 * q + 2][i], acc[mt][4 * q + 3][i]};
         if (IN_STAT) {
           const uint32_t slot = row_s >> lbr, r = row_s & (p.Br - 1);
-          if (slot >= p.kappa) continue;  // kappa*Br below the tile height: idle rows
-          const int64_t plane = (int64_t)z * p.kappa + slot;
+          if (slot >= kap) continue;  // fewer stacked rows than the tile is high: idle rows
+          const int64_t plane = (int64_t)z * p.kappa + slot0 + slot;
           float* dst = a.ws + (plane * p.k + (int64_t)s_blk[slot] * p.Br + r) * a.ldw + colq;
           *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
         } else if (a.zsplit > 1) {  // OUT with split rows: plane z, summed by the reduce kernel
@@ -674,6 +679,7 @@ struct Plan {
   bool ok = false;
   bool in_stat = false;
   int mt = 0, nrg = 0, ncg = 0, zsplit = 1, stages = 0, run = 1, cpl = 4, pfx = 1;
+  int groups = 1, group_slots = 0;  // IN: slot groups (A is read once per group)
   int64_t ldw = 0;
   int planes = 0;
   size_t lds = 0;
@@ -710,9 +716,14 @@ Plan make_plan(const SketchParams& p, const void* A, int64_t lda, int64_t n, fs_
   int mt_i = 0, nrg_i = 0, mt_o = 0, nrg_o = 0;
   // IN: the kappa*Br stacked rows sit in the smallest tile that holds them (rows above them idle)
   const uint64_t rw = (uint64_t)p.kappa * p.Br;
-  const bool can_in = rw <= 128 && tile_shape(rw <= 32 ? 32 : rw <= 64 ? 64 : 128, &mt_i, &nrg_i);
   const bool can_out = tile_shape(p.Br, &mt_o, &nrg_o);
+  // More stacked rows than the highest tile and blocks too small for OUT: groups of 128/Br slots,
+  // each a work-group of its own that reads the input block again.
+  const bool grouped = rw > 128 && !can_out && p.Br < 32;
+  const bool can_in = (rw <= 128 || grouped) && tile_shape(rw <= 32 ? 32 : rw <= 64 ? 64 : 128, &mt_i, &nrg_i);
   if (!can_in && !can_out) return pl;
+  const int group_slots = grouped ? (int)(128 / p.Br) : (int)p.kappa;
+  const int groups = (int)((p.kappa + group_slots - 1) / group_slots);
 
   // IN-stationary row split: more work-groups fill the chip better, but every split adds kappa
   // partial planes.  Pick the split with the smallest modelled time: A streamed at ~6 TB/s once
@@ -720,12 +731,12 @@ Plan make_plan(const SketchParams& p, const void* A, int64_t lda, int64_t n, fs_
   // (rates measured on this kernel pair).
   int zs = 1;
   {
-    const double a_bytes = (double)p.d * (double)n * esz;
+    const double a_bytes = (double)p.d * (double)n * esz * groups;
     const double waves_per_wg = pl.ncg * (can_in ? nrg_i : 1);
     double best = 0;
     for (int zc = 1; zc <= 16; zc *= 2) {
       if (zc > 1 && ((p.Bc / zc) % KC != 0 || p.Bc / zc < (uint32_t)KC)) break;
-      const double waves = (double)p.M * col_tiles * zc * waves_per_wg;
+      const double waves = (double)p.M * col_tiles * zc * waves_per_wg * groups;
       const double plane_bytes = (double)zc * p.kappa * (double)p.k * (double)n * 4.0;
       const double t = a_bytes / (6e12 * (waves < 1024 ? waves / 1024 : 1.0)) + plane_bytes / 3.4e12 +
                        plane_bytes / 6e12;
@@ -744,7 +755,8 @@ Plan make_plan(const SketchParams& p, const void* A, int64_t lda, int64_t n, fs_
     pl.stages = (int)(p.Bc / zs / KC);
     pl.ldw = (n + 3) & ~(int64_t)3;
     pl.planes = zs * (int)p.kappa;
-    if (zs > 65535) return pl;
+    pl.groups = groups; pl.group_slots = group_slots;
+    if (zs * groups > 65535) return pl;
     // orbit runs of 4: the 64-row / 256-column shape, enough blocks for one work-group
     // per CU, and a merge buffer that fits beside nothing else in LDS
     constexpr int R = 4;
@@ -845,12 +857,13 @@ hipError_t launch_mfma(const SketchParams& p, const void* A, int64_t lda, int64_
   a.pos2blk = orbit;
   a.lda = lda; a.ldo = ldo; a.ldw = pl.ldw; a.n = (int)n;
   a.zsplit = pl.zsplit; a.stages = pl.stages;
+  a.group_slots = pl.in_stat ? pl.group_slots : (int)p.kappa;
   a.out_vec = ((uintptr_t)out % (4 * esz) == 0 && (ldo * esz) % (4 * esz) == 0) ? 1 : 0;
   a.log2_br = 0;
   while ((1u << a.log2_br) < p.Br) ++a.log2_br;
   const int tnw = 32 * pl.cpl * pl.ncg;
   const unsigned col_tiles = (unsigned)((n + tnw - 1) / tnw);
-  dim3 grid(p.M / pl.run, col_tiles, pl.zsplit);
+  dim3 grid(p.M / pl.run, col_tiles, pl.zsplit * pl.groups);
 
   if (ev.start) (void)hipEventRecord(ev.start, st);
   hipError_t e;

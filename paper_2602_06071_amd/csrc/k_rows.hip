@@ -46,6 +46,8 @@ struct RowsArgs {
   int64_t ldg, ldo;
   int n;        // examples
   int stages;   // 64-row stages per work-group
+  int zsplit;       // IN: row splits of an input block
+  int group_slots;  // IN: wiring slots one work-group stacks (grid.z = zsplit * slot groups)
   uint32_t log2_br;
 };
 
@@ -93,18 +95,22 @@ void rows_kernel(RowsArgs a) {
     blk = __builtin_amdgcn_readfirstlane(a.orbit[opos]);
   }
   const int ex0 = (int)ey * (32 * ET);
-  const int z = (int)blockIdx.z;
+  // IN with kappa*Br above the tile height: grid.z also numbers groups of `group_slots` wiring
+  // slots; a work-group serves the slots [slot0, slot0 + kap) and G is read once per group
+  const int z = OUT ? 0 : (int)(blockIdx.z % (uint32_t)a.zsplit);
+  const uint32_t slot0 = OUT ? 0u : (blockIdx.z / (uint32_t)a.zsplit) * (uint32_t)a.group_slots;
+  const uint32_t kap = OUT ? p.kappa : min(p.kappa - slot0, (uint32_t)a.group_slots);
   const int T_stages = a.stages;
   const uint32_t lbr = a.log2_br;
 
   // slot tables and an empty tile
-  for (int sl = lane; sl < (int)p.kappa; sl += 64) {
+  for (int sl = lane; sl < (int)kap; sl += 64) {
     uint32_t x = blk;
     if (remap) {
       const uint32_t l = (sl + p.kappa - (opos + 1) % p.kappa) % p.kappa;  // 0 .. kappa-1
       x = a.orbit[(opos + 1 + l) % p.M];
     } else {
-      for (int l = 0; l <= sl; ++l) x = OUT ? wire_next(x, p.a, p.b, p.M) : wire_prev(x, p.a_inv, p.b, p.M);
+      for (int l = 0; l <= (int)slot0 + sl; ++l) x = OUT ? wire_next(x, p.a, p.b, p.M) : wire_prev(x, p.a_inv, p.b, p.M);
     }
     s_blk[sl] = x;
     s_bk[sl] = OUT ? block_key(p.key1, blk, x, p.M) : block_key(p.key1, x, blk, p.M);
@@ -192,7 +198,7 @@ void rows_kernel(RowsArgs a) {
       return;
     }
     const uint32_t u = (uint32_t)(z * T_stages + t) * KC + lane;
-    for (uint32_t slot = part; slot < p.kappa; slot += KSTEPS) {
+    for (uint32_t slot = part; slot < kap; slot += KSTEPS) {
       const RowHash rh = row_hash_pow2(s_bk[slot], u, p.Br);
       uint32_t r = rh.shift;
       const uint32_t base = slot << lbr;
@@ -302,7 +308,7 @@ void rows_kernel(RowsArgs a) {
   // output's position p), and neighbouring outputs read neighbouring records.
   {
     const uint32_t rec = a.orbit ? __builtin_amdgcn_readfirstlane(a.orbit[p.M + blk]) : blk;
-    float* base = a.ws + (((int64_t)z * a.n + ex0) * p.M + rec) * RWV + m;
+    float* base = a.ws + (((int64_t)blockIdx.z * a.n + ex0) * p.M + rec) * RWV + m;  // set (group, z)
     const int64_t ex_stride = (int64_t)p.M * RWV;
 #pragma unroll
     for (int c = 0; c < ET; ++c)
@@ -326,6 +332,7 @@ void rows_kernel(RowsArgs a) {
 template <typename T, int VEC>
 __global__ __launch_bounds__(256) void reduce_rows_kernel(const float* __restrict__ part, int zsplit, int n,
                                                           SketchParams p, uint32_t lbr, uint32_t rw,
+                                                          uint32_t group_slots,
                                                           const uint32_t* __restrict__ orbit,
                                                           T* __restrict__ out, int64_t ldo) {
   const int64_t q = p.k / VEC;
@@ -344,7 +351,8 @@ __global__ __launch_bounds__(256) void reduce_rows_kernel(const float* __restric
   for (uint32_t l = 0; l < p.kappa; ++l) {
     if (orbit) rec = rec + 1 == p.M ? 0u : rec + 1;
     else rec = wire_next(rec, p.a, p.b, p.M);
-    const float* ph = src + (int64_t)rec * rw + (l << lbr);
+    const uint32_t grp = l / group_slots;  // the set of records that holds slot l, and where in a record
+    const float* ph = src + (int64_t)grp * zsplit * z_stride + (int64_t)rec * rw + ((l - grp * group_slots) << lbr);
     for (int zc = 0; zc < zsplit; ++zc) {
       if constexpr (VEC == 4) {
         const float4 v = *reinterpret_cast<const float4*>(ph + zc * z_stride);
@@ -374,7 +382,7 @@ __global__ __launch_bounds__(256) void reduce_rows_kernel(const float* __restric
 
 struct RowsPlan {
   bool ok = false;
-  int mt = 0, et = 0, zsplit = 1, stages = 0, planes = 0;
+  int mt = 0, et = 0, zsplit = 1, stages = 0, planes = 0, groups = 1, group_slots = 0;
   bool staged = false, out_stat = false;
   size_t lds = 0;
 };
@@ -392,7 +400,11 @@ RowsPlan make_rows_plan(const SketchParams& p, const void* G, int64_t ldg, int64
   } else if (rw <= 32) { pl.mt = 1; pl.et = 4; }   // the smallest tile that holds the stacked rows
   else if (rw <= 64) { pl.mt = 2; pl.et = 4; }
   else if (rw <= 128) { pl.mt = 4; pl.et = 2; }
-  else if (br_tile) {  // too many stacked rows: output-stationary
+  else if (p.Br < 32) {  // more stacked rows than the highest tile, blocks too small for OUT:
+    pl.mt = 4; pl.et = 2;  // groups of 128/Br slots, G read once per group
+    pl.group_slots = (int)(128 / p.Br);
+    pl.groups = (int)((p.kappa + pl.group_slots - 1) / pl.group_slots);
+  } else if (br_tile) {  // too many stacked rows: output-stationary
     pl.out_stat = true;
     pl.mt = (int)p.Br / 32;
     pl.et = pl.mt == 4 ? 2 : 4;
@@ -403,11 +415,12 @@ RowsPlan make_rows_plan(const SketchParams& p, const void* G, int64_t ldg, int64
   if (ex_tiles > 65535) return pl;
   // row split: the traffic model of the column layout (G at ~6 TB/s once 1024 waves exist,
   // planes written at ~3.4 TB/s and read back at ~6 TB/s)
-  const double g_bytes = (double)p.d * (double)n * esz;
+  if (pl.group_slots == 0) pl.group_slots = (int)p.kappa;
+  const double g_bytes = (double)p.d * (double)n * esz * pl.groups;
   double best = 0;
   for (int zc = 1; zc <= 16; zc *= 2) {
     if (zc > 1 && ((p.Bc / zc) % KC != 0 || p.Bc / zc < (uint32_t)KC)) break;
-    const double waves = (double)p.M * ex_tiles * zc;
+    const double waves = (double)p.M * ex_tiles * zc * pl.groups;
     const double plane_bytes = (double)zc * p.kappa * (double)p.k * (double)n * 4.0;
     const double t = g_bytes / (6e12 * (waves < 1024 ? waves / 1024 : 1.0)) + plane_bytes / 3.4e12 +
                      plane_bytes / 6e12;
@@ -441,7 +454,8 @@ size_t rows_workspace_bytes(const SketchParams& p, const void* G, int64_t ldg, i
   const RowsPlan pl = make_rows_plan(p, G, ldg, n, dt);
   if (!pl.ok) return 0;
   // [z][example][block][tile height]
-  return pl.out_stat ? 0 : (size_t)pl.zsplit * (size_t)n * (size_t)p.M * (size_t)(32 * pl.mt) * sizeof(float);
+  return pl.out_stat ? 0 : (size_t)pl.groups * (size_t)pl.zsplit * (size_t)n * (size_t)p.M * (size_t)(32 * pl.mt) *
+                               sizeof(float);
 }
 
 hipError_t launch_rows(const SketchParams& p, const void* G, int64_t ldg, int64_t n, void* out,
@@ -455,7 +469,8 @@ hipError_t launch_rows(const SketchParams& p, const void* G, int64_t ldg, int64_
   a.stages = pl.stages;
   a.log2_br = 0;
   while ((1u << a.log2_br) < p.Br) ++a.log2_br;
-  const dim3 grid(p.M, (unsigned)((n + 32 * pl.et - 1) / (32 * pl.et)), pl.zsplit);
+  a.zsplit = pl.zsplit; a.group_slots = pl.group_slots;
+  const dim3 grid(p.M, (unsigned)((n + 32 * pl.et - 1) / (32 * pl.et)), pl.zsplit * pl.groups);
 
   if (ev.start) (void)hipEventRecord(ev.start, st);
   hipError_t e;
@@ -478,7 +493,7 @@ hipError_t launch_rows(const SketchParams& p, const void* G, int64_t ldg, int64_
   const dim3 rgrid((unsigned)((work + 255) / 256));
 #define FS_RED(T, VEC)                                                                                   \
   hipLaunchKernelGGL((reduce_rows_kernel<T, VEC>), rgrid, dim3(256), 0, st, a.ws, pl.zsplit, (int)n, p, \
-                     a.log2_br, (uint32_t)(32 * pl.mt), orbit, (T*)out, ldo)
+                     a.log2_br, (uint32_t)(32 * pl.mt), (uint32_t)pl.group_slots, orbit, (T*)out, ldo)
   if (dt == FS_BF16)     { if (vec == 4) FS_RED(uint16_t, 4); else FS_RED(uint16_t, 1); }
   else if (dt == FS_F16) { if (vec == 4) FS_RED(f16, 4); else FS_RED(f16, 1); }
   else                   { if (vec == 4) FS_RED(float, 4); else FS_RED(float, 1); }

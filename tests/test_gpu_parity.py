@@ -124,6 +124,11 @@ SMALL = [
     ((4096, 128, 512, 16, 1, 4), 64, 0, 4),         # kappa = 1, Br = 16
     ((512, 16, 64, 2, 7, 2), 33, 3, 0),             # 14 in 32, one stage per block
     ((1024, 128, 128, 16, 7, 3), 256, 0, 0),        # 112 in 128, two stages (deep prefetch ring)
+    # more than 128 stacked rows of small blocks: groups of 128/Br wiring slots
+    ((8192, 2048, 64, 16, 16, 2), 300, 0, 0),       # 256 rows: two full groups
+    ((2048, 256, 64, 8, 20, 2), 130, 2, 0),         # 160 rows: a full group and one of 4 slots
+    ((4096, 256, 64, 4, 40, 3), 70, 2, 4),          # Br = 4: groups of 32 slots
+    ((8192, 128, 64, 1, 128, 1), 64, 0, 0),         # Br = 1, kappa = M = 128: one full group
 ]
 
 
@@ -518,10 +523,13 @@ ROWS = [
     ((4096, 64, 64, 1, 4, 1), 70, 0, 0),            # Br = 1: 4 in 32, scalar reduction
     ((4096, 128, 512, 16, 1, 4), 64, 0, 4),         # kappa = 1, Br = 16
     ((512, 16, 64, 2, 7, 2), 33, 0, 0),             # 14 in 32
+    # more than 128 stacked rows of small blocks: groups of 128/Br wiring slots
+    ((8192, 2048, 64, 16, 16, 2), 33, 0, 0),        # 256 rows: two full groups
+    ((2048, 256, 64, 8, 20, 2), 130, 0, 0),         # 160 rows: a full group and one of 4 slots
+    ((4096, 256, 64, 4, 40, 3), 70, 8, 4),          # Br = 4: groups of 32 slots
     # shapes only the general kernel takes
     ((1152, 72, 96, 6, 5, 3), 70, 1, 3),            # Br = 6, M = 12, odd row stride
     ((4000, 256, 512, 32, 2, 4), 130, 0, 0),        # last input block partly filled
-    ((8192, 2048, 64, 16, 16, 2), 33, 0, 0),        # kappa*Br = 256 with Br = 16
     ((1440, 180, 80, 10, 18, 10), 5, 0, 0),         # kappa = M, s = Br = 10
     ((4096, 1024, 1024, 256, 2, 8), 129, 0, 0),     # Br = 256: two row passes per block at 128 examples a tile
 ]
@@ -577,11 +585,11 @@ def test_apply_rows_forced_matrix_core_variant_reports_unsupported_shapes():
     """Shapes the matrix-core rows kernel cannot take run on the general one; forcing the
     matrix-core variant turns them into FS_ERR_UNSUPPORTED instead."""
     G = torch.zeros((4, 8192), device=DEV)
-    for params in [(8192, 2048, 64, 16, 16, 2),      # kappa*Br = 256 with Br = 16: no matrix-core kernel
+    for params in [(8192, 384, 128, 6, 4, 2),        # Br = 6: no matrix-core kernel
                    (8192, 512, 1024, 64, 1, 8)]:     # fine shape, checked below with a bad stride
         sk = B.Sketch(*params, seed=0)
         odd = torch.zeros((4, 8192 + 2), device=DEV)[:, :8192]  # row stride not a multiple of 16 bytes
-        bad = G if params[4] * params[3] > 128 else odd
+        bad = G if params[3] == 6 else odd
         sk.apply_rows(bad)
         assert sk.info().last_variant == B.VARIANT_GENERIC
         sk.set_variant(B.VARIANT_MFMA)
