@@ -8,7 +8,9 @@ encodes what the kernels of this library prefer, in that order:
      reads A once; then any other power-of-two Br with kappa*Br <= 128 (the stacked rows sit in
      a 32-, 64- or 128-row tile with its top rows idle), fullest tile first;
   2. Br in {128, 64, 32}: the output-stationary matrix-core path (A read kappa times);
-  3. any Br dividing k (generic kernel).
+  3. Br in {16, 8, 4, 2, 1} with kappa*Br > 128: input-stationary in groups of 128/Br wiring
+     slots (A read once per group);
+  4. any Br dividing k (generic kernel).
 
 subject to the sketch's own constraints: Br | k, M = k/Br = ceil(d/Bc), kappa <= M, s <= Br,
 and for the matrix-core paths Bc a multiple of 64.  It only does integer arithmetic on shapes;
@@ -25,7 +27,7 @@ def _bc_for(d: int, M: int, multiple: int):
 
 
 def suggest_blocks(d: int, k: int, kappa: int, s: int = 2):
-    """Return (Bc, Br, path) with path in {"in", "out", "generic"}, or raise ValueError when no
+    """Return (Bc, Br, path) with path in {"in", "out", "grouped", "generic"}, or raise ValueError when no
     block grid satisfies the constraints (e.g. kappa > k)."""
     if min(d, k, kappa, s) < 1:
         raise ValueError("d, k, kappa, s must be positive")
@@ -43,7 +45,8 @@ def suggest_blocks(d: int, k: int, kappa: int, s: int = 2):
     exact = [r // kappa for r in (64, 32, 128) if r % kappa == 0]
     partial = sorted((b for b in (128, 64, 32, 16, 8, 4, 2, 1) if kappa * b <= 128 and b not in exact),
                      key=lambda b: (-fill(b), -b))
-    for path, cands in (("in", exact + partial), ("out", [128, 64, 32])):
+    grouped = [b for b in (16, 8, 4, 2, 1) if kappa * b > 128]
+    for path, cands in (("in", exact + partial), ("out", [128, 64, 32]), ("grouped", grouped)):
         for br in cands:
             if br >= 1 and (br & (br - 1)) == 0 and ok(br):
                 bc = _bc_for(d, k // br, 64)

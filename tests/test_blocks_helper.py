@@ -18,6 +18,7 @@ from paper_2602_06071_amd.blocks import suggest_blocks
     (4000, 256, 2, 4, "in"),           # d not a multiple of the block: padded grid
     (1000, 90, 3, 5, "generic"),       # k has no power-of-two block
     (49152, 768, 3, 4, "in"),          # kappa = 3: 96 stacked rows in a 128-row tile
+    (16896, 528, 32, 8, "grouped"),    # k = 16 * 33, s = 8: no block of 32 rows or more, kappa*16 = 512
     (20480, 320, 5, 2, "in"),          # kappa = 5: Br = 16, 80 stacked rows in a 128-row tile
 ])
 def test_suggestions_are_valid_and_on_the_named_path(d, k, kappa, s, want):
@@ -28,6 +29,8 @@ def test_suggestions_are_valid_and_on_the_named_path(d, k, kappa, s, want):
     assert k % Br == 0 and math.ceil(d / Bc) == k // Br and kappa <= k // Br and s <= Br
     if path == "in":
         assert kappa * Br <= 128 and Br & (Br - 1) == 0 and Bc % 64 == 0
+    if path == "grouped":
+        assert Br in (1, 2, 4, 8, 16) and kappa * Br > 128 and Bc % 64 == 0
     if path == "out":
         assert Br in (32, 64, 128) and Bc % 64 == 0
     B.Sketch(d, k, Bc, Br, kappa, s).close()         # and the library's (host-side create)
