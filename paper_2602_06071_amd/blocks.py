@@ -12,8 +12,10 @@ encodes what the kernels of this library prefer, in that order:
      slots (A read once per group);
   4. any Br dividing k (generic kernel).
 
-subject to the sketch's own constraints: Br | k, M = k/Br = ceil(d/Bc), kappa <= M, s <= Br,
-and for the matrix-core paths Bc a multiple of 64.  It only does integer arithmetic on shapes;
+subject to the sketch's own constraints: Br | k, M = k/Br = ceil(d/Bc), kappa <= M, s <= Br.
+For a given Br, Bc is the smallest multiple of 64 with ceil(d/Bc) = M when there is one (whole
+64-row stages; the examples-as-rows kernel needs that, and Bc | d), else ceil(d/M): the
+column-layout matrix-core kernel takes any Bc, its last stage per block partly filled.  It only does integer arithmetic on shapes;
 nothing here touches the sketch's hash or values.
 """
 from __future__ import annotations
@@ -49,7 +51,7 @@ def suggest_blocks(d: int, k: int, kappa: int, s: int = 2):
     for path, cands in (("in", exact + partial), ("out", [128, 64, 32]), ("grouped", grouped)):
         for br in cands:
             if br >= 1 and (br & (br - 1)) == 0 and ok(br):
-                bc = _bc_for(d, k // br, 64)
+                bc = _bc_for(d, k // br, 64) or _bc_for(d, k // br, 1)
                 if bc is not None:
                     return bc, br, path
     for br in sorted((b for b in range(1, min(k, 65536) + 1) if k % b == 0), key=lambda b: abs(b - 32)):

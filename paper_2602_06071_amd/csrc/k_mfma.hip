@@ -122,7 +122,9 @@ void mfma_kernel(MfmaArgs a) {
   const uint32_t slot0 = IN_STAT ? (blockIdx.z / (uint32_t)a.zsplit) * (uint32_t)a.group_slots : 0u;
   const uint32_t kap = IN_STAT ? min(p.kappa - slot0, (uint32_t)a.group_slots) : p.kappa;
   const int T_stages = a.stages;
-  const uint32_t rows_per_blk_stage = p.Bc / KC;  // stages per input block (OUT)
+  // stages per input block (OUT).  Bc need not be a multiple of the stage: the rows of the last
+  // stage at or beyond Bc lie outside the block's buffer range and read as 0.
+  const uint32_t rows_per_blk_stage = (p.Bc + KC - 1) / KC;
   const uint32_t lbr = a.log2_br;
 
   // ---- slot tables and empty tiles ------------------------------------------------
@@ -245,10 +247,11 @@ void mfma_kernel(MfmaArgs a) {
     // scalar registers and only rebuilds the descriptor when it crosses into the next block.
     __amdgpu_buffer_rsrc_t f_rs = make_rsrc(0, 0);
     uint32_t f_so = 0, f_kr = 0, f_l = 0;
-    const uint32_t per_blk_k = p.Bc / 16;
+    const uint32_t per_blk_k = rows_per_blk_stage * KSTEPS;
     auto cursor_init = [&]() {
       if (IN_STAT) {
-        f_rs = make_rsrc((int64_t)blk * p.Bc + (int64_t)z * T_stages * KC, (int64_t)T_stages * KC);
+        const int64_t row0 = (int64_t)z * T_stages * KC;  // the range ends with the block's last row
+        f_rs = make_rsrc((int64_t)blk * p.Bc + row0, min((int64_t)T_stages * KC, (int64_t)p.Bc - row0));
       } else {
         const uint32_t kg0 = (uint32_t)(z * T_stages * KSTEPS);
         f_l = kg0 / per_blk_k;
@@ -705,10 +708,11 @@ Plan make_plan(const SketchParams& p, const void* A, int64_t lda, int64_t n, fs_
                bool have_orbit) {
   Plan pl;
   const size_t esz = dt == FS_F32 ? 4 : 2;
-  if (!p.br_pow2 || p.Bc % KC || p.kappa > (uint32_t)MAX_KAPPA || n < 1) return pl;
+  if (!p.br_pow2 || p.kappa > (uint32_t)MAX_KAPPA || n < 1) return pl;
+  const int64_t blk_stages = ((int64_t)p.Bc + KC - 1) / KC;  // the last one may be partly filled
   if ((uintptr_t)A % (4 * esz) || (lda * esz) % (4 * esz)) return pl;  // 4-column vector loads
   if ((16 * lda + n) * (int64_t)esz >= ((int64_t)1 << 31)) return pl;     // 32-bit lane offsets
-  if ((int64_t)p.Bc * lda * (int64_t)esz >= ((int64_t)1 << 31)) return pl;  // 32-bit row offsets in a block
+  if (blk_stages * KC * lda * (int64_t)esz >= ((int64_t)1 << 31)) return pl;  // 32-bit row offsets in a block
   pl.ncg = n > WCOLS ? 2 : 1;
   const int64_t col_tiles = (n + WCOLS * pl.ncg - 1) / (WCOLS * pl.ncg);
   if (col_tiles > 65535) return pl;
@@ -735,7 +739,7 @@ Plan make_plan(const SketchParams& p, const void* A, int64_t lda, int64_t n, fs_
     const double waves_per_wg = pl.ncg * (can_in ? nrg_i : 1);
     double best = 0;
     for (int zc = 1; zc <= 16; zc *= 2) {
-      if (zc > 1 && ((p.Bc / zc) % KC != 0 || p.Bc / zc < (uint32_t)KC)) break;
+      if (zc > 1 && p.Bc % (uint32_t)(zc * KC) != 0) break;  // splits are whole stages
       const double waves = (double)p.M * col_tiles * zc * waves_per_wg * groups;
       const double plane_bytes = (double)zc * p.kappa * (double)p.k * (double)n * 4.0;
       const double t = a_bytes / (6e12 * (waves < 1024 ? waves / 1024 : 1.0)) + plane_bytes / 3.4e12 +
@@ -752,7 +756,7 @@ Plan make_plan(const SketchParams& p, const void* A, int64_t lda, int64_t n, fs_
   pl.in_stat = can_in && (!can_out || (p.kappa > 1 && (out_starved || rho <= 0.23 * (p.kappa - 1))));
   if (pl.in_stat) {
     pl.mt = mt_i; pl.nrg = nrg_i; pl.zsplit = zs;
-    pl.stages = (int)(p.Bc / zs / KC);
+    pl.stages = (int)(blk_stages / zs);
     pl.ldw = (n + 3) & ~(int64_t)3;
     pl.planes = zs * (int)p.kappa;
     pl.groups = groups; pl.group_slots = group_slots;
@@ -769,7 +773,7 @@ Plan make_plan(const SketchParams& p, const void* A, int64_t lda, int64_t n, fs_
   } else {
     // split the kappa*Bc rows of a work-group over grid.z when there are too few output tiles to
     // fill the chip (small n), as long as the extra plane traffic stays below that of reading A
-    const int total_stages = (int)((uint64_t)p.kappa * p.Bc / KC);
+    const int total_stages = (int)((int64_t)p.kappa * blk_stages);
     int zo = 1;
     while ((int64_t)p.M * col_tiles * zo < 512 && zo < 8 && total_stages % (zo * 2) == 0 &&
            2.0 * (zo * 2) * (double)p.k * 4.0 / ((double)p.d * esz) <= 1.0)

@@ -19,6 +19,7 @@ from paper_2602_06071_amd.blocks import suggest_blocks
     (1000, 90, 3, 5, "generic"),       # k has no power-of-two block
     (49152, 768, 3, 4, "in"),          # kappa = 3: 96 stacked rows in a 128-row tile
     (16896, 528, 32, 8, "grouped"),    # k = 16 * 33, s = 8: no block of 32 rows or more, kappa*16 = 512
+    (1000, 384, 2, 4, "in"),           # M = 12: no multiple of 64 gives 12 blocks, Bc = 84
     (20480, 320, 5, 2, "in"),          # kappa = 5: Br = 16, 80 stacked rows in a 128-row tile
 ])
 def test_suggestions_are_valid_and_on_the_named_path(d, k, kappa, s, want):
@@ -28,11 +29,11 @@ def test_suggestions_are_valid_and_on_the_named_path(d, k, kappa, s, want):
     p.check()                                        # the oracle's statement of the constraints
     assert k % Br == 0 and math.ceil(d / Bc) == k // Br and kappa <= k // Br and s <= Br
     if path == "in":
-        assert kappa * Br <= 128 and Br & (Br - 1) == 0 and Bc % 64 == 0
+        assert kappa * Br <= 128 and Br & (Br - 1) == 0 and (Bc % 64 == 0 or Bc == -(-d // (k // Br)))
     if path == "grouped":
-        assert Br in (1, 2, 4, 8, 16) and kappa * Br > 128 and Bc % 64 == 0
+        assert Br in (1, 2, 4, 8, 16) and kappa * Br > 128 and (Bc % 64 == 0 or Bc == -(-d // (k // Br)))
     if path == "out":
-        assert Br in (32, 64, 128) and Bc % 64 == 0
+        assert Br in (32, 64, 128) and (Bc % 64 == 0 or Bc == -(-d // (k // Br)))
     B.Sketch(d, k, Bc, Br, kappa, s).close()         # and the library's (host-side create)
 
 

@@ -129,6 +129,12 @@ SMALL = [
     ((2048, 256, 64, 8, 20, 2), 130, 2, 0),         # 160 rows: a full group and one of 4 slots
     ((4096, 256, 64, 4, 40, 3), 70, 2, 4),          # Br = 4: groups of 32 slots
     ((8192, 128, 64, 1, 128, 1), 64, 0, 0),         # Br = 1, kappa = M = 128: one full group
+    # Bc not a multiple of the 64-row stage: the last stage of a block is partly filled
+    ((1000, 256, 125, 32, 2, 4), 300, 0, 0),        # Bc = 125, input-stationary
+    ((1536, 1024, 96, 64, 4, 4), 256, 0, 0),        # Bc = 96, output-stationary
+    ((640, 128, 40, 8, 4, 2), 130, 2, 0),           # Bc = 40: less than one stage
+    ((1990, 128, 250, 16, 8, 2), 64, 0, 0),         # Bc = 250 and a partly filled last block
+    ((73728, 8192, 72, 8, 8, 2), 256, 0, 0),        # Bc = 72, orbit runs
 ]
 
 
@@ -141,10 +147,11 @@ def test_apply_matches_oracle(case, dtype, variant):
     seed = 5
     d, k = params[0], params[1]
     g = torch.Generator(device=DEV).manual_seed(n + d)
-    Abuf = torch.randn((d, n + pa), generator=g, device=DEV).to(dtype)
+    Abuf = torch.randn((d + 70, n + pa), generator=g, device=DEV).to(dtype)
+    Abuf[d:] = float("nan")         # nor may memory past the last row (a partly filled last block reads zeros)
     if pa:
         Abuf[:, n:] = float("nan")  # the padding between n and lda must never reach the result
-    A = Abuf[:, :n]
+    A = Abuf[:d, :n]
     obuf = torch.full((k, n + po), float("nan"), device=DEV, dtype=dtype)
     sk = make_sketch(params, seed, variant)
     apply_or_skip(sk, A, obuf[:, :n])
@@ -543,10 +550,11 @@ def test_apply_rows_matches_oracle(case, dtype, variant):
     print("rows", params, n, dtype, VNAME[variant], flush=True)
     d, k = params[0], params[1]
     g = torch.Generator(device=DEV).manual_seed(n + k)
-    Gbuf = torch.randn((n, d + pg), generator=g, device=DEV).to(dtype)
+    Gbuf = torch.randn((n + 3, d + pg), generator=g, device=DEV).to(dtype)
+    Gbuf[n:] = float("nan")         # memory past the last example must never reach the result
     if pg:
         Gbuf[:, d:] = float("nan")
-    G = Gbuf[:, :d]
+    G = Gbuf[:n, :d]
     obuf = torch.full((n, k + po), float("nan"), device=DEV, dtype=dtype)
     sk = make_sketch(params, 9, variant)
     sk.apply_rows(G, obuf[:, :k])
