@@ -62,6 +62,7 @@ struct MfmaArgs {
   int n;
   int zsplit;       // IN: row splits of an input block; OUT: splits of the kappa*Bc rows
   int group_slots;  // IN: wiring slots one work-group stacks (grid.z = zsplit * slot groups)
+  int nsub;         // OUT, Br > 128: 128-row slices of an output block (grid.y = column tiles * nsub)
   int stages;       // stages per work-group
   int out_vec;      // out rows allow 4-column vector stores
   uint32_t log2_br;
@@ -69,7 +70,9 @@ struct MfmaArgs {
 
 // PFX multiplies the depth of the register prefetch ring (1 or 2).  A ring deeper than one
 // stage (bf16, PFX = 2: 8 k-steps) needs an even number of stages, which the host checks.
-template <typename T, int MT, int NRG, int NCG, bool IN_STAT, int RUN, int CPL, int PFX = 1>
+// SUB (OUT, Br > 128): a work-group owns one 128-row slice of its output block; it walks the same
+// input blocks and keeps only the nonzeros that fall into its slice.
+template <typename T, int MT, int NRG, int NCG, bool IN_STAT, int RUN, int CPL, int PFX = 1, bool SUB = false>
 __global__ __launch_bounds__(64 * NRG * NCG * RUN) __attribute__((amdgpu_waves_per_eu(MT > 2 ? 1 : 2)))
 void mfma_kernel(MfmaArgs a) {
   using V = typename LdN<T, CPL>::V;
@@ -80,6 +83,7 @@ void mfma_kernel(MfmaArgs a) {
   constexpr int RWV = 32 * MT;                 // stacked Phi rows of one wave
   constexpr int TILE = RWV * PHI_LD;           // bf16 elements of one Phi tile
   static_assert(RUN == 1 || IN_STAT, "orbit runs are an IN-stationary mode");
+  static_assert(!SUB || (!IN_STAT && NRG == 1), "row slices are an OUT-stationary mode");
 
   // dynamic LDS: per sub-group [MAX_KAPPA] keys and blocks, then per wave two Phi tiles
   // [RWV][PHI_LD] bf16 (consume / refill: a wave makes exactly the rows it consumes, so the
@@ -110,6 +114,11 @@ void mfma_kernel(MfmaArgs a) {
     if (total % 8 == 0) id = (id % 8) * (total / 8) + id / 8;
     opos = id % gridDim.x;
     jt = id / gridDim.x;
+  }
+  uint32_t slice = 0;
+  if constexpr (SUB) {
+    slice = jt % (uint32_t)a.nsub;
+    jt /= (uint32_t)a.nsub;
   }
   const int col0 = (int)jt * (WC * NCG) + cg * WC + CPL * (lane & 31);
   // IN: input block h (RUN > 1: the block at orbit position blockIdx.x*RUN + sg); OUT: g
@@ -174,7 +183,7 @@ void mfma_kernel(MfmaArgs a) {
   // Scatter into tile `buf` the nonzeros of stage t that fall in this wave's stacked rows
   // [row_lo, row_lo + RWV): one lane per row of the stage, the wave's slots in turn.  Part
   // `part` (of KSTEPS) takes every KSTEPS-th slot so the hashing spreads over the stage.
-  const uint32_t row_lo = (uint32_t)rg * RWV;
+  const uint32_t row_lo = SUB ? slice * RWV : (uint32_t)rg * RWV;
   // `whole`: the slot lies entirely inside this wave's rows, so no nonzero is filtered out.
   auto scatter = [&](uint16_t* phi, uint32_t key, uint32_t u, uint32_t slot_row0, bool whole) {
     const RowHash rh = row_hash_pow2(key, u, p.Br);
@@ -398,7 +407,9 @@ void mfma_kernel(MfmaArgs a) {
         dst[mt] = *reinterpret_cast<const uint4*>(tile + (mt * 32 + (lane & 31)) * PHI_LD + ks * 16 + kg * 8);
     };
     auto put_one = [&](uint16_t* tile, uint32_t i, bool real) {
-      tile[real ? __umul24(pr, (uint32_t)PHI_LD) + lane : pad_at] = (uint16_t)(((prh.signs >> i) << 15) | Fmt<T>::one);
+      const uint32_t local = SUB ? pr - row_lo : pr;  // unsigned: rows below the slice wrap high
+      const bool keep = SUB ? real && local < (uint32_t)RWV : real;
+      tile[keep ? __umul24(local, (uint32_t)PHI_LD) + lane : pad_at] = (uint16_t)(((prh.signs >> i) << 15) | Fmt<T>::one);
       pr = (pr + prh.stride) & (p.Br - 1);
     };
     auto fill_part = [&](int t1, uint16_t* tile, int ks) {
@@ -612,10 +623,10 @@ void mfma_kernel(MfmaArgs a) {
           float* dst = a.ws + (plane * p.k + (int64_t)s_blk[slot] * p.Br + r) * a.ldw + colq;
           *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
         } else if (a.zsplit > 1) {  // OUT with split rows: plane z, summed by the reduce kernel
-          float* dst = a.ws + ((int64_t)z * p.k + (int64_t)blk * p.Br + row_s) * a.ldw + colq;
+          float* dst = a.ws + ((int64_t)z * p.k + (int64_t)blk * p.Br + (SUB ? row_lo : 0u) + row_s) * a.ldw + colq;
           *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
         } else {
-          T* dst = reinterpret_cast<T*>(a.out) + ((int64_t)blk * p.Br + row_s) * a.ldo + colq;
+          T* dst = reinterpret_cast<T*>(a.out) + ((int64_t)blk * p.Br + (SUB ? row_lo : 0u) + row_s) * a.ldo + colq;
 #pragma unroll
           for (int c = 0; c < 4; ++c) v[c] *= p.scale;
           if (a.out_vec && colq + 3 < a.n) {
@@ -683,6 +694,7 @@ struct Plan {
   bool in_stat = false;
   int mt = 0, nrg = 0, ncg = 0, zsplit = 1, stages = 0, run = 1, cpl = 4, pfx = 1;
   int groups = 1, group_slots = 0;  // IN: slot groups (A is read once per group)
+  int nsub = 1;                     // OUT: 128-row slices of an output block
   int64_t ldw = 0;
   int planes = 0;
   size_t lds = 0;
@@ -720,7 +732,9 @@ Plan make_plan(const SketchParams& p, const void* A, int64_t lda, int64_t n, fs_
   int mt_i = 0, nrg_i = 0, mt_o = 0, nrg_o = 0;
   // IN: the kappa*Br stacked rows sit in the smallest tile that holds them (rows above them idle)
   const uint64_t rw = (uint64_t)p.kappa * p.Br;
-  const bool can_out = tile_shape(p.Br, &mt_o, &nrg_o);
+  // OUT: blocks of 32, 64 or 128 rows, or 128-row slices of a higher (power-of-two) block
+  const int nsub = p.Br > 128 ? (int)(p.Br / 128) : 1;
+  const bool can_out = tile_shape(p.Br > 128 ? 128 : p.Br, &mt_o, &nrg_o);
   // More stacked rows than the highest tile and blocks too small for OUT: groups of 128/Br slots,
   // each a work-group of its own that reads the input block again.
   const bool grouped = rw > 128 && !can_out && p.Br < 32;
@@ -775,10 +789,11 @@ Plan make_plan(const SketchParams& p, const void* A, int64_t lda, int64_t n, fs_
     // fill the chip (small n), as long as the extra plane traffic stays below that of reading A
     const int total_stages = (int)((int64_t)p.kappa * blk_stages);
     int zo = 1;
-    while ((int64_t)p.M * col_tiles * zo < 512 && zo < 8 && total_stages % (zo * 2) == 0 &&
+    while ((int64_t)p.M * col_tiles * nsub * zo < 512 && zo < 8 && total_stages % (zo * 2) == 0 &&
            2.0 * (zo * 2) * (double)p.k * 4.0 / ((double)p.d * esz) <= 1.0)
       zo *= 2;
-    pl.mt = mt_o; pl.nrg = nrg_o; pl.zsplit = zo;
+    pl.mt = mt_o; pl.nrg = nrg_o; pl.zsplit = zo; pl.nsub = nsub;
+    if (col_tiles * nsub > 65535) return pl;
     pl.stages = total_stages / zo;
     if (zo > 1) { pl.ldw = (n + 3) & ~(int64_t)3; pl.planes = zo; }
   }
@@ -811,6 +826,15 @@ hipError_t launch_shape(const Plan& pl, const MfmaArgs& a, dim3 grid, hipStream_
   return go(mfma_kernel<T, MT, NRG, NCG, IN_STAT, RUN, 4>, grid, 64 * NRG * NCG * RUN, pl.lds, st, a)
 #define FS_GO4(NCG)                                                                            \
   do {                                                                                         \
+    if constexpr (!IN_STAT) {                                                                  \
+      if (pl.nsub > 1) {                                                                       \
+        if constexpr (sizeof(T) == 2) {                                                        \
+          if (pl.pfx == 2)                                                                     \
+            return go(mfma_kernel<T, 4, 1, NCG, false, 1, 4, 2, true>, grid, 64 * NCG, pl.lds, st, a); \
+        }                                                                                      \
+        return go(mfma_kernel<T, 4, 1, NCG, false, 1, 4, 1, true>, grid, 64 * NCG, pl.lds, st, a);     \
+      }                                                                                        \
+    }                                                                                          \
     if constexpr (sizeof(T) == 2) {                                                            \
       if (pl.pfx == 2)                                                                         \
         return go(mfma_kernel<T, 4, 1, NCG, IN_STAT, 1, 4, 2>, grid, 64 * NCG, pl.lds, st, a); \
@@ -862,12 +886,13 @@ hipError_t launch_mfma(const SketchParams& p, const void* A, int64_t lda, int64_
   a.lda = lda; a.ldo = ldo; a.ldw = pl.ldw; a.n = (int)n;
   a.zsplit = pl.zsplit; a.stages = pl.stages;
   a.group_slots = pl.in_stat ? pl.group_slots : (int)p.kappa;
+  a.nsub = pl.nsub;
   a.out_vec = ((uintptr_t)out % (4 * esz) == 0 && (ldo * esz) % (4 * esz) == 0) ? 1 : 0;
   a.log2_br = 0;
   while ((1u << a.log2_br) < p.Br) ++a.log2_br;
   const int tnw = 32 * pl.cpl * pl.ncg;
   const unsigned col_tiles = (unsigned)((n + tnw - 1) / tnw);
-  dim3 grid(p.M / pl.run, col_tiles, pl.zsplit * pl.groups);
+  dim3 grid(p.M / pl.run, col_tiles * pl.nsub, pl.zsplit * pl.groups);
 
   if (ev.start) (void)hipEventRecord(ev.start, st);
   hipError_t e;

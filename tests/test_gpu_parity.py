@@ -135,6 +135,10 @@ SMALL = [
     ((640, 128, 40, 8, 4, 2), 130, 2, 0),           # Bc = 40: less than one stage
     ((1990, 128, 250, 16, 8, 2), 64, 0, 0),         # Bc = 250 and a partly filled last block
     ((73728, 8192, 72, 8, 8, 2), 256, 0, 0),        # Bc = 72, orbit runs
+    # output blocks higher than the 128-row tile: 128-row slices
+    ((4096, 1024, 1024, 256, 2, 8), 300, 0, 0),     # Br = 256
+    ((8192, 4096, 1024, 512, 3, 32), 130, 2, 0),    # Br = 512, s = 32
+    ((2048, 2048, 1024, 1024, 2, 16), 64, 0, 4),    # Br = 1024, M = 2: split stages as well
 ]
 
 
