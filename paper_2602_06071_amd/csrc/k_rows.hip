@@ -23,8 +23,9 @@
 //  * fp32 inputs: exact three-way bf16 split of the 8 values a lane holds, three MFMAs;
 //  * the prefetch ring holds whole example tiles (all lines of a tile are requested together).
 //
-// Shapes: power-of-two Br with kappa*Br <= 128 (tile height 32, 64 or 128; rows above kappa*Br idle), Bc a multiple of 64 that divides d,
-// 16-byte aligned rows.  Inputs must be finite (a dense product also multiplies by the zeros).
+// Shapes: power-of-two Br (kappa*Br <= 128: tile height 32, 64 or 128, rows above kappa*Br idle;
+// more: Br < 32 in groups of wiring slots, Br in {32, 64, 128} output-stationary), Bc a multiple
+// of 64, 16-byte aligned rows.  Inputs must be finite (a dense product also multiplies by the zeros).
 #include <type_traits>
 
 #include "handle.h"
@@ -134,7 +135,10 @@ void rows_kernel(RowsArgs a) {
   const int64_t row_bytes = a.ldg * (int64_t)sizeof(T);
   const int rows_valid = min(32 * ET, a.n - ex0);
   const int64_t range =
-      rows_valid > 0 ? (int64_t)(rows_valid - 1) * row_bytes + p.d * (int64_t)sizeof(T) : 0;
+      // (the last row's end rounded up to a dword: range checks are per dword, and the dword that
+      // holds entry d-1 must not count as outside; its other half lies in the same aligned word,
+      // hence in mapped memory, and is cleared with the rest of the tail)
+      rows_valid > 0 ? (int64_t)(rows_valid - 1) * row_bytes + ((p.d * (int64_t)sizeof(T) + 3) & ~(int64_t)3) : 0;
   const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<char*>(reinterpret_cast<const char*>(a.G) + (int64_t)ex0 * row_bytes), 0,
       (int)(uint32_t)range, 0x00020000);
@@ -212,8 +216,17 @@ void rows_kernel(RowsArgs a) {
   // One stage.  All Phi^T operands of the stage are read into registers first; LDS operations
   // of a wave complete in order, so the one tile can be cleared and refilled for the next stage
   // right behind those reads.
+  // Entries of a vector at or beyond d (the zero padding of a partly filled last input block) are
+  // whatever follows in memory: the row's own padding or the next example.  They are cleared in
+  // registers, in the few stages that reach that far.
+  const int d_bytes = (int)(p.d * (int64_t)sizeof(T));
+  auto dword_mask = [](int rem) -> uint32_t {  // rem = valid bytes from this dword on
+    return rem >= 4 ? 0xFFFFFFFFu : rem >= 2 ? 0x0000FFFFu : 0u;
+  };
   auto stage = [&](int t, auto last_tag) {
     constexpr bool LAST = decltype(last_tag)::value;
+    const int tail_bytes = d_bytes - (int)kb_c;  // bytes of this stage's K-range that lie before entry d
+    const bool tail = tail_bytes < ROWB;
     uint4 pb[KSTEPS][MT];  // stacked row rt*32 + m, the K-values of (k-step j, half kg)
 #pragma unroll
     for (int j = 0; j < KSTEPS; ++j)
@@ -229,6 +242,17 @@ void rows_kernel(RowsArgs a) {
         for (int part = c * KSTEPS / ET; part < (c + 1) * KSTEPS / ET; ++part) produce(t + 1, part);
       }
       uint4(&cur)[NLD] = ld[c % R];
+      if (tail) {  // wave-uniform: only the stages of a partly filled last block that reach entry d
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) {
+          // bytes of this 16-byte piece that lie before entry d (<= 0: none, >= 16: all)
+          const int vb = tail_bytes - (STAGED ? (lane % LPR) * 16 : kg * 32 * (int)sizeof(T) + i * 16);
+          cur[i].x &= dword_mask(vb);
+          cur[i].y &= dword_mask(vb - 4);
+          cur[i].z &= dword_mask(vb - 8);
+          cur[i].w &= dword_mask(vb - 12);
+        }
+      }
       uint4 g[NLD];  // operand pieces: k-step j is g[j*NV .. j*NV + NV)
       if constexpr (STAGED) {
 #pragma unroll
@@ -390,7 +414,7 @@ struct RowsPlan {
 RowsPlan make_rows_plan(const SketchParams& p, const void* G, int64_t ldg, int64_t n, fs_dtype dt) {
   RowsPlan pl;
   const size_t esz = dt == FS_F32 ? 4 : 2;
-  if (!p.br_pow2 || p.Bc % KC || p.d % p.Bc || p.kappa > (uint32_t)MAX_KAPPA || n < 1) return pl;
+  if (!p.br_pow2 || p.Bc % KC || p.kappa > (uint32_t)MAX_KAPPA || n < 1) return pl;
   const uint64_t rw = (uint64_t)p.kappa * p.Br;
   const bool br_tile = p.Br == 32 || p.Br == 64 || p.Br == 128;
   if (p.kappa == 1 && br_tile) {  // nothing is re-read: output-stationary stores the result directly

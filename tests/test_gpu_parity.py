@@ -538,9 +538,13 @@ ROWS = [
     ((8192, 2048, 64, 16, 16, 2), 33, 0, 0),        # 256 rows: two full groups
     ((2048, 256, 64, 8, 20, 2), 130, 0, 0),         # 160 rows: a full group and one of 4 slots
     ((4096, 256, 64, 4, 40, 3), 70, 8, 4),          # Br = 4: groups of 32 slots
+    # d not a multiple of Bc: the entries of the last block at or beyond d are cleared in registers
+    ((4000, 256, 512, 32, 2, 4), 130, 0, 0),        # 416 of 512 entries, input-stationary
+    ((4001, 256, 512, 32, 2, 4), 70, 7, 0),         # odd d: the cut falls inside a dword (16-bit types)
+    ((7000, 448, 1024, 64, 4, 8), 100, 0, 4),       # output-stationary, M = 7, whole stages beyond d
     # shapes only the general kernel takes
     ((1152, 72, 96, 6, 5, 3), 70, 1, 3),            # Br = 6, M = 12, odd row stride
-    ((4000, 256, 512, 32, 2, 4), 130, 0, 0),        # last input block partly filled
+    ((4000, 256, 500, 32, 2, 4), 130, 0, 0),        # Bc = 500: not whole 64-entry stages
     ((1440, 180, 80, 10, 18, 10), 5, 0, 0),         # kappa = M, s = Br = 10
     ((4096, 1024, 1024, 256, 2, 8), 129, 0, 0),     # Br = 256: two row passes per block at 128 examples a tile
 ]
