@@ -481,6 +481,8 @@ def test_apply_on_a_side_stream_and_profile_brackets():
     ((32768, 64, 4096, 8, 8, 2), 1024, 256),     # IN-stationary with partial planes + reduce kernel
     ((65536, 8192, 64, 8, 8, 2), 512, 256),      # orbit-run mode
     ((8192, 1024, 512, 64, 4, 8), 512, 512),     # OUT-stationary, direct store
+    ((8192, 2048, 64, 16, 16, 2), 512, 256),     # slot groups
+    ((4096, 1024, 1024, 256, 2, 8), 512, 256),   # 128-row slices of a 256-row block, split stages
 ])
 def test_chunked_apply_replays_from_a_hip_graph(params, n, chunk):
     """The apply only enqueues kernels once a handle has run once (workspace and orbit table
@@ -511,6 +513,39 @@ def test_chunked_apply_replays_from_a_hip_graph(params, n, chunk):
         assert torch.equal(scratch, eager[:, :chunk])
     ref = O.apply(oracle_csc(params, 2), host64(A))
     check(out, ref, torch.bfloat16, "graph replay")
+
+
+@pytest.mark.parametrize("params,n,chunk", [
+    ((32768, 64, 4096, 8, 8, 2), 512, 256),      # input-stationary: partial records + gather reduction
+    ((8192, 1024, 512, 64, 4, 8), 256, 128),     # output-stationary
+    ((1152, 72, 96, 6, 5, 3), 140, 70),          # general kernel
+])
+def test_chunked_apply_rows_replays_from_a_hip_graph(params, n, chunk):
+    """The same for the examples-as-rows entry point."""
+    print("graph rows", params, flush=True)
+    d, k = params[0], params[1]
+    g = torch.Generator(device=DEV).manual_seed(12)
+    G = torch.randn((n, d), generator=g, device=DEV).to(torch.bfloat16)
+    sk = B.Sketch(*params, seed=2)
+    eager = torch.empty((n, k), device=DEV, dtype=G.dtype)
+    for c in range(0, n, chunk):
+        sk.apply_rows(G[c:c + chunk], eager[c:c + chunk])
+    torch.cuda.synchronize()
+    out = torch.zeros_like(eager)
+    graph = torch.cuda.CUDAGraph()
+    gc.collect()
+    with torch.cuda.graph(graph):
+        for c in range(0, n, chunk):
+            sk.apply_rows(G[c:c + chunk], out[c:c + chunk])
+    for rep in range(3):
+        out.zero_()
+        scratch = sk.apply_rows(G[:chunk])
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), f"replay {rep} differs from the eager result"
+        assert torch.equal(scratch, eager[:chunk])
+    check(out, O.apply_rows(oracle_csc(params, 2), host64(G)), torch.bfloat16, "graph replay, rows")
 
 
 # ------------------------------------------ examples-as-rows layout -------
