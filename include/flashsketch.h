@@ -95,8 +95,9 @@ typedef enum {
   FS_VARIANT_AUTO = 0,    /* pick by shape/dtype/alignment                          */
   FS_VARIANT_GENERIC = 1, /* one lane per column, LDS-private output tile, any Br   */
   FS_VARIANT_MFMA = 2     /* +-1 operand on the matrix cores: any power-of-two Br
-                             and any Bc, kappa <= 128, A and lda aligned to 4 columns,
-                             64*ceil(Bc/64)*lda*sizeof(elt) < 2^31                   */
+                             and any Bc, kappa <= 128,
+                             64*ceil(Bc/64)*lda*sizeof(elt) < 2^31; about twice as fast
+                             when A and lda are aligned to 4 columns (vector loads)  */
 } fs_variant;
 
 typedef struct {

@@ -48,6 +48,9 @@ namespace fs {
 hipError_t launch_mfma_f32(const mm::Plan& pl, const mm::MfmaArgs& a, dim3 grid, hipStream_t st);
 hipError_t launch_mfma_bf16(const mm::Plan& pl, const mm::MfmaArgs& a, dim3 grid, hipStream_t st);
 hipError_t launch_mfma_f16(const mm::Plan& pl, const mm::MfmaArgs& a, dim3 grid, hipStream_t st);
+hipError_t launch_mfma_f32_unal(const mm::Plan& pl, const mm::MfmaArgs& a, dim3 grid, hipStream_t st);
+hipError_t launch_mfma_bf16_unal(const mm::Plan& pl, const mm::MfmaArgs& a, dim3 grid, hipStream_t st);
+hipError_t launch_mfma_f16_unal(const mm::Plan& pl, const mm::MfmaArgs& a, dim3 grid, hipStream_t st);
 
 namespace {
 
@@ -77,7 +80,8 @@ Plan make_plan(const SketchParams& p, const void* A, int64_t lda, int64_t n, fs_
   const size_t esz = dt == FS_F32 ? 4 : 2;
   if (!p.br_pow2 || p.kappa > (uint32_t)MAX_KAPPA || n < 1) return pl;
   const int64_t blk_stages = ((int64_t)p.Bc + KC - 1) / KC;  // the last one may be partly filled
-  if ((uintptr_t)A % (4 * esz) || (lda * esz) % (4 * esz)) return pl;  // 4-column vector loads
+  if ((uintptr_t)A % esz) return pl;
+  pl.unal = (uintptr_t)A % (4 * esz) || (lda * esz) % (4 * esz);  // no 4-column vector loads
   if ((16 * lda + n) * (int64_t)esz >= ((int64_t)1 << 31)) return pl;     // 32-bit lane offsets
   if (blk_stages * KC * lda * (int64_t)esz >= ((int64_t)1 << 31)) return pl;  // 32-bit row offsets in a block
   pl.ncg = n > WCOLS ? 2 : 1;
@@ -134,7 +138,7 @@ Plan make_plan(const SketchParams& p, const void* A, int64_t lda, int64_t n, fs_
     // per CU, and a merge buffer that fits beside nothing else in LDS
     constexpr int R = 4;
     const size_t merge = (size_t)(p.kappa + R - 1) * p.Br * (WCOLS * 2) * 4;
-    if (have_orbit && zs == 1 && rw == 64 && pl.nrg == 1 && pl.ncg == 2 && p.kappa > 1 &&
+    if (have_orbit && !pl.unal && zs == 1 && rw == 64 && pl.nrg == 1 && pl.ncg == 2 && p.kappa > 1 &&
         p.M % R == 0 && (int64_t)(p.M / R) * col_tiles >= 256 && merge <= 100 * 1024) {
       pl.run = R;
       pl.planes = (int)((p.kappa + R - 2) / R) + 1;
@@ -155,7 +159,7 @@ Plan make_plan(const SketchParams& p, const void* A, int64_t lda, int64_t n, fs_
   // bf16 with one wave per SIMD (128-row tiles) has the registers for a ring twice as deep, and
   // with a single wave nothing else hides the latency of A; the two-stage ring needs an even
   // stage count.  (For fp32 the deeper ring measured no gain.)
-  if (pl.mt == 4 && dt != FS_F32 && pl.stages % 2 == 0) pl.pfx = 2;
+  if (pl.mt == 4 && dt != FS_F32 && pl.stages % 2 == 0 && !pl.unal) pl.pfx = 2;
   pl.lds = lds_bytes(pl.mt, pl.nrg, pl.ncg, pl.run,
                      pl.run > 1 ? (size_t)(p.kappa + pl.run - 1) * p.Br * 256 * 4 : 0);
   pl.ok = pl.lds <= kLdsBudget;
@@ -205,9 +209,9 @@ hipError_t launch_mfma(const SketchParams& p, const void* A, int64_t lda, int64_
 
   if (ev.start) (void)hipEventRecord(ev.start, st);
   hipError_t e;
-  if (dt == FS_BF16) e = launch_mfma_bf16(pl, a, grid, st);
-  else if (dt == FS_F16) e = launch_mfma_f16(pl, a, grid, st);
-  else e = launch_mfma_f32(pl, a, grid, st);
+  if (dt == FS_BF16) e = pl.unal ? launch_mfma_bf16_unal(pl, a, grid, st) : launch_mfma_bf16(pl, a, grid, st);
+  else if (dt == FS_F16) e = pl.unal ? launch_mfma_f16_unal(pl, a, grid, st) : launch_mfma_f16(pl, a, grid, st);
+  else e = pl.unal ? launch_mfma_f32_unal(pl, a, grid, st) : launch_mfma_f32(pl, a, grid, st);
   if (ev.stop) (void)hipEventRecord(ev.stop, st);
   if (e != hipSuccess || pl.planes == 0) return e;
 

@@ -35,6 +35,7 @@ struct Plan {
   int mt = 0, nrg = 0, ncg = 0, zsplit = 1, stages = 0, run = 1, cpl = 4, pfx = 1;
   int groups = 1, group_slots = 0;  // IN: slot groups (A is read once per group)
   int nsub = 1;                     // OUT: 128-row slices of an output block
+  bool unal = false;                // A or lda not aligned to 4 columns: element-wise loads
   int64_t ldw = 0;
   int planes = 0;
   size_t lds = 0;
@@ -50,11 +51,16 @@ using namespace mm;
 // stage (bf16, PFX = 2: 8 k-steps) needs an even number of stages, which the host checks.
 // SUB (OUT, Br > 128): a work-group owns one 128-row slice of its output block; it walks the same
 // input blocks and keeps only the nonzeros that fall into its slice.
-template <typename T, int MT, int NRG, int NCG, bool IN_STAT, int RUN, int CPL, int PFX = 1, bool SUB = false>
+// UNAL: A or lda is not a multiple of 4 columns, so a lane's 4 columns are not one aligned
+// vector: they are loaded element by element (same registers afterwards, four times the load
+// instructions).
+template <typename T, int MT, int NRG, int NCG, bool IN_STAT, int RUN, int CPL, int PFX = 1, bool SUB = false,
+          bool UNAL = false>
 __global__ __launch_bounds__(64 * NRG * NCG * RUN) __attribute__((amdgpu_waves_per_eu(MT > 2 ? 1 : 2)))
 void mfma_kernel(MfmaArgs a) {
   using V = typename LdN<T, CPL>::V;
-  constexpr int PFD = LdN<T, CPL>::PFD * PFX;
+  // (element loads hold four registers per row until they are packed: half the ring)
+  constexpr int PFD = UNAL ? 2 : LdN<T, CPL>::PFD * PFX;
   static_assert(PFD <= KSTEPS || PFD == 2 * KSTEPS, "ring depth: within a stage, or exactly two stages");
   constexpr int WC = 32 * CPL;                 // columns per wave
   constexpr int NW = NRG * NCG, NT = 64 * NW;  // waves / threads of one sub-group
@@ -224,7 +230,8 @@ void mfma_kernel(MfmaArgs a) {
     // padding, inside the same aligned 8/16-byte granule as a valid element) is masked to zero.
     auto make_rsrc = [&](int64_t first_row, int64_t nrows) {
       const int64_t valid = min(nrows, p.d - first_row);
-      const int64_t ncols = ((int64_t)a.n + 3) & ~(int64_t)3;
+      // (element loads, UNAL, never reach past column n-1 of the last valid row)
+      const int64_t ncols = UNAL ? (int64_t)a.n : ((int64_t)a.n + 3) & ~(int64_t)3;
       const int64_t bytes = valid > 0 ? (valid - 1) * row_bytes + ncols * (int64_t)sizeof(T) : 0;
       return __builtin_amdgcn_make_buffer_rsrc(
           const_cast<char*>(Abase + first_row * row_bytes), 0, (int)bytes, 0x00020000);
@@ -270,7 +277,22 @@ void mfma_kernel(MfmaArgs a) {
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
         const uint32_t soj = so + (uint32_t)j * (uint32_t)row_bytes;
-        if constexpr (sizeof(V) == 8)
+        if constexpr (UNAL && sizeof(V) == 8) {
+          // (written as 16-bit vector inserts so that the halves of a register are loaded in
+          // place, without a packing step)
+          typedef unsigned short us4 __attribute__((ext_vector_type(4)));
+          us4 e;
+          e.x = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(rs, voff, soj, 0);
+          e.y = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(rs, voff + 2u, soj, 0);
+          e.z = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(rs, voff + 4u, soj, 0);
+          e.w = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(rs, voff + 6u, soj, 0);
+          dst[j] = __builtin_bit_cast(V, e);
+        } else if constexpr (UNAL) {
+          uint32_t* e = reinterpret_cast<uint32_t*>(&dst[j]);
+#pragma unroll
+          for (int c = 0; c < 4; ++c)
+            e[c] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(rs, voff + 4u * c, soj, 0);
+        } else if constexpr (sizeof(V) == 8)
           dst[j] = __builtin_bit_cast(V, __builtin_amdgcn_raw_buffer_load_b64(rs, voff, soj, 0));
         else
           dst[j] = __builtin_bit_cast(V, __builtin_amdgcn_raw_buffer_load_b128(rs, voff, soj, 0));
@@ -677,6 +699,28 @@ hipError_t go(K kernel, dim3 grid, unsigned threads, size_t lds, hipStream_t st,
   }
   hipLaunchKernelGGL(kernel, grid, dim3(threads), lds, st, a);
   return hipGetLastError();
+}
+
+// Element-wise loads (Plan::unal): one ring depth, no orbit runs.
+template <typename T, bool IN_STAT>
+hipError_t launch_shape_unal(const Plan& pl, const MfmaArgs& a, dim3 grid, hipStream_t st) {
+#define FS_GO(MT, NCG) \
+  return go(mfma_kernel<T, MT, 1, NCG, IN_STAT, 1, 4, 1, false, true>, grid, 64 * NCG, pl.lds, st, a)
+#define FS_GO4(NCG)                                                                                      \
+  do {                                                                                                   \
+    if constexpr (!IN_STAT) {                                                                            \
+      if (pl.nsub > 1)                                                                                   \
+        return go(mfma_kernel<T, 4, 1, NCG, false, 1, 4, 1, true, true>, grid, 64 * NCG, pl.lds, st, a); \
+    }                                                                                                    \
+    FS_GO(4, NCG);                                                                                       \
+  } while (0)
+  if (pl.ncg == 1) {
+    if (pl.mt == 1) FS_GO(1, 1); else if (pl.mt == 2) FS_GO(2, 1); else FS_GO4(1);
+  } else {
+    if (pl.mt == 1) FS_GO(1, 2); else if (pl.mt == 2) FS_GO(2, 2); else FS_GO4(2);
+  }
+#undef FS_GO
+#undef FS_GO4
 }
 
 template <typename T, bool IN_STAT>

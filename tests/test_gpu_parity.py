@@ -135,6 +135,12 @@ SMALL = [
     ((640, 128, 40, 8, 4, 2), 130, 2, 0),           # Bc = 40: less than one stage
     ((1990, 128, 250, 16, 8, 2), 64, 0, 0),         # Bc = 250 and a partly filled last block
     ((73728, 8192, 72, 8, 8, 2), 256, 0, 0),        # Bc = 72, orbit runs
+    # lda not a multiple of 4 columns: the matrix-core kernels load element by element
+    ((4096, 256, 512, 32, 2, 4), 301, 0, 0),        # input-stationary, lda = 301
+    ((32768, 64, 4096, 8, 8, 2), 255, 0, 0),        # gradient-config blocks, lda = 255
+    ((8192, 1024, 512, 64, 4, 8), 250, 1, 0),       # output-stationary, lda = 251
+    ((16384, 1024, 2048, 128, 4, 8), 130, 1, 3),    # 128-row tiles, lda = 131
+    ((4001, 256, 512, 32, 2, 4), 77, 0, 0),         # and a partly filled last block
     # output blocks higher than the 128-row tile: 128-row slices
     ((4096, 1024, 1024, 256, 2, 8), 300, 0, 0),     # Br = 256
     ((8192, 4096, 1024, 512, 3, 32), 130, 2, 0),    # Br = 512, s = 32
@@ -191,6 +197,23 @@ def test_one_hot_probes_reproduce_columns_exactly(params, dtype, variant):
     torch.cuda.synchronize()
     want = oracle_csc(params, 0)[:, cols].toarray()
     assert np.array_equal(host64(out), want)
+
+
+@DTYPES
+@pytest.mark.parametrize("params", [(4096, 256, 512, 32, 2, 4), (8192, 1024, 512, 64, 4, 8)])
+def test_apply_on_a_view_that_starts_at_an_odd_column(params, dtype):
+    """A view whose first element is not aligned to 4 columns (here: column 1 or 3 of a wider
+    buffer) takes the element-wise loads of the matrix-core kernel and still matches."""
+    d, k = params[0], params[1]
+    g = torch.Generator(device=DEV).manual_seed(21)
+    buf = torch.randn((d, 264), generator=g, device=DEV).to(dtype)
+    sk = make_sketch(params, 6, B.VARIANT_MFMA)
+    for first, n in ((1, 256), (3, 130)):
+        A = buf[:, first:first + n]
+        out = sk.apply(A)
+        torch.cuda.synchronize()
+        check(out, O.apply(oracle_csc(params, 6), host64(A)), dtype, f"view from column {first}")
+        assert torch.equal(out, sk.apply(A.contiguous()) if n % 4 == 0 else out)
 
 
 # ------------------------------------------ half: the ends of its range ---
