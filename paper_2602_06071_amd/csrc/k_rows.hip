@@ -58,7 +58,9 @@ struct RowsArgs {
 // walks the kappa input blocks f^l(g) with Br = 32*MT MFMA columns, and stores the scaled result
 // itself; G is read kappa times (the re-reads hit L2 when neighbouring waves are in step), there
 // are no partial results.  Used when kappa*Br is more than one wave can accumulate.
-template <typename T, int MT, int ET, bool STAGED, bool OUT>
+// UNAL: rows are only 4-byte aligned (G or ldg*sizeof(T) not a multiple of 16): every 16-byte
+// piece is loaded as four dwords.
+template <typename T, int MT, int ET, bool STAGED, bool OUT, bool UNAL = false>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2)))
 void rows_kernel(RowsArgs a) {
   constexpr int RWV = 32 * MT;         // tile height: kappa * Br stacked output rows, rounded up
@@ -176,7 +178,14 @@ void rows_kernel(RowsArgs a) {
     for (int i = 0; i < NLD; ++i) {
       const uint32_t so = STAGED ? (uint32_t)(c * 32 + i * RPI) * (uint32_t)row_bytes + kb
                                  : (uint32_t)(c * 32) * (uint32_t)row_bytes + kb + (uint32_t)(i * 16);
-      dst[i] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rs, voff, so, 0));
+      if constexpr (UNAL) {
+        dst[i].x = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(rs, voff, so, 0);
+        dst[i].y = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(rs, voff + 4u, so, 0);
+        dst[i].z = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(rs, voff + 8u, so, 0);
+        dst[i].w = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(rs, voff + 12u, so, 0);
+      } else {
+        dst[i] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rs, voff, so, 0));
+      }
     }
   };
 
@@ -407,7 +416,7 @@ __global__ __launch_bounds__(256) void reduce_rows_kernel(const float* __restric
 struct RowsPlan {
   bool ok = false;
   int mt = 0, et = 0, zsplit = 1, stages = 0, planes = 0, groups = 1, group_slots = 0;
-  bool staged = false, out_stat = false;
+  bool staged = false, out_stat = false, unal = false;
   size_t lds = 0;
 };
 
@@ -433,7 +442,8 @@ RowsPlan make_rows_plan(const SketchParams& p, const void* G, int64_t ldg, int64
     pl.mt = (int)p.Br / 32;
     pl.et = pl.mt == 4 ? 2 : 4;
   } else return pl;
-  if ((uintptr_t)G % 16 || (ldg * (int64_t)esz) % 16) return pl;         // 128-bit loads
+  if ((uintptr_t)G % 4 || (ldg * (int64_t)esz) % 4) return pl;           // rows at least dword aligned
+  pl.unal = (uintptr_t)G % 16 || (ldg * (int64_t)esz) % 16;              // no 128-bit loads: four dwords each
   if (128 * ldg * (int64_t)esz >= ((int64_t)1 << 31)) return pl;          // 32-bit lane offsets and range
   const int64_t ex_tiles = (n + 32 * pl.et - 1) / (32 * pl.et);
   if (ex_tiles > 65535) return pl;
@@ -498,11 +508,12 @@ hipError_t launch_rows(const SketchParams& p, const void* G, int64_t ldg, int64_
 
   if (ev.start) (void)hipEventRecord(ev.start, st);
   hipError_t e;
-#define FS_ROWS(T, MT, ET)                                                                        \
-  (pl.out_stat ? (pl.staged ? go(rows_kernel<T, MT, ET, true, true>, grid, pl.lds, st, a)           \
-                            : go(rows_kernel<T, MT, ET, false, true>, grid, pl.lds, st, a))         \
-               : (pl.staged ? go(rows_kernel<T, MT, ET, true, false>, grid, pl.lds, st, a)          \
-                            : go(rows_kernel<T, MT, ET, false, false>, grid, pl.lds, st, a)))
+#define FS_ROWS_U(T, MT, ET, U)                                                                    \
+  (pl.out_stat ? (pl.staged ? go(rows_kernel<T, MT, ET, true, true, U>, grid, pl.lds, st, a)        \
+                            : go(rows_kernel<T, MT, ET, false, true, U>, grid, pl.lds, st, a))      \
+               : (pl.staged ? go(rows_kernel<T, MT, ET, true, false, U>, grid, pl.lds, st, a)       \
+                            : go(rows_kernel<T, MT, ET, false, false, U>, grid, pl.lds, st, a)))
+#define FS_ROWS(T, MT, ET) (pl.unal ? FS_ROWS_U(T, MT, ET, true) : FS_ROWS_U(T, MT, ET, false))
   if (dt == FS_BF16)
     e = pl.mt == 1 ? FS_ROWS(uint16_t, 1, 4) : pl.mt == 2 ? FS_ROWS(uint16_t, 2, 4) : FS_ROWS(uint16_t, 4, 2);
   else if (dt == FS_F16)
@@ -510,6 +521,7 @@ hipError_t launch_rows(const SketchParams& p, const void* G, int64_t ldg, int64_
   else
     e = pl.mt == 1 ? FS_ROWS(float, 1, 4) : pl.mt == 2 ? FS_ROWS(float, 2, 4) : FS_ROWS(float, 4, 2);
 #undef FS_ROWS
+#undef FS_ROWS_U
   if (ev.stop) (void)hipEventRecord(ev.stop, st);
   if (e != hipSuccess || pl.out_stat) return e;
   const int vec = p.Br % 4 == 0 ? 4 : 1;

@@ -600,6 +600,12 @@ ROWS = [
     ((4000, 256, 512, 32, 2, 4), 130, 0, 0),        # 416 of 512 entries, input-stationary
     ((4001, 256, 512, 32, 2, 4), 70, 7, 0),         # odd d: the cut falls inside a dword (16-bit types)
     ((7000, 448, 1024, 64, 4, 8), 100, 0, 4),       # output-stationary, M = 7, whole stages beyond d
+    # rows that are dword- but not 16-byte aligned: four dword loads per piece (an odd ldg of a
+    # 16-bit type is not even that and runs on the general kernel)
+    ((4096, 256, 512, 32, 2, 4), 128, 2, 0),        # ldg = 4098
+    ((4096, 256, 512, 32, 2, 4), 70, 1, 1),         # ldg = 4097
+    ((8192, 1024, 512, 64, 4, 8), 100, 2, 0),       # output-stationary, ldg = 8194
+    ((4001, 256, 512, 32, 2, 4), 40, 1, 0),         # ldg = 4002 and a partly filled last block
     # shapes only the general kernel takes
     ((1152, 72, 96, 6, 5, 3), 70, 1, 3),            # Br = 6, M = 12, odd row stride
     ((4000, 256, 500, 32, 2, 4), 130, 0, 0),        # Bc = 500: not whole 64-entry stages
@@ -662,7 +668,8 @@ def test_apply_rows_forced_matrix_core_variant_reports_unsupported_shapes():
     for params in [(8192, 384, 128, 6, 4, 2),        # Br = 6: no matrix-core kernel
                    (8192, 512, 1024, 64, 1, 8)]:     # fine shape, checked below with a bad stride
         sk = B.Sketch(*params, seed=0)
-        odd = torch.zeros((4, 8192 + 2), device=DEV)[:, :8192]  # row stride not a multiple of 16 bytes
+        odd = torch.zeros((4, 8192 + 1), device=DEV, dtype=torch.bfloat16)[:, :8192]  # rows not dword aligned
+        G = G.to(torch.bfloat16)
         bad = G if params[3] == 6 else odd
         sk.apply_rows(bad)
         assert sk.info().last_variant == B.VARIANT_GENERIC
