@@ -52,26 +52,26 @@ struct RowsArgs {
   uint32_t log2_br;
 };
 
-// STAGED: G goes through the wave's LDS transposition tile (coalesced loads); otherwise the
-// operands are loaded in MFMA lane order.
 // OUT: output-stationary instead (Alg. 1's order): the wave owns output block g for its examples,
 // walks the kappa input blocks f^l(g) with Br = 32*MT MFMA columns, and stores the scaled result
 // itself; G is read kappa times (the re-reads hit L2 when neighbouring waves are in step), there
 // are no partial results.  Used when kappa*Br is more than one wave can accumulate.
+// fp32 with 64 or 128 stacked rows gets the whole register file of a SIMD (one wave): with two
+// waves the accumulators and the split operands spill.
 // UNAL: rows are only 4-byte aligned (G or ldg*sizeof(T) not a multiple of 16): every 16-byte
 // piece is loaded as four dwords.
-template <typename T, int MT, int ET, bool STAGED, bool OUT, bool UNAL = false>
-__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2)))
+template <typename T, int MT, int ET, bool OUT, bool UNAL = false>
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(sizeof(T) == 4 && MT >= 2 ? 1 : 2)))
 void rows_kernel(RowsArgs a) {
   constexpr int RWV = 32 * MT;         // tile height: kappa * Br stacked output rows, rounded up
   constexpr int TILE = RWV * PHI_LD;   // bf16 elements of the Phi tile
   constexpr int ROWB = KC * (int)sizeof(T);   // bytes of a row per stage: 128 / 256
   constexpr int GLD = ROWB + 16;              // LDS row of the transposition tile (conflict-free b128)
-  constexpr int LPR = ROWB / 16;              // STAGED: lanes per row: 8 / 16
-  constexpr int RPI = 64 / LPR;               //         rows per load instruction: 8 / 4
+  constexpr int LPR = ROWB / 16;              // lanes per row: 8 / 16
+  constexpr int RPI = 64 / LPR;               // rows per load instruction: 8 / 4
   constexpr int NLD = 32 / RPI;               // 16-byte loads per lane and 32-example tile: 4 / 8
   constexpr int NV = (int)sizeof(T) / 2;      // 16-byte loads per k-step operand: 1 / 2
-  static_assert(NLD == KSTEPS * NV, "both load orders move the same registers");
+  static_assert(NLD == KSTEPS * NV, "what a lane loads of a tile is what it uses as operands of a stage");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const SketchParams& p = a.p;
   const int lane = (int)threadIdx.x;
@@ -79,7 +79,7 @@ void rows_kernel(RowsArgs a) {
   uint32_t* s_bk = reinterpret_cast<uint32_t*>(smem);   // [MAX_KAPPA] block keys per slot
   uint32_t* s_blk = s_bk + MAX_KAPPA;                   // [MAX_KAPPA] destination block g_l
   uint16_t* s_phi = reinterpret_cast<uint16_t*>(smem + 2 * MAX_KAPPA * 4);
-  unsigned char* s_g = smem + 2 * MAX_KAPPA * 4 + TILE * 2;  // STAGED: [32][GLD] bytes
+  unsigned char* s_g = smem + 2 * MAX_KAPPA * 4 + TILE * 2;  // transposition tile: [32][GLD] bytes
 
   // Which (block, example tile) this wave takes.  OUT with an orbit table: work-groups are
   // renumbered so that the ones an XCD runs side by side (the hardware deals linear ids
@@ -130,10 +130,8 @@ void rows_kernel(RowsArgs a) {
   // ---- loads ---------------------------------------------------------------------------
   // One descriptor per wave: base = first example row of the wave; the range ends with the last
   // valid example row, so rows at or beyond n read as 0 without touching memory.  The scalar
-  // offset selects example tile and the stage's K-range (and, STAGED, the row group); the lane
-  // offset the row and the 16-byte piece.
-  // K-values of k-step j in lane half kg: STAGED 16 j + 8 kg (the natural operand order);
-  // otherwise 32 kg + 8 j, so that a lane's four pieces are 64 (128) contiguous bytes.
+  // offset selects example tile, row group and the stage's K-range; the lane offset the row in
+  // the group and the 16-byte piece.  K-values of k-step j in lane half kg: 16 j + 8 kg.
   const int64_t row_bytes = a.ldg * (int64_t)sizeof(T);
   const int rows_valid = min(32 * ET, a.n - ex0);
   const int64_t range =
@@ -161,11 +159,10 @@ void rows_kernel(RowsArgs a) {
       kb_n += ROWB;
     }
   };
-  const uint32_t voff = STAGED ? (uint32_t)((int64_t)(lane / LPR) * row_bytes + (lane % LPR) * 16)
-                               : (uint32_t)((int64_t)m * row_bytes + kg * 32 * (int)sizeof(T));
+  const uint32_t voff = (uint32_t)((int64_t)(lane / LPR) * row_bytes + (lane % LPR) * 16);
   unsigned char* g_wr = s_g + (lane / LPR) * GLD + (lane % LPR) * 16;
   const unsigned char* g_rd = s_g + m * GLD + kg * (8 * (int)sizeof(T));
-  const int phi_k = STAGED ? kg * 8 : kg * 32;  // + (STAGED ? 16 : 8) * j
+  const int phi_k = kg * 8;  // + 16 j
 
   // Prefetch ring of R example tiles, a whole stage of each: the lines of a tile are requested
   // back to back, once.  (Requesting them one k-step at a time, a stage apart, re-fetched every
@@ -176,8 +173,7 @@ void rows_kernel(RowsArgs a) {
   auto issue_tile = [&](uint32_t kb, int c, uint4 (&dst)[NLD]) {
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
-      const uint32_t so = STAGED ? (uint32_t)(c * 32 + i * RPI) * (uint32_t)row_bytes + kb
-                                 : (uint32_t)(c * 32) * (uint32_t)row_bytes + kb + (uint32_t)(i * 16);
+      const uint32_t so = (uint32_t)(c * 32 + i * RPI) * (uint32_t)row_bytes + kb;
       if constexpr (UNAL) {
         dst[i].x = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(rs, voff, so, 0);
         dst[i].y = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(rs, voff + 4u, so, 0);
@@ -242,7 +238,7 @@ void rows_kernel(RowsArgs a) {
 #pragma unroll
       for (int rt = 0; rt < MT; ++rt)
         pb[j][rt] = *reinterpret_cast<const uint4*>(s_phi + (rt * 32 + m) * PHI_LD + phi_k +
-                                                    (STAGED ? 16 : 8) * j);
+                                                    16 * j);
     if constexpr (!LAST) { clear_tile(); step_next(); }
 #pragma unroll
     for (int c = 0; c < ET; ++c) {
@@ -255,7 +251,7 @@ void rows_kernel(RowsArgs a) {
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
           // bytes of this 16-byte piece that lie before entry d (<= 0: none, >= 16: all)
-          const int vb = tail_bytes - (STAGED ? (lane % LPR) * 16 : kg * 32 * (int)sizeof(T) + i * 16);
+          const int vb = tail_bytes - (lane % LPR) * 16;
           cur[i].x &= dword_mask(vb);
           cur[i].y &= dword_mask(vb - 4);
           cur[i].z &= dword_mask(vb - 8);
@@ -263,21 +259,15 @@ void rows_kernel(RowsArgs a) {
         }
       }
       uint4 g[NLD];  // operand pieces: k-step j is g[j*NV .. j*NV + NV)
-      if constexpr (STAGED) {
 #pragma unroll
-        for (int i = 0; i < NLD; ++i) *reinterpret_cast<uint4*>(g_wr + i * RPI * GLD) = cur[i];
-      } else {
-#pragma unroll
-        for (int i = 0; i < NLD; ++i) g[i] = cur[i];
-      }
+      for (int i = 0; i < NLD; ++i) *reinterpret_cast<uint4*>(g_wr + i * RPI * GLD) = cur[i];
       // refill the slot with the tile R places further on: same stage, or the next one
       const int CN = (c + R) % ET;  // compile-time after unrolling
       const bool wrap = c + R >= ET;
       if (!(LAST && wrap)) issue_tile(wrap ? kb_n : kb_c, CN, cur);
-      if constexpr (STAGED) {
 #pragma unroll
-        for (int i = 0; i < NLD; ++i) g[i] = *reinterpret_cast<const uint4*>(g_rd + (i / NV) * (16 * (int)sizeof(T)) + (i % NV) * 16);
-      }
+      for (int i = 0; i < NLD; ++i)
+        g[i] = *reinterpret_cast<const uint4*>(g_rd + (i / NV) * (16 * (int)sizeof(T)) + (i % NV) * 16);
       if constexpr (sizeof(T) == 2) {
 #pragma unroll
         for (int j = 0; j < KSTEPS; ++j)
@@ -416,7 +406,7 @@ __global__ __launch_bounds__(256) void reduce_rows_kernel(const float* __restric
 struct RowsPlan {
   bool ok = false;
   int mt = 0, et = 0, zsplit = 1, stages = 0, planes = 0, groups = 1, group_slots = 0;
-  bool staged = false, out_stat = false, unal = false;
+  bool out_stat = false, unal = false;
   size_t lds = 0;
 };
 
@@ -463,11 +453,8 @@ RowsPlan make_rows_plan(const SketchParams& p, const void* G, int64_t ldg, int64
   if (pl.out_stat) pl.zsplit = 1;
   pl.stages = pl.out_stat ? (int)(p.kappa * (p.Bc / KC)) : (int)(p.Bc / pl.zsplit / KC);
   pl.planes = pl.out_stat ? 0 : pl.zsplit * (int)p.kappa;
-  // measured: the LDS-staged loads win for bf16 (4.9 against 4.8 TB/s with a padded row stride,
-  // 4.4 against 2.6 at a power-of-two stride) and for 32 stacked rows; fp32 with 64 or 128
-  // stacked rows is short of registers and LDS and is faster with the direct loads
-  pl.staged = dt != FS_F32 || pl.mt == 1;
-  pl.lds = 2 * MAX_KAPPA * 4 + (size_t)(32 * pl.mt) * PHI_LD * 2 + (pl.staged ? 32 * (KC * esz + 16) : 0);
+  // slot tables, the Phi^T tile and the transposition tile
+  pl.lds = 2 * MAX_KAPPA * 4 + (size_t)(32 * pl.mt) * PHI_LD * 2 + 32 * (KC * esz + 16);
   pl.ok = true;
   return pl;
 }
@@ -509,10 +496,8 @@ hipError_t launch_rows(const SketchParams& p, const void* G, int64_t ldg, int64_
   if (ev.start) (void)hipEventRecord(ev.start, st);
   hipError_t e;
 #define FS_ROWS_U(T, MT, ET, U)                                                                    \
-  (pl.out_stat ? (pl.staged ? go(rows_kernel<T, MT, ET, true, true, U>, grid, pl.lds, st, a)        \
-                            : go(rows_kernel<T, MT, ET, false, true, U>, grid, pl.lds, st, a))      \
-               : (pl.staged ? go(rows_kernel<T, MT, ET, true, false, U>, grid, pl.lds, st, a)       \
-                            : go(rows_kernel<T, MT, ET, false, false, U>, grid, pl.lds, st, a)))
+  (pl.out_stat ? go(rows_kernel<T, MT, ET, true, U>, grid, pl.lds, st, a)  \
+               : go(rows_kernel<T, MT, ET, false, U>, grid, pl.lds, st, a))
 #define FS_ROWS(T, MT, ET) (pl.unal ? FS_ROWS_U(T, MT, ET, true) : FS_ROWS_U(T, MT, ET, false))
   if (dt == FS_BF16)
     e = pl.mt == 1 ? FS_ROWS(uint16_t, 1, 4) : pl.mt == 2 ? FS_ROWS(uint16_t, 2, 4) : FS_ROWS(uint16_t, 4, 2);
