@@ -56,12 +56,13 @@ struct RowsArgs {
 // walks the kappa input blocks f^l(g) with Br = 32*MT MFMA columns, and stores the scaled result
 // itself; G is read kappa times (the re-reads hit L2 when neighbouring waves are in step), there
 // are no partial results.  Used when kappa*Br is more than one wave can accumulate.
-// fp32 with 64 or 128 stacked rows gets the whole register file of a SIMD (one wave): with two
-// waves the accumulators and the split operands spill.
+// fp32 with 64 stacked rows and every type with 128 get the whole register file of a SIMD (one
+// wave): with two waves fp32 spills its accumulators and split operands, and a 128-row tile with
+// four example tiles (256 accumulators, in AGPRs) reuses every Phi^T operand twice as often.
 // UNAL: rows are only 4-byte aligned (G or ldg*sizeof(T) not a multiple of 16): every 16-byte
 // piece is loaded as four dwords.
 template <typename T, int MT, int ET, bool OUT, bool UNAL = false>
-__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(sizeof(T) == 4 && MT >= 2 ? 1 : 2)))
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu((sizeof(T) == 4 && MT >= 2) || MT == 4 ? 1 : 2)))
 void rows_kernel(RowsArgs a) {
   constexpr int RWV = 32 * MT;         // tile height: kappa * Br stacked output rows, rounded up
   constexpr int TILE = RWV * PHI_LD;   // bf16 elements of the Phi tile
@@ -419,18 +420,18 @@ RowsPlan make_rows_plan(const SketchParams& p, const void* G, int64_t ldg, int64
   if (p.kappa == 1 && br_tile) {  // nothing is re-read: output-stationary stores the result directly
     pl.out_stat = true;
     pl.mt = (int)p.Br / 32;
-    pl.et = pl.mt == 4 ? 2 : 4;
+    pl.et = 4;
   } else if (rw <= 32) { pl.mt = 1; pl.et = 4; }   // the smallest tile that holds the stacked rows
   else if (rw <= 64) { pl.mt = 2; pl.et = 4; }
-  else if (rw <= 128) { pl.mt = 4; pl.et = 2; }
+  else if (rw <= 128) { pl.mt = 4; pl.et = 4; }
   else if (p.Br < 32) {  // more stacked rows than the highest tile, blocks too small for OUT:
-    pl.mt = 4; pl.et = 2;  // groups of 128/Br slots, G read once per group
+    pl.mt = 4; pl.et = 4;  // groups of 128/Br slots, G read once per group
     pl.group_slots = (int)(128 / p.Br);
     pl.groups = (int)((p.kappa + pl.group_slots - 1) / pl.group_slots);
   } else if (br_tile) {  // too many stacked rows: output-stationary
     pl.out_stat = true;
     pl.mt = (int)p.Br / 32;
-    pl.et = pl.mt == 4 ? 2 : 4;
+    pl.et = 4;
   } else return pl;
   if ((uintptr_t)G % 4 || (ldg * (int64_t)esz) % 4) return pl;           // rows at least dword aligned
   pl.unal = (uintptr_t)G % 16 || (ldg * (int64_t)esz) % 16;              // no 128-bit loads: four dwords each
@@ -500,11 +501,11 @@ hipError_t launch_rows(const SketchParams& p, const void* G, int64_t ldg, int64_
                : go(rows_kernel<T, MT, ET, false, U>, grid, pl.lds, st, a))
 #define FS_ROWS(T, MT, ET) (pl.unal ? FS_ROWS_U(T, MT, ET, true) : FS_ROWS_U(T, MT, ET, false))
   if (dt == FS_BF16)
-    e = pl.mt == 1 ? FS_ROWS(uint16_t, 1, 4) : pl.mt == 2 ? FS_ROWS(uint16_t, 2, 4) : FS_ROWS(uint16_t, 4, 2);
+    e = pl.mt == 1 ? FS_ROWS(uint16_t, 1, 4) : pl.mt == 2 ? FS_ROWS(uint16_t, 2, 4) : FS_ROWS(uint16_t, 4, 4);
   else if (dt == FS_F16)
-    e = pl.mt == 1 ? FS_ROWS(f16, 1, 4) : pl.mt == 2 ? FS_ROWS(f16, 2, 4) : FS_ROWS(f16, 4, 2);
+    e = pl.mt == 1 ? FS_ROWS(f16, 1, 4) : pl.mt == 2 ? FS_ROWS(f16, 2, 4) : FS_ROWS(f16, 4, 4);
   else
-    e = pl.mt == 1 ? FS_ROWS(float, 1, 4) : pl.mt == 2 ? FS_ROWS(float, 2, 4) : FS_ROWS(float, 4, 2);
+    e = pl.mt == 1 ? FS_ROWS(float, 1, 4) : pl.mt == 2 ? FS_ROWS(float, 2, 4) : FS_ROWS(float, 4, 4);
 #undef FS_ROWS
 #undef FS_ROWS_U
   if (ev.stop) (void)hipEventRecord(ev.stop, st);
