@@ -14,7 +14,7 @@
 //
 //  * input-stationary (one wave = one work-group): (input block h, 32*ET examples, row split z)
 //    reads its K-range of G once and accumulates the kappa stacked destination blocks
-//    g_l = f^{-l}(h) (kappa*Br = 32*MT MFMA columns); fp32 partial results stored by input
+//    g_l = f^{-l}(h) (kappa*Br <= 32*MT MFMA columns); fp32 partial results stored by input
 //    block and a fixed-order gather-reduction give `out` without atomics on data;
 //  * Phi^T is generated exactly as in the column layout: per 64-row stage one lane per input
 //    row hashes its kappa slots (Appendix E, "Within-block hashing") and scatters +-1 as bf16
@@ -25,7 +25,8 @@
 //
 // Shapes: power-of-two Br (kappa*Br <= 128: tile height 32, 64 or 128, rows above kappa*Br idle;
 // more: Br < 32 in groups of wiring slots, Br in {32, 64, 128} output-stationary), Bc a multiple
-// of 64, 16-byte aligned rows.  Inputs must be finite (a dense product also multiplies by the zeros).
+// of 64, rows aligned to 4 bytes (to 16 for 128-bit loads).  Inputs must be finite (a dense
+// product also multiplies by the zeros).
 #include <type_traits>
 
 #include "handle.h"
