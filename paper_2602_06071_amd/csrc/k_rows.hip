@@ -60,9 +60,10 @@ struct RowsArgs {
 // fp32 with 64 stacked rows and every type with 128 get the whole register file of a SIMD (one
 // wave): with two waves fp32 spills its accumulators and split operands, and a 128-row tile with
 // four example tiles (256 accumulators, in AGPRs) reuses every Phi^T operand twice as often.
-// UNAL: rows are only 4-byte aligned (G or ldg*sizeof(T) not a multiple of 16): every 16-byte
-// piece is loaded as four dwords.
-template <typename T, int MT, int ET, bool OUT, bool UNAL = false>
+// UNAL = 1: rows are only 4-byte aligned (G or ldg*sizeof(T) not a multiple of 16): every 16-byte
+// piece is loaded as four dwords.  UNAL = 2 (16-bit types): rows are only 2-byte aligned (odd
+// ldg): eight element loads per piece, and a ring of two example tiles.
+template <typename T, int MT, int ET, bool OUT, int UNAL = 0>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu((sizeof(T) == 4 && MT >= 2) || MT == 4 ? 1 : 2)))
 void rows_kernel(RowsArgs a) {
   constexpr int RWV = 32 * MT;         // tile height: kappa * Br stacked output rows, rounded up
@@ -139,8 +140,11 @@ void rows_kernel(RowsArgs a) {
   const int64_t range =
       // (the last row's end rounded up to a dword: range checks are per dword, and the dword that
       // holds entry d-1 must not count as outside; its other half lies in the same aligned word,
-      // hence in mapped memory, and is cleared with the rest of the tail)
-      rows_valid > 0 ? (int64_t)(rows_valid - 1) * row_bytes + ((p.d * (int64_t)sizeof(T) + 3) & ~(int64_t)3) : 0;
+      // hence in mapped memory, and is cleared with the rest of the tail.  Element loads, UNAL = 2,
+      // are checked per element and get the exact end: their rows need not start on a dword.)
+      rows_valid > 0 ? (int64_t)(rows_valid - 1) * row_bytes +
+                           (UNAL == 2 ? p.d * (int64_t)sizeof(T) : (p.d * (int64_t)sizeof(T) + 3) & ~(int64_t)3)
+                     : 0;
   const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
       const_cast<char*>(reinterpret_cast<const char*>(a.G) + (int64_t)ex0 * row_bytes), 0,
       (int)(uint32_t)range, 0x00020000);
@@ -169,14 +173,21 @@ void rows_kernel(RowsArgs a) {
   // Prefetch ring of R example tiles, a whole stage of each: the lines of a tile are requested
   // back to back, once.  (Requesting them one k-step at a time, a stage apart, re-fetched every
   // line four times.)
-  constexpr int R = sizeof(T) == 2 ? ET : 2;
+  constexpr int R = sizeof(T) == 2 && UNAL != 2 ? ET : 2;
   static_assert(ET % R == 0, "the ring divides a stage");
   uint4 ld[R][NLD];
   auto issue_tile = [&](uint32_t kb, int c, uint4 (&dst)[NLD]) {
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
       const uint32_t so = (uint32_t)(c * 32 + i * RPI) * (uint32_t)row_bytes + kb;
-      if constexpr (UNAL) {
+      if constexpr (UNAL == 2) {
+        typedef unsigned short us8 __attribute__((ext_vector_type(8)));
+        us8 e;
+#pragma unroll
+        for (int c = 0; c < 8; ++c)
+          e[c] = (unsigned short)__builtin_amdgcn_raw_buffer_load_b16(rs, voff + 2u * c, so, 0);
+        dst[i] = __builtin_bit_cast(uint4, e);
+      } else if constexpr (UNAL == 1) {
         dst[i].x = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(rs, voff, so, 0);
         dst[i].y = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(rs, voff + 4u, so, 0);
         dst[i].z = (uint32_t)__builtin_amdgcn_raw_buffer_load_b32(rs, voff + 8u, so, 0);
@@ -408,7 +419,8 @@ __global__ __launch_bounds__(256) void reduce_rows_kernel(const float* __restric
 struct RowsPlan {
   bool ok = false;
   int mt = 0, et = 0, zsplit = 1, stages = 0, planes = 0, groups = 1, group_slots = 0;
-  bool out_stat = false, unal = false;
+  bool out_stat = false;
+  int unal = 0;  // 0: 128-bit loads, 1: dword loads, 2: element loads (16-bit types)
   size_t lds = 0;
 };
 
@@ -434,8 +446,9 @@ RowsPlan make_rows_plan(const SketchParams& p, const void* G, int64_t ldg, int64
     pl.mt = (int)p.Br / 32;
     pl.et = 4;
   } else return pl;
-  if ((uintptr_t)G % 4 || (ldg * (int64_t)esz) % 4) return pl;           // rows at least dword aligned
-  pl.unal = (uintptr_t)G % 16 || (ldg * (int64_t)esz) % 16;              // no 128-bit loads: four dwords each
+  if ((uintptr_t)G % esz) return pl;
+  if ((uintptr_t)G % 4 || (ldg * (int64_t)esz) % 4) pl.unal = 2;         // not even dword aligned: element loads
+  else if ((uintptr_t)G % 16 || (ldg * (int64_t)esz) % 16) pl.unal = 1;  // no 128-bit loads: four dwords each
   if (128 * ldg * (int64_t)esz >= ((int64_t)1 << 31)) return pl;          // 32-bit lane offsets and range
   const int64_t ex_tiles = (n + 32 * pl.et - 1) / (32 * pl.et);
   if (ex_tiles > 65535) return pl;
@@ -500,13 +513,16 @@ hipError_t launch_rows(const SketchParams& p, const void* G, int64_t ldg, int64_
 #define FS_ROWS_U(T, MT, ET, U)                                                                    \
   (pl.out_stat ? go(rows_kernel<T, MT, ET, true, U>, grid, pl.lds, st, a)  \
                : go(rows_kernel<T, MT, ET, false, U>, grid, pl.lds, st, a))
-#define FS_ROWS(T, MT, ET) (pl.unal ? FS_ROWS_U(T, MT, ET, true) : FS_ROWS_U(T, MT, ET, false))
+// (U2: what pl.unal == 2 selects -- element loads exist for the 16-bit types only; fp32 rows are
+// always dword aligned)
+#define FS_ROWS(T, MT, ET, U2) \
+  (pl.unal == 0 ? FS_ROWS_U(T, MT, ET, 0) : pl.unal == 1 ? FS_ROWS_U(T, MT, ET, 1) : FS_ROWS_U(T, MT, ET, U2))
   if (dt == FS_BF16)
-    e = pl.mt == 1 ? FS_ROWS(uint16_t, 1, 4) : pl.mt == 2 ? FS_ROWS(uint16_t, 2, 4) : FS_ROWS(uint16_t, 4, 4);
+    e = pl.mt == 1 ? FS_ROWS(uint16_t, 1, 4, 2) : pl.mt == 2 ? FS_ROWS(uint16_t, 2, 4, 2) : FS_ROWS(uint16_t, 4, 4, 2);
   else if (dt == FS_F16)
-    e = pl.mt == 1 ? FS_ROWS(f16, 1, 4) : pl.mt == 2 ? FS_ROWS(f16, 2, 4) : FS_ROWS(f16, 4, 4);
+    e = pl.mt == 1 ? FS_ROWS(f16, 1, 4, 2) : pl.mt == 2 ? FS_ROWS(f16, 2, 4, 2) : FS_ROWS(f16, 4, 4, 2);
   else
-    e = pl.mt == 1 ? FS_ROWS(float, 1, 4) : pl.mt == 2 ? FS_ROWS(float, 2, 4) : FS_ROWS(float, 4, 4);
+    e = pl.mt == 1 ? FS_ROWS(float, 1, 4, 1) : pl.mt == 2 ? FS_ROWS(float, 2, 4, 1) : FS_ROWS(float, 4, 4, 1);
 #undef FS_ROWS
 #undef FS_ROWS_U
   if (ev.stop) (void)hipEventRecord(ev.stop, st);

@@ -125,7 +125,7 @@ def test_apply_argument_errors_before_any_hip_call():
     assert L.fs_sketch_apply_rows(h, buf, 4096, -1, buf, 256, 0, None) == 1   # n < 0
     assert L.fs_sketch_apply_rows(h, buf, 4096, 8, buf, 256, 7, None) == 1    # unknown dtype
     assert L.fs_sketch_set_variant(h, B.VARIANT_MFMA) == 0                    # (AUTO would run the general kernel)
-    assert L.fs_sketch_apply_rows(h, buf, 4097, 8, buf, 256, 1, None) == 2    # bf16 rows not dword aligned
+    assert L.fs_sketch_apply_rows(h, C.c_void_p(4097), 4096, 8, buf, 256, 1, None) == 1   # G not element aligned
     assert L.fs_sketch_rows_workspace_bytes(h, 8, 0, C.byref(out)) == 0
     one_set = 2 * 8 * 256 * 4                                                 # kappa planes of n x k floats
     assert out.value >= one_set and out.value % one_set == 0                  # times the row split

@@ -600,10 +600,12 @@ ROWS = [
     ((4000, 256, 512, 32, 2, 4), 130, 0, 0),        # 416 of 512 entries, input-stationary
     ((4001, 256, 512, 32, 2, 4), 70, 7, 0),         # odd d: the cut falls inside a dword (16-bit types)
     ((7000, 448, 1024, 64, 4, 8), 100, 0, 4),       # output-stationary, M = 7, whole stages beyond d
-    # rows that are dword- but not 16-byte aligned: four dword loads per piece (an odd ldg of a
-    # 16-bit type is not even that and runs on the general kernel)
+    # rows that are not 16-byte aligned: four dword loads per piece, or (an odd ldg of a 16-bit
+    # type) eight element loads
     ((4096, 256, 512, 32, 2, 4), 128, 2, 0),        # ldg = 4098
     ((4096, 256, 512, 32, 2, 4), 70, 1, 1),         # ldg = 4097
+    ((16384, 256, 2048, 32, 4, 4), 72, 3, 0),       # 128 stacked rows, ldg = 16387
+    ((8192, 1024, 512, 64, 4, 8), 100, 1, 0),       # output-stationary, ldg = 8193
     ((8192, 1024, 512, 64, 4, 8), 100, 2, 0),       # output-stationary, ldg = 8194
     ((4001, 256, 512, 32, 2, 4), 40, 1, 0),         # ldg = 4002 and a partly filled last block
     # shapes only the general kernel takes
@@ -664,22 +666,16 @@ def test_apply_rows_one_hot_rows_reproduce_columns_exactly():
 def test_apply_rows_forced_matrix_core_variant_reports_unsupported_shapes():
     """Shapes the matrix-core rows kernel cannot take run on the general one; forcing the
     matrix-core variant turns them into FS_ERR_UNSUPPORTED instead."""
-    G = torch.zeros((4, 8192), device=DEV)
-    for params in [(8192, 384, 128, 6, 4, 2),        # Br = 6: no matrix-core kernel
-                   (8192, 512, 1024, 64, 1, 8)]:     # fine shape, checked below with a bad stride
+    for params in [(8192, 384, 128, 6, 4, 2),        # Br = 6: not a power of two
+                   (8000, 512, 1000, 64, 1, 8)]:     # Bc = 1000: not whole 64-entry stages
+        G = torch.zeros((4, params[0]), device=DEV, dtype=torch.bfloat16)
         sk = B.Sketch(*params, seed=0)
-        odd = torch.zeros((4, 8192 + 1), device=DEV, dtype=torch.bfloat16)[:, :8192]  # rows not dword aligned
-        G = G.to(torch.bfloat16)
-        bad = G if params[3] == 6 else odd
-        sk.apply_rows(bad)
+        sk.apply_rows(G)
         assert sk.info().last_variant == B.VARIANT_GENERIC
         sk.set_variant(B.VARIANT_MFMA)
         with pytest.raises(B.FlashSketchError) as e:
-            sk.apply_rows(bad)
-        assert e.value.status == 2
-        if bad is odd:
             sk.apply_rows(G)
-            assert sk.info().last_variant == B.VARIANT_MFMA
+        assert e.value.status == 2
     torch.cuda.synchronize()
 
 
