@@ -156,12 +156,13 @@ fs_status fs_sketch_apply_ld(fs_sketch_t h, const void* A, int64_t lda, int64_t 
  *    read once; fastest when kappa*Br is exactly 32, 64 or 128, the heights of its tiles);
  *    beyond that Br in {32, 64, 128} is output-stationary (G is read kappa times, mostly from
  *    L2) and smaller Br input-stationary in groups of 128/Br wiring slots (G is read once per
- *    group).  Also needs Bc a multiple of 64 (d need not be one of Bc) and
- *    128*ldg*sizeof(elt) < 2^31.  Fastest when G and ldg*sizeof(elt) are multiples of 16
+ *    group).  Also needs 128*ldg*sizeof(elt) < 2^31 (any Bc; d need not be a multiple of it).
+ *    Fastest when G, ldg*sizeof(elt) and Bc*sizeof(elt) are multiples of 16
  *    bytes (128-bit loads; otherwise four dword loads or, for an odd ldg of a 16-bit type,
  *    eight element loads per piece).  A row stride that is a large power of two maps the
  *    rows of a tile to one HBM channel: prefer ldg = d + 64 elements.
- *  - general: every other valid sketch (any Br, any Bc);
+ *  - general: every other valid sketch (Br not a power of two, or 256 and more with
+ *    kappa > 1, kappa > 128);
  *    tiles are turned through LDS and accumulated without atomics, G is read kappa times.
  * Forcing FS_VARIANT_MFMA on a call the matrix-core kernel cannot take returns
  * FS_ERR_UNSUPPORTED (nothing is launched).

@@ -14,8 +14,8 @@ encodes what the kernels of this library prefer, in that order:
 
 subject to the sketch's own constraints: Br | k, M = k/Br = ceil(d/Bc), kappa <= M, s <= Br.
 For a given Br, Bc is the smallest multiple of 64 with ceil(d/Bc) = M when there is one (whole
-64-row stages; the examples-as-rows matrix-core kernel needs that), else ceil(d/M): the
-column-layout matrix-core kernel takes any Bc, its last stage per block partly filled.  It only does integer arithmetic on shapes;
+64-row stages, aligned block starts), else ceil(d/M): the matrix-core kernels take any Bc,
+the last stage of a block partly filled.  It only does integer arithmetic on shapes;
 nothing here touches the sketch's hash or values.
 """
 from __future__ import annotations

@@ -24,8 +24,8 @@
 //  * the prefetch ring holds whole example tiles (all lines of a tile are requested together).
 //
 // Shapes: power-of-two Br (kappa*Br <= 128: tile height 32, 64 or 128, rows above kappa*Br idle;
-// more: Br < 32 in groups of wiring slots, Br in {32, 64, 128} output-stationary), Bc a multiple
-// of 64, rows aligned to 4 bytes (to 16 for 128-bit loads).  Inputs must be finite (a dense
+// more: Br < 32 in groups of wiring slots, Br in {32, 64, 128} output-stationary), any Bc and
+// alignment (128-bit loads need G, ldg and Bc to be multiples of 16 bytes).  Inputs must be finite (a dense
 // product also multiplies by the zeros).
 #include <type_traits>
 
@@ -151,7 +151,9 @@ void rows_kernel(RowsArgs a) {
   // Byte offset in a row of a stage's first K-value.  IN: the wave's own K-range.  OUT: stage t
   // lies in input block s_blk[t / spb]; (sl_n, st_n, kb_n) describe stage "current + 1" and are
   // stepped once per stage, kb_c is the current stage's offset.
-  const uint32_t spb = p.Bc / KC;  // stages per input block
+  // stages per input block; the last one may reach past the block (Bc not a multiple of 64):
+  // Phi^T gets no nonzeros for those K-values, so the neighbouring block's entries count as 0
+  const uint32_t spb = (p.Bc + KC - 1) / KC;
   uint32_t sl_n = 0, st_n = 0;
   uint32_t kb_c = OUT ? (uint32_t)__builtin_amdgcn_readfirstlane(s_blk[0]) * p.Bc * (uint32_t)sizeof(T)
                       : (uint32_t)(((int64_t)blk * p.Bc + (int64_t)z * T_stages * KC) * (int64_t)sizeof(T));
@@ -211,15 +213,17 @@ void rows_kernel(RowsArgs a) {
   auto produce = [&](int t, int part) {
     if constexpr (OUT) {
       if (part != 0) return;
-      const RowHash rh = row_hash_pow2(s_bk[sl_n], st_n * KC + lane, p.Br);
+      const uint32_t u = st_n * KC + lane;
+      const RowHash rh = row_hash_pow2(s_bk[sl_n], u, p.Br);
       uint32_t r = rh.shift;
-      for (uint32_t i = 0; i < p.s; ++i) {
+      for (uint32_t i = 0; i < (u < p.Bc ? p.s : 0u); ++i) {
         s_phi[__umul24(r, (uint32_t)PHI_LD) + lane] = (uint16_t)(((rh.signs >> i) << 15) | Fmt<T>::one);
         r = (r + rh.stride) & (p.Br - 1);
       }
       return;
     }
     const uint32_t u = (uint32_t)(z * T_stages + t) * KC + lane;
+    if (u >= p.Bc) return;  // past the block
     for (uint32_t slot = part; slot < kap; slot += KSTEPS) {
       const RowHash rh = row_hash_pow2(s_bk[slot], u, p.Br);
       uint32_t r = rh.shift;
@@ -427,7 +431,8 @@ struct RowsPlan {
 RowsPlan make_rows_plan(const SketchParams& p, const void* G, int64_t ldg, int64_t n, fs_dtype dt) {
   RowsPlan pl;
   const size_t esz = dt == FS_F32 ? 4 : 2;
-  if (!p.br_pow2 || p.Bc % KC || p.kappa > (uint32_t)MAX_KAPPA || n < 1) return pl;
+  if (!p.br_pow2 || p.kappa > (uint32_t)MAX_KAPPA || n < 1) return pl;
+  const int64_t blk_stages = ((int64_t)p.Bc + KC - 1) / KC;  // the last one may be partly filled
   const uint64_t rw = (uint64_t)p.kappa * p.Br;
   const bool br_tile = p.Br == 32 || p.Br == 64 || p.Br == 128;
   if (p.kappa == 1 && br_tile) {  // nothing is re-read: output-stationary stores the result directly
@@ -447,8 +452,10 @@ RowsPlan make_rows_plan(const SketchParams& p, const void* G, int64_t ldg, int64
     pl.et = 4;
   } else return pl;
   if ((uintptr_t)G % esz) return pl;
-  if ((uintptr_t)G % 4 || (ldg * (int64_t)esz) % 4) pl.unal = 2;         // not even dword aligned: element loads
-  else if ((uintptr_t)G % 16 || (ldg * (int64_t)esz) % 16) pl.unal = 1;  // no 128-bit loads: four dwords each
+  // what every piece address G + example*ldg + block*Bc + 64*stage (in bytes) is a multiple of
+  const int64_t bc_bytes = (int64_t)p.Bc * (int64_t)esz;
+  if ((uintptr_t)G % 4 || (ldg * (int64_t)esz) % 4 || bc_bytes % 4) pl.unal = 2;         // element loads
+  else if ((uintptr_t)G % 16 || (ldg * (int64_t)esz) % 16 || bc_bytes % 16) pl.unal = 1;  // four dwords each
   if (128 * ldg * (int64_t)esz >= ((int64_t)1 << 31)) return pl;          // 32-bit lane offsets and range
   const int64_t ex_tiles = (n + 32 * pl.et - 1) / (32 * pl.et);
   if (ex_tiles > 65535) return pl;
@@ -458,7 +465,7 @@ RowsPlan make_rows_plan(const SketchParams& p, const void* G, int64_t ldg, int64
   const double g_bytes = (double)p.d * (double)n * esz * pl.groups;
   double best = 0;
   for (int zc = 1; zc <= 16; zc *= 2) {
-    if (zc > 1 && ((p.Bc / zc) % KC != 0 || p.Bc / zc < (uint32_t)KC)) break;
+    if (zc > 1 && p.Bc % (uint32_t)(zc * KC) != 0) break;  // splits are whole stages
     const double waves = (double)p.M * ex_tiles * zc * pl.groups;
     const double plane_bytes = (double)zc * p.kappa * (double)p.k * (double)n * 4.0;
     const double t = g_bytes / (6e12 * (waves < 1024 ? waves / 1024 : 1.0)) + plane_bytes / 3.4e12 +
@@ -466,7 +473,7 @@ RowsPlan make_rows_plan(const SketchParams& p, const void* G, int64_t ldg, int64
     if (zc == 1 || t < best) { best = t; pl.zsplit = zc; }
   }
   if (pl.out_stat) pl.zsplit = 1;
-  pl.stages = pl.out_stat ? (int)(p.kappa * (p.Bc / KC)) : (int)(p.Bc / pl.zsplit / KC);
+  pl.stages = pl.out_stat ? (int)(p.kappa * blk_stages) : (int)(blk_stages / pl.zsplit);
   pl.planes = pl.out_stat ? 0 : pl.zsplit * (int)p.kappa;
   // slot tables, the Phi^T tile and the transposition tile
   pl.lds = 2 * MAX_KAPPA * 4 + (size_t)(32 * pl.mt) * PHI_LD * 2 + 32 * (KC * esz + 16);

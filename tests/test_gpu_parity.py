@@ -608,9 +608,13 @@ ROWS = [
     ((8192, 1024, 512, 64, 4, 8), 100, 1, 0),       # output-stationary, ldg = 8193
     ((8192, 1024, 512, 64, 4, 8), 100, 2, 0),       # output-stationary, ldg = 8194
     ((4001, 256, 512, 32, 2, 4), 40, 1, 0),         # ldg = 4002 and a partly filled last block
+    # Bc not a multiple of the 64-entry stage: no nonzeros of Phi^T past the block
+    ((4000, 256, 500, 32, 2, 4), 130, 0, 0),        # Bc = 500
+    ((1000, 256, 125, 32, 2, 4), 70, 0, 0),         # Bc = 125: blocks start at odd entries
+    ((1536, 1024, 96, 64, 4, 4), 100, 0, 0),        # Bc = 96, output-stationary
+    ((1990, 128, 250, 16, 8, 2), 64, 2, 0),         # Bc = 250 and a partly filled last block
     # shapes only the general kernel takes
     ((1152, 72, 96, 6, 5, 3), 70, 1, 3),            # Br = 6, M = 12, odd row stride
-    ((4000, 256, 500, 32, 2, 4), 130, 0, 0),        # Bc = 500: not whole 64-entry stages
     ((1440, 180, 80, 10, 18, 10), 5, 0, 0),         # kappa = M, s = Br = 10
     ((4096, 1024, 1024, 256, 2, 8), 129, 0, 0),     # Br = 256: two row passes per block at 128 examples a tile
 ]
@@ -667,7 +671,7 @@ def test_apply_rows_forced_matrix_core_variant_reports_unsupported_shapes():
     """Shapes the matrix-core rows kernel cannot take run on the general one; forcing the
     matrix-core variant turns them into FS_ERR_UNSUPPORTED instead."""
     for params in [(8192, 384, 128, 6, 4, 2),        # Br = 6: not a power of two
-                   (8000, 512, 1000, 64, 1, 8)]:     # Bc = 1000: not whole 64-entry stages
+                   (8192, 2048, 1024, 256, 2, 8)]:   # 512 stacked rows of 256-row blocks
         G = torch.zeros((4, params[0]), device=DEV, dtype=torch.bfloat16)
         sk = B.Sketch(*params, seed=0)
         sk.apply_rows(G)
