@@ -50,6 +50,7 @@ struct RowsArgs {
   int stages;   // 64-row stages per work-group
   int zsplit;       // IN: row splits of an input block
   int group_slots;  // IN: wiring slots one work-group stacks (grid.z = zsplit * slot groups)
+  int nsub;         // OUT, Br > 128: 128-row slices of an output block (grid.y = example tiles * nsub)
   uint32_t log2_br;
 };
 
@@ -99,6 +100,12 @@ void rows_kernel(RowsArgs a) {
     opos = id % gridDim.x;
     ey = id / gridDim.x;
     blk = __builtin_amdgcn_readfirstlane(a.orbit[opos]);
+  }
+  // OUT with blocks higher than the tile: the wave owns rows [row_lo, row_lo + 32*MT) of its block
+  uint32_t row_lo = 0;
+  if (OUT && a.nsub > 1) {
+    row_lo = (ey % (uint32_t)a.nsub) * RWV;
+    ey /= (uint32_t)a.nsub;
   }
   const int ex0 = (int)ey * (32 * ET);
   // IN with kappa*Br above the tile height: grid.z also numbers groups of `group_slots` wiring
@@ -216,9 +223,19 @@ void rows_kernel(RowsArgs a) {
       const uint32_t u = st_n * KC + lane;
       const RowHash rh = row_hash_pow2(s_bk[sl_n], u, p.Br);
       uint32_t r = rh.shift;
-      for (uint32_t i = 0; i < (u < p.Bc ? p.s : 0u); ++i) {
-        s_phi[__umul24(r, (uint32_t)PHI_LD) + lane] = (uint16_t)(((rh.signs >> i) << 15) | Fmt<T>::one);
-        r = (r + rh.stride) & (p.Br - 1);
+      const uint32_t cnt = u < p.Bc ? p.s : 0u;
+      if (a.nsub > 1) {  // (wave-uniform) keep the nonzeros that fall into this wave's slice
+        for (uint32_t i = 0; i < cnt; ++i) {
+          const uint32_t local = r - row_lo;  // unsigned: rows below the slice wrap high
+          if (local < (uint32_t)RWV)
+            s_phi[__umul24(local, (uint32_t)PHI_LD) + lane] = (uint16_t)(((rh.signs >> i) << 15) | Fmt<T>::one);
+          r = (r + rh.stride) & (p.Br - 1);
+        }
+      } else {
+        for (uint32_t i = 0; i < cnt; ++i) {
+          s_phi[__umul24(r, (uint32_t)PHI_LD) + lane] = (uint16_t)(((rh.signs >> i) << 15) | Fmt<T>::one);
+          r = (r + rh.stride) & (p.Br - 1);
+        }
       }
       return;
     }
@@ -326,7 +343,7 @@ void rows_kernel(RowsArgs a) {
   // ---- epilogue: accumulator v of tile (c, rt) is example ex0 + 32 c + 8 (v/4) + 4 kg + v%4,
   // stacked row 32 rt + m.
   if constexpr (OUT) {  // the finished block: scale, convert, 32 consecutive columns per half-wave
-    T* base = reinterpret_cast<T*>(a.out) + (int64_t)ex0 * a.ldo + (int64_t)blk * p.Br + m;
+    T* base = reinterpret_cast<T*>(a.out) + (int64_t)ex0 * a.ldo + (int64_t)blk * p.Br + row_lo + m;
 #pragma unroll
     for (int c = 0; c < ET; ++c)
 #pragma unroll
@@ -425,6 +442,7 @@ struct RowsPlan {
   int mt = 0, et = 0, zsplit = 1, stages = 0, planes = 0, groups = 1, group_slots = 0;
   bool out_stat = false;
   int unal = 0;  // 0: 128-bit loads, 1: dword loads, 2: element loads (16-bit types)
+  int nsub = 1;  // OUT: 128-row slices of an output block
   size_t lds = 0;
 };
 
@@ -434,10 +452,12 @@ RowsPlan make_rows_plan(const SketchParams& p, const void* G, int64_t ldg, int64
   if (!p.br_pow2 || p.kappa > (uint32_t)MAX_KAPPA || n < 1) return pl;
   const int64_t blk_stages = ((int64_t)p.Bc + KC - 1) / KC;  // the last one may be partly filled
   const uint64_t rw = (uint64_t)p.kappa * p.Br;
-  const bool br_tile = p.Br == 32 || p.Br == 64 || p.Br == 128;
+  const bool br_tile = p.Br >= 32;  // a power of two: 32, 64, 128, or 128-row slices of a higher block
+  const int out_mt = (int)(p.Br > 128 ? 128 : p.Br) / 32;
+  const int out_nsub = p.Br > 128 ? (int)(p.Br / 128) : 1;
   if (p.kappa == 1 && br_tile) {  // nothing is re-read: output-stationary stores the result directly
     pl.out_stat = true;
-    pl.mt = (int)p.Br / 32;
+    pl.mt = out_mt; pl.nsub = out_nsub;
     pl.et = 4;
   } else if (rw <= 32) { pl.mt = 1; pl.et = 4; }   // the smallest tile that holds the stacked rows
   else if (rw <= 64) { pl.mt = 2; pl.et = 4; }
@@ -448,7 +468,7 @@ RowsPlan make_rows_plan(const SketchParams& p, const void* G, int64_t ldg, int64
     pl.groups = (int)((p.kappa + pl.group_slots - 1) / pl.group_slots);
   } else if (br_tile) {  // too many stacked rows: output-stationary
     pl.out_stat = true;
-    pl.mt = (int)p.Br / 32;
+    pl.mt = out_mt; pl.nsub = out_nsub;
     pl.et = 4;
   } else return pl;
   if ((uintptr_t)G % esz) return pl;
@@ -458,7 +478,7 @@ RowsPlan make_rows_plan(const SketchParams& p, const void* G, int64_t ldg, int64
   else if ((uintptr_t)G % 16 || (ldg * (int64_t)esz) % 16 || bc_bytes % 16) pl.unal = 1;  // four dwords each
   if (128 * ldg * (int64_t)esz >= ((int64_t)1 << 31)) return pl;          // 32-bit lane offsets and range
   const int64_t ex_tiles = (n + 32 * pl.et - 1) / (32 * pl.et);
-  if (ex_tiles > 65535) return pl;
+  if (ex_tiles * pl.nsub > 65535) return pl;
   // row split: the traffic model of the column layout (G at ~6 TB/s once 1024 waves exist,
   // planes written at ~3.4 TB/s and read back at ~6 TB/s)
   if (pl.group_slots == 0) pl.group_slots = (int)p.kappa;
@@ -512,8 +532,8 @@ hipError_t launch_rows(const SketchParams& p, const void* G, int64_t ldg, int64_
   a.stages = pl.stages;
   a.log2_br = 0;
   while ((1u << a.log2_br) < p.Br) ++a.log2_br;
-  a.zsplit = pl.zsplit; a.group_slots = pl.group_slots;
-  const dim3 grid(p.M, (unsigned)((n + 32 * pl.et - 1) / (32 * pl.et)), pl.zsplit * pl.groups);
+  a.zsplit = pl.zsplit; a.group_slots = pl.group_slots; a.nsub = pl.nsub;
+  const dim3 grid(p.M, (unsigned)((n + 32 * pl.et - 1) / (32 * pl.et)) * pl.nsub, pl.zsplit * pl.groups);
 
   if (ev.start) (void)hipEventRecord(ev.start, st);
   hipError_t e;

@@ -613,10 +613,14 @@ ROWS = [
     ((1000, 256, 125, 32, 2, 4), 70, 0, 0),         # Bc = 125: blocks start at odd entries
     ((1536, 1024, 96, 64, 4, 4), 100, 0, 0),        # Bc = 96, output-stationary
     ((1990, 128, 250, 16, 8, 2), 64, 2, 0),         # Bc = 250 and a partly filled last block
+    # output blocks higher than the 128-row tile: 128-row slices
+    ((4096, 1024, 1024, 256, 2, 8), 129, 0, 0),     # Br = 256
+    ((8192, 4096, 1024, 512, 3, 32), 70, 2, 0),     # Br = 512, s = 32
+    ((2048, 2048, 1024, 1024, 1, 16), 40, 0, 4),    # Br = 1024, kappa = 1
     # shapes only the general kernel takes
     ((1152, 72, 96, 6, 5, 3), 70, 1, 3),            # Br = 6, M = 12, odd row stride
     ((1440, 180, 80, 10, 18, 10), 5, 0, 0),         # kappa = M, s = Br = 10
-    ((4096, 1024, 1024, 256, 2, 8), 129, 0, 0),     # Br = 256: two row passes per block at 128 examples a tile
+    ((1440, 180, 80, 10, 18, 10), 130, 2, 0),       # the same over two example tiles
 ]
 
 
@@ -671,7 +675,7 @@ def test_apply_rows_forced_matrix_core_variant_reports_unsupported_shapes():
     """Shapes the matrix-core rows kernel cannot take run on the general one; forcing the
     matrix-core variant turns them into FS_ERR_UNSUPPORTED instead."""
     for params in [(8192, 384, 128, 6, 4, 2),        # Br = 6: not a power of two
-                   (8192, 2048, 1024, 256, 2, 8)]:   # 512 stacked rows of 256-row blocks
+                   (7680, 1200, 64, 10, 4, 2)]:      # Br = 10
         G = torch.zeros((4, params[0]), device=DEV, dtype=torch.bfloat16)
         sk = B.Sketch(*params, seed=0)
         sk.apply_rows(G)
