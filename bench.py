@@ -26,7 +26,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the dominant kernel on the default workload, from the rocprofv3
 # FETCH_SIZE / WRITE_SIZE runs summarised in profiles/blockperm_mfma_grad_bf16_chunk256.md
-MEASURED_TRAFFIC = {("grad", "mfma"): (2_097_532 + 22_528) * 1024}
+MEASURED_TRAFFIC = {("grad", "mfma"): (2_097_533 + 22_528) * 1024}
 
 
 def parse():
