@@ -156,7 +156,8 @@ fs_status fs_sketch_apply_ld(fs_sketch_t h, const void* A, int64_t lda, int64_t 
  *    once; fastest when kappa*Br is exactly 32, 64 or 128, the heights of its tiles); beyond
  *    that Br >= 32 is output-stationary (G is read kappa times, mostly from L2; blocks higher
  *    than 128 rows in 128-row slices) and smaller Br input-stationary in groups of 128/Br
- *    wiring slots (G is read once per group).  Also needs 128*ldg*sizeof(elt) < 2^31 (any Bc; d need not be a multiple of it).
+ *    wiring slots (G is read once per group).  Also needs 130*ldg*sizeof(elt) < 2^31 (input-stationary: 34*ldg*sizeof(elt));
+ *    any Bc, and d need not be a multiple of it.
  *    Fastest when G, ldg*sizeof(elt) and Bc*sizeof(elt) are multiples of 16
  *    bytes (128-bit loads; otherwise four dword loads or, for an odd ldg of a 16-bit type,
  *    eight element loads per piece).  A row stride that is a large power of two maps the
@@ -172,6 +173,26 @@ fs_status fs_sketch_apply_ld(fs_sketch_t h, const void* A, int64_t lda, int64_t 
 fs_status fs_sketch_apply_rows(fs_sketch_t h, const void* G, int64_t ldg, int64_t n, void* out,
                                int64_t ldo, fs_dtype dtype, void* stream);
 fs_status fs_sketch_rows_workspace_bytes(fs_sketch_t h, int64_t n, fs_dtype dtype, size_t* bytes);
+
+/* Which kernel an apply with these arguments would launch, without launching anything (pure
+ * host work, usable without a GPU): for tuning block sizes and for checking that a call stays
+ * on the fast path.  `rows` = 0 describes fs_sketch_apply_ld(h, A, ld, n, ...), 1 describes
+ * fs_sketch_apply_rows(h, A, ld, n, ...); only the alignment of the address A is used, the
+ * memory is not touched.  Results: *variant (fs_variant that would run; for kinds other than
+ * FS_KIND_BLOCKPERM FS_VARIANT_GENERIC), *mode (as fs_info.last_mode), *flags (fs_plan_flags),
+ * *workspace_bytes (what the call needs attached or would allocate).  The handle's
+ * fs_sketch_set_variant choice is honoured.  Errors as for the apply it describes
+ * (FS_ERR_INVALID_ARG, FS_ERR_UNSUPPORTED); any result pointer may be NULL. */
+typedef enum {
+  FS_PLAN_ELEMENT_LOADS = 1, /* A / G not aligned for vector loads: narrower loads, slower    */
+  FS_PLAN_ROW_SLICES = 2,    /* output blocks higher than 128 rows, served in 128-row slices   */
+  FS_PLAN_SLOT_GROUPS = 4,   /* more than 128 stacked rows of small blocks: input read once
+                                per group of wiring slots                                      */
+  FS_PLAN_SPLIT = 8          /* the rows of a work-group's input are split over grid.z         */
+} fs_plan_flags;
+fs_status fs_sketch_plan(fs_sketch_t h, const void* A, int64_t ld, int64_t n, fs_dtype dtype,
+                         int32_t rows, int32_t* variant, int32_t* mode, int32_t* flags,
+                         size_t* workspace_bytes);
 
 /* Materialise the nonzeros of S on the device (BLOCKPERM / SJLT_SCATTER):
  * rows[c*kappa*s + (l-1)*s + i] = global output row, signs[...] = +1/-1, for

@@ -22,8 +22,9 @@ SYMBOLS = [
     "fs_sketch_export", "fs_sketch_export_dense", "fs_sketch_info", "fs_sketch_workspace_bytes",
     "fs_sketch_set_workspace", "fs_sketch_set_variant", "fs_sketch_destroy", "fs_status_string",
     "fs_sketch_profile_begin", "fs_sketch_profile_end",
-    "fs_sketch_apply_rows", "fs_sketch_rows_workspace_bytes",
+    "fs_sketch_apply_rows", "fs_sketch_rows_workspace_bytes", "fs_sketch_plan",
 ]
+PLAN_ELEMENT_LOADS, PLAN_ROW_SLICES, PLAN_SLOT_GROUPS, PLAN_SPLIT = 1, 2, 4, 8
 
 
 class FlashSketchError(RuntimeError):
@@ -58,6 +59,8 @@ def _load() -> C.CDLL:
     L.fs_sketch_apply_ld.argtypes = [vp, vp, i64, i64, vp, i64, C.c_int, vp]
     L.fs_sketch_apply_rows.argtypes = [vp, vp, i64, i64, vp, i64, C.c_int, vp]
     L.fs_sketch_rows_workspace_bytes.argtypes = [vp, i64, C.c_int, C.POINTER(C.c_size_t)]
+    i32p = C.POINTER(C.c_int32)
+    L.fs_sketch_plan.argtypes = [vp, vp, i64, i64, C.c_int, C.c_int32, i32p, i32p, i32p, C.POINTER(C.c_size_t)]
     L.fs_sketch_export.argtypes = [vp, vp, vp, vp]
     L.fs_sketch_export_dense.argtypes = [vp, vp, vp]
     L.fs_sketch_info.argtypes = [vp, C.POINTER(fs_info)]
@@ -212,6 +215,18 @@ class Sketch:
                                         _dtype_code(G), _stream_ptr(stream)),
                "fs_sketch_apply_rows")
         return out
+
+    def plan(self, n: int, dtype: torch.dtype, ld: int | None = None, rows: bool = False,
+             address: int = 256) -> dict:
+        """Which kernel an apply of n vectors would launch (host-only; nothing runs).  `ld` is the
+        leading dimension (default: packed), `address` stands for the data pointer: only its
+        alignment matters."""
+        if ld is None:
+            ld = self.d if rows else n
+        v, m, f, w = C.c_int32(), C.c_int32(), C.c_int32(), C.c_size_t()
+        _check(lib.fs_sketch_plan(self._h, C.c_void_p(address), ld, n, _DTYPE_CODES[dtype], int(rows),
+                                  C.byref(v), C.byref(m), C.byref(f), C.byref(w)), "fs_sketch_plan")
+        return {"variant": v.value, "mode": m.value, "flags": f.value, "workspace_bytes": w.value}
 
     def rows_workspace_bytes(self, n: int, dtype: torch.dtype) -> int:
         out = C.c_size_t()

@@ -383,8 +383,36 @@ fs_status fs_sketch_rows_workspace_bytes(fs_sketch_t h, int64_t n, fs_dtype dt, 
   if (n == 0 || h->kind != FS_KIND_BLOCKPERM) return FS_OK;
   const size_t esz = dt == FS_F32 ? 4 : 2;
   const int64_t ld = (h->p.d + 7) & ~(int64_t)7;  // a well-aligned call: packed rows rounded to 16 bytes
-  if (128 * ld * (int64_t)esz >= ((int64_t)1 << 31)) return FS_OK;
+  if (34 * ld * (int64_t)esz >= ((int64_t)1 << 31)) return FS_OK;
   *bytes = fs::rows_workspace_bytes(h->p, (const void*)(uintptr_t)256, ld, n, dt);
+  return FS_OK;
+}
+
+fs_status fs_sketch_plan(fs_sketch_t h, const void* A, int64_t ld, int64_t n, fs_dtype dt, int32_t rows,
+                         int32_t* variant, int32_t* mode, int32_t* flags, size_t* workspace_bytes) {
+  if (!h || n < 0 || !valid_dtype(dt) || (rows != 0 && rows != 1)) return FS_ERR_INVALID_ARG;
+  const size_t esz = dt == FS_F32 ? 4 : 2;
+  if (!A || (uintptr_t)A % esz || ld < (rows ? h->p.d : n) || n > 0x7fffffff || ld > ((int64_t)1 << 40))
+    return FS_ERR_INVALID_ARG;
+  if (rows && h->kind != FS_KIND_BLOCKPERM) return FS_ERR_UNSUPPORTED;
+  int v = FS_VARIANT_GENERIC, m = 0, f = 0;
+  size_t ws = 0;
+  if (n > 0 && h->kind == FS_KIND_BLOCKPERM) {
+    int mm = 0, ff = 0;
+    size_t w = 0;
+    const bool can = rows ? fs::rows_describe(h->p, A, ld, n, dt, &mm, &ff, &w)
+                          : fs::mfma_describe(h->p, A, ld, n, dt, fs::mfma_wants_orbit(h->p), &mm, &ff, &w);
+    if (h->variant == FS_VARIANT_MFMA && !can) return FS_ERR_UNSUPPORTED;
+    if (can && h->variant != FS_VARIANT_GENERIC) { v = FS_VARIANT_MFMA; m = mm; f = ff; ws = w; }
+  } else if (n > 0) {
+    int vv;
+    const fs_status rc = needed_workspace(h, A, ld, n, A, n, dt, &vv, &ws);
+    if (rc != FS_OK) return rc;
+  }
+  if (variant) *variant = v;
+  if (mode) *mode = m;
+  if (flags) *flags = f;
+  if (workspace_bytes) *workspace_bytes = ws;
   return FS_OK;
 }
 

@@ -65,12 +65,18 @@ size_t mfma_workspace_bytes(const SketchParams& p, int64_t n, fs_dtype dt);
 // orbit: device array of 2*M words (block at each orbit position of the wiring map
 // starting from block 0, then the inverse), or NULL.
 bool mfma_wants_orbit(const SketchParams& p);
+// What launch_mfma would do, without launching (pure host work): mode 1 output-stationary, 2
+// input-stationary, 3 the same with orbit runs; flags as in fs_plan_flags.  False: unsupported.
+bool mfma_describe(const SketchParams& p, const void* A, int64_t lda, int64_t n, fs_dtype dt,
+                   bool have_orbit, int* mode, int* flags, size_t* workspace);
 hipError_t launch_mfma(const SketchParams& p, const void* A, int64_t lda, int64_t n, void* out,
                        int64_t ldo, fs_dtype dt, void* ws, const uint32_t* orbit, hipStream_t st,
                        EventPair ev, int* mode);
 
 // Matrix-core path for inputs held examples-as-rows: G is n x d (ld = ldg), out is n x k.
 bool rows_supported(const SketchParams& p, const void* G, int64_t ldg, int64_t n, fs_dtype dt);
+bool rows_describe(const SketchParams& p, const void* G, int64_t ldg, int64_t n, fs_dtype dt, int* mode,
+                   int* flags, size_t* workspace);
 size_t rows_workspace_bytes(const SketchParams& p, const void* G, int64_t ldg, int64_t n, fs_dtype dt);
 hipError_t launch_rows(const SketchParams& p, const void* G, int64_t ldg, int64_t n, void* out,
                        int64_t ldo, fs_dtype dt, void* ws, const uint32_t* orbit, hipStream_t st,

@@ -174,6 +174,17 @@ bool mfma_supported(const SketchParams& p, const void* A, int64_t lda, int64_t n
   return make_plan(p, A, lda, n, dt, false).ok;
 }
 
+bool mfma_describe(const SketchParams& p, const void* A, int64_t lda, int64_t n, fs_dtype dt,
+                   bool have_orbit, int* mode, int* flags, size_t* workspace) {
+  const Plan pl = make_plan(p, A, lda, n, dt, have_orbit);
+  if (!pl.ok) return false;
+  *mode = !pl.in_stat ? 1 : pl.run > 1 ? 3 : 2;
+  *flags = (pl.unal ? FS_PLAN_ELEMENT_LOADS : 0) | (pl.nsub > 1 ? FS_PLAN_ROW_SLICES : 0) |
+           (pl.groups > 1 ? FS_PLAN_SLOT_GROUPS : 0) | (pl.zsplit > 1 ? FS_PLAN_SPLIT : 0);
+  *workspace = (size_t)pl.planes * (size_t)p.k * (size_t)pl.ldw * sizeof(float);
+  return true;
+}
+
 bool mfma_wants_orbit(const SketchParams& p) {
   return p.M >= 4 && p.M <= (1u << 20);
 }

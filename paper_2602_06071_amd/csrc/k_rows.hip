@@ -64,7 +64,9 @@ struct RowsArgs {
 // UNAL = 1: rows are only 4-byte aligned (G or ldg*sizeof(T) not a multiple of 16): every 16-byte
 // piece is loaded as four dwords.  UNAL = 2 (16-bit types): rows are only 2-byte aligned (odd
 // ldg): eight element loads per piece, and a ring of two example tiles.
-template <typename T, int MT, int ET, bool OUT, int UNAL = 0>
+// BIG (input-stationary only): rows so long that 128 of them span 2^31 bytes get one buffer
+// descriptor per 32-example tile instead of one per wave (2 % slower on the gradient workload).
+template <typename T, int MT, int ET, bool OUT, int UNAL = 0, bool BIG = false>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu((sizeof(T) == 4 && MT >= 2) || MT == 4 ? 1 : 2)))
 void rows_kernel(RowsArgs a) {
   constexpr int RWV = 32 * MT;         // tile height: kappa * Br stacked output rows, rounded up
@@ -138,23 +140,30 @@ void rows_kernel(RowsArgs a) {
   __syncthreads();  // one wave: orders the table writes before the reads by other lanes
 
   // ---- loads ---------------------------------------------------------------------------
-  // One descriptor per wave: base = first example row of the wave; the range ends with the last
-  // valid example row, so rows at or beyond n read as 0 without touching memory.  The scalar
-  // offset selects example tile, row group and the stage's K-range; the lane offset the row in
-  // the group and the 16-byte piece.  K-values of k-step j in lane half kg: 16 j + 8 kg.
+  // One descriptor per wave (BIG: per 32-example tile): base = its first example row; the range
+  // ends with its last valid example row, so rows at or beyond n read as 0 without touching
+  // memory.  The scalar offset selects example tile (not BIG), row group and the stage's K-range;
+  // the lane offset the row in the group and the 16-byte piece.
+  // K-values of k-step j in lane half kg: 16 j + 8 kg.
   const int64_t row_bytes = a.ldg * (int64_t)sizeof(T);
   const int rows_valid = min(32 * ET, a.n - ex0);
-  const int64_t range =
+  const int64_t last_row_bytes =
       // (the last row's end rounded up to a dword: range checks are per dword, and the dword that
       // holds entry d-1 must not count as outside; its other half lies in the same aligned word,
       // hence in mapped memory, and is cleared with the rest of the tail.  Element loads, UNAL = 2,
       // are checked per element and get the exact end: their rows need not start on a dword.)
-      rows_valid > 0 ? (int64_t)(rows_valid - 1) * row_bytes +
-                           (UNAL == 2 ? p.d * (int64_t)sizeof(T) : (p.d * (int64_t)sizeof(T) + 3) & ~(int64_t)3)
-                     : 0;
-  const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
-      const_cast<char*>(reinterpret_cast<const char*>(a.G) + (int64_t)ex0 * row_bytes), 0,
-      (int)(uint32_t)range, 0x00020000);
+      UNAL == 2 ? p.d * (int64_t)sizeof(T) : (p.d * (int64_t)sizeof(T) + 3) & ~(int64_t)3;
+  constexpr int ND = BIG ? ET : 1;      // descriptors
+  constexpr int DR = BIG ? 32 : 32 * ET;  // example rows each covers
+  __amdgpu_buffer_rsrc_t rs_t[ND];
+#pragma unroll
+  for (int c = 0; c < ND; ++c) {
+    const int valid = min(DR, rows_valid - DR * c);
+    const int64_t range = valid > 0 ? (int64_t)(valid - 1) * row_bytes + last_row_bytes : 0;
+    rs_t[c] = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<char*>(reinterpret_cast<const char*>(a.G) + (int64_t)(ex0 + DR * c) * row_bytes), 0,
+        (int)(uint32_t)range, 0x00020000);
+  }
   // Byte offset in a row of a stage's first K-value.  IN: the wave's own K-range.  OUT: stage t
   // lies in input block s_blk[t / spb]; (sl_n, st_n, kb_n) describe stage "current + 1" and are
   // stepped once per stage, kb_c is the current stage's offset.
@@ -188,7 +197,8 @@ void rows_kernel(RowsArgs a) {
   auto issue_tile = [&](uint32_t kb, int c, uint4 (&dst)[NLD]) {
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
-      const uint32_t so = (uint32_t)(c * 32 + i * RPI) * (uint32_t)row_bytes + kb;
+      const __amdgpu_buffer_rsrc_t rs = rs_t[BIG ? c : 0];
+      const uint32_t so = (uint32_t)((BIG ? 0 : c * 32) + i * RPI) * (uint32_t)row_bytes + kb;
       if constexpr (UNAL == 2) {
         typedef unsigned short us8 __attribute__((ext_vector_type(8)));
         us8 e;
@@ -443,6 +453,7 @@ struct RowsPlan {
   bool out_stat = false;
   int unal = 0;  // 0: 128-bit loads, 1: dword loads, 2: element loads (16-bit types)
   int nsub = 1;  // OUT: 128-row slices of an output block
+  bool big = false;  // IN: one descriptor per 32-example tile (very long rows)
   size_t lds = 0;
 };
 
@@ -476,7 +487,10 @@ RowsPlan make_rows_plan(const SketchParams& p, const void* G, int64_t ldg, int64
   const int64_t bc_bytes = (int64_t)p.Bc * (int64_t)esz;
   if ((uintptr_t)G % 4 || (ldg * (int64_t)esz) % 4 || bc_bytes % 4) pl.unal = 2;         // element loads
   else if ((uintptr_t)G % 16 || (ldg * (int64_t)esz) % 16 || bc_bytes % 16) pl.unal = 1;  // four dwords each
-  if (128 * ldg * (int64_t)esz >= ((int64_t)1 << 31)) return pl;          // 32-bit lane offsets and range
+  // 32-bit offsets: within the wave's 128 examples, or (input-stationary only) within a 32-example tile
+  if (34 * ldg * (int64_t)esz >= ((int64_t)1 << 31)) return pl;
+  pl.big = 130 * ldg * (int64_t)esz >= ((int64_t)1 << 31);
+  if (pl.big && pl.out_stat) return pl;
   const int64_t ex_tiles = (n + 32 * pl.et - 1) / (32 * pl.et);
   if (ex_tiles * pl.nsub > 65535) return pl;
   // row split: the traffic model of the column layout (G at ~6 TB/s once 1024 waves exist,
@@ -513,6 +527,17 @@ bool rows_supported(const SketchParams& p, const void* G, int64_t ldg, int64_t n
   return make_rows_plan(p, G, ldg, n, dt).ok;
 }
 
+bool rows_describe(const SketchParams& p, const void* G, int64_t ldg, int64_t n, fs_dtype dt, int* mode,
+                   int* flags, size_t* workspace) {
+  const RowsPlan pl = make_rows_plan(p, G, ldg, n, dt);
+  if (!pl.ok) return false;
+  *mode = pl.out_stat ? 1 : 2;
+  *flags = (pl.unal ? FS_PLAN_ELEMENT_LOADS : 0) | (pl.nsub > 1 ? FS_PLAN_ROW_SLICES : 0) |
+           (pl.groups > 1 ? FS_PLAN_SLOT_GROUPS : 0) | (pl.zsplit > 1 ? FS_PLAN_SPLIT : 0);
+  *workspace = rows_workspace_bytes(p, G, ldg, n, dt);
+  return true;
+}
+
 size_t rows_workspace_bytes(const SketchParams& p, const void* G, int64_t ldg, int64_t n, fs_dtype dt) {
   const RowsPlan pl = make_rows_plan(p, G, ldg, n, dt);
   if (!pl.ok) return 0;
@@ -537,8 +562,9 @@ hipError_t launch_rows(const SketchParams& p, const void* G, int64_t ldg, int64_
 
   if (ev.start) (void)hipEventRecord(ev.start, st);
   hipError_t e;
-#define FS_ROWS_U(T, MT, ET, U)                                                                    \
-  (pl.out_stat ? go(rows_kernel<T, MT, ET, true, U>, grid, pl.lds, st, a)  \
+#define FS_ROWS_U(T, MT, ET, U)                                                   \
+  (pl.out_stat ? go(rows_kernel<T, MT, ET, true, U>, grid, pl.lds, st, a)         \
+   : pl.big    ? go(rows_kernel<T, MT, ET, false, U, true>, grid, pl.lds, st, a)  \
                : go(rows_kernel<T, MT, ET, false, U>, grid, pl.lds, st, a))
 // (U2: what pl.unal == 2 selects -- element loads exist for the 16-bit types only; fp32 rows are
 // always dword aligned)

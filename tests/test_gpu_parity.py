@@ -166,6 +166,8 @@ def test_apply_matches_oracle(case, dtype, variant):
     sk = make_sketch(params, seed, variant)
     apply_or_skip(sk, A, obuf[:, :n])
     torch.cuda.synchronize()
+    plan, did = sk.plan(n, dtype, ld=A.stride(0), address=A.data_ptr()), sk.info()
+    assert (plan["variant"], plan["mode"]) == (did.last_variant, did.last_mode)   # the host-side query agrees
     ref = O.apply(oracle_csc(params, seed), host64(A))
     check(obuf[:, :n], ref, dtype, "apply")
     if po:
@@ -437,6 +439,26 @@ def test_full_config_grad_rows_layout_sampled():
     check(out[idx], ref, cfg.dtype, "grad rows layout, sampled examples")
 
 
+def test_rows_so_long_that_128_of_them_span_2_to_31_bytes():
+    """fp32 vectors of the gradient configuration's length held as rows: 16 MiB per row, so the
+    kernel addresses each 32-example tile through a descriptor of its own.  The oracle on a
+    sample of the examples (one of them in the ragged last tile)."""
+    cfg = W.CONFIGS["grad"]
+    n = 150
+    print("long fp32 rows", flush=True)
+    g = torch.Generator(device=DEV).manual_seed(33)
+    Gbuf = torch.randn((n, cfg.d + 64), generator=g, device=DEV)
+    G = Gbuf[:, :cfg.d]
+    sk = B.Sketch(*cfg.params, seed=cfg.sketch_seed)
+    assert sk.plan(n, torch.float32, ld=cfg.d + 64, rows=True)["variant"] == B.VARIANT_MFMA
+    out = sk.apply_rows(G)
+    torch.cuda.synchronize()
+    assert sk.info().last_variant == B.VARIANT_MFMA
+    idx = torch.tensor([0, 31, 32, 127, 128, n - 1], device=DEV)
+    ref = O.apply_rows(oracle_csc(cfg.params, cfg.sketch_seed), host64(G[idx]))
+    check(out[idx], ref, torch.float32, "long fp32 rows, sampled examples")
+
+
 @pytest.mark.parametrize("params,n", [
     ((65536, 65536, 65536, 65536, 1, 2), 8),     # Br at its maximum, one block
     ((1 << 20, 1 << 20, 1, 1, 5, 1), 3),         # Br = Bc = 1, M = 2^20 blocks
@@ -641,6 +663,8 @@ def test_apply_rows_matches_oracle(case, dtype, variant):
     sk = make_sketch(params, 9, variant)
     sk.apply_rows(G, obuf[:, :k])
     torch.cuda.synchronize()
+    plan, did = sk.plan(n, dtype, ld=G.stride(0), rows=True, address=G.data_ptr()), sk.info()
+    assert plan["variant"] == did.last_variant
     ref = O.apply_rows(oracle_csc(params, 9), host64(G))
     check(obuf[:, :k], ref, dtype, "apply_rows")
     if po:
