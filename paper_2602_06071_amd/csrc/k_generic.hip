@@ -36,13 +36,20 @@ __global__ __launch_bounds__(256) void generic_kernel(SketchParams p, const T* _
   for (uint32_t l = 0; l < p.kappa; ++l) {
     h = wire_next(h, p.a, p.b, p.M);
     const uint32_t bk = block_key(p.key1, g, h, p.M);
-    const T* src = A + (int64_t)h * p.Bc * lda + col;
+    // Every load goes to a valid address (row and column clamped into the block) and what should
+    // not count is zeroed afterwards: unconditional loads are issued back to back, conditional
+    // ones were waited for one by one.  Rows at or beyond d (padding of a partly filled last
+    // block) and lanes beyond column n read as 0.
+    const uint32_t rows_here = (uint32_t)min((int64_t)p.Bc, p.d - (int64_t)h * p.Bc);  // >= 1
+    const T* src = A + (int64_t)h * p.Bc * lda + min(col, n - 1);
     for (uint32_t u0 = 0; u0 < p.Bc; u0 += kRowUnroll) {
       float v[kRowUnroll];
 #pragma unroll
       for (int q = 0; q < kRowUnroll; ++q)
-        v[q] = (active && u0 + q < p.Bc && (int64_t)h * p.Bc + u0 + q < p.d)  // padding rows read as 0
-                   ? Elt<T>::load(src + (int64_t)(u0 + q) * lda) : 0.f;
+        v[q] = Elt<T>::load(src + (int64_t)min(u0 + q, rows_here - 1) * lda);
+#pragma unroll
+      for (int q = 0; q < kRowUnroll; ++q)
+        if (!active || u0 + q >= rows_here) v[q] = 0.f;
 #pragma unroll
       for (int q = 0; q < kRowUnroll; ++q) {
         if (u0 + q >= p.Bc) break;
@@ -96,11 +103,14 @@ __global__ __launch_bounds__(128) void generic_rows_kernel(SketchParams p, const
     const uint32_t bk = block_key(p.key1, g, h, p.M);
     for (uint32_t u0 = 0; u0 < p.Bc; u0 += kChunk) {
       __syncthreads();  // the previous chunk has been consumed
+      // (loads at clamped, always valid addresses, zeroed afterwards where they do not count:
+      // see the column kernel)
       for (int idx = tid; idx < te * kChunk; idx += te) {
         const int e = idx / kChunk, q = idx % kChunk;
         const int64_t col = (int64_t)h * p.Bc + u0 + q;  // entry of the vector; padding reads as 0
         const bool ok = ex0 + e < n && u0 + q < p.Bc && col < p.d;
-        sG[q * ld + e] = ok ? Elt<T>::load(G + (ex0 + e) * ldg + col) : 0.f;
+        const float x = Elt<T>::load(G + min(ex0 + e, (int64_t)n - 1) * ldg + min(col, p.d - 1));
+        sG[q * ld + e] = ok ? x : 0.f;
       }
       __syncthreads();
       for (int q = 0; q < kChunk; ++q) {
