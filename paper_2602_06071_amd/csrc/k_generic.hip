@@ -42,7 +42,13 @@ __global__ __launch_bounds__(256) void generic_kernel(SketchParams p, const T* _
     // block) and lanes beyond column n read as 0.
     const uint32_t rows_here = (uint32_t)min((int64_t)p.Bc, p.d - (int64_t)h * p.Bc);  // >= 1
     const T* src = A + (int64_t)h * p.Bc * lda + min(col, n - 1);
+    RowHash lane_rh{0u, 0u, 0u};
+    static_assert(64 % kRowUnroll == 0, "a group of 64 hashed rows is a whole number of load batches");
     for (uint32_t u0 = 0; u0 < p.Bc; u0 += kRowUnroll) {
+      // The hashes of 64 rows at a time, one lane per row, handed to the wave-uniform walk below
+      // with v_readlane: the walk runs on the CU's one scalar unit, which would otherwise also
+      // compute every row's hash once per wave.
+      if (u0 % 64 == 0) lane_rh = POW2 ? row_hash_pow2(bk, u0 + (tid & 63), p.Br) : row_hash_any(bk, u0 + (tid & 63), p.Br);
       float v[kRowUnroll];
 #pragma unroll
       for (int q = 0; q < kRowUnroll; ++q)
@@ -53,7 +59,11 @@ __global__ __launch_bounds__(256) void generic_kernel(SketchParams p, const T* _
 #pragma unroll
       for (int q = 0; q < kRowUnroll; ++q) {
         if (u0 + q >= p.Bc) break;
-        const RowHash rh = POW2 ? row_hash_pow2(bk, u0 + q, p.Br) : row_hash_any(bk, u0 + q, p.Br);
+        const int src_lane = (int)((u0 + q) & 63u);
+        RowHash rh;
+        rh.shift = (uint32_t)__builtin_amdgcn_readlane((int)lane_rh.shift, src_lane);
+        rh.stride = (uint32_t)__builtin_amdgcn_readlane((int)lane_rh.stride, src_lane);
+        rh.signs = (uint32_t)__builtin_amdgcn_readlane((int)lane_rh.signs, src_lane);
         uint32_t r = rh.shift;
         for (uint32_t i = 0; i < p.s; ++i) {
           const uint32_t rel = r - r0;
@@ -105,18 +115,35 @@ __global__ __launch_bounds__(128) void generic_rows_kernel(SketchParams p, const
       __syncthreads();  // the previous chunk has been consumed
       // (loads at clamped, always valid addresses, zeroed afterwards where they do not count:
       // see the column kernel)
-      for (int idx = tid; idx < te * kChunk; idx += te) {
-        const int e = idx / kChunk, q = idx % kChunk;
+      // thread tid takes entry q = tid % 32 of the examples tid/32, tid/32 + te/32, ...: the
+      // column is fixed per thread and the row pointer advances by a constant
+      {
+        const int q = tid % kChunk;
         const int64_t col = (int64_t)h * p.Bc + u0 + q;  // entry of the vector; padding reads as 0
-        const bool ok = ex0 + e < n && u0 + q < p.Bc && col < p.d;
-        const float x = Elt<T>::load(G + min(ex0 + e, (int64_t)n - 1) * ldg + min(col, p.d - 1));
-        sG[q * ld + e] = ok ? x : 0.f;
+        const bool col_ok = u0 + q < p.Bc && col < p.d;
+        const T* colp = G + min(col, p.d - 1);
+        const int64_t last = ((int64_t)n - 1) * ldg;  // offset of the last example's row
+        const int e_step = te / kChunk;
+        int e = tid / kChunk;
+        int64_t row = (ex0 + e) * ldg;
+#pragma unroll 8
+        for (int it = 0; it < kChunk; ++it, e += e_step, row += (int64_t)e_step * ldg) {
+          const bool row_ok = ex0 + e < n;
+          const float x = Elt<T>::load(colp + (row_ok ? row : last));
+          sG[q * ld + e] = (row_ok && col_ok) ? x : 0.f;
+        }
       }
       __syncthreads();
+      // the chunk's hashes, one lane per entry (the upper half-wave repeats the lower one)
+      const RowHash lane_rh = POW2 ? row_hash_pow2(bk, u0 + (tid & (kChunk - 1)), p.Br)
+                                   : row_hash_any(bk, u0 + (tid & (kChunk - 1)), p.Br);
       for (int q = 0; q < kChunk; ++q) {
         if (u0 + q >= p.Bc) break;
         const float v = sG[q * ld + tid];
-        const RowHash rh = POW2 ? row_hash_pow2(bk, u0 + q, p.Br) : row_hash_any(bk, u0 + q, p.Br);
+        RowHash rh;
+        rh.shift = (uint32_t)__builtin_amdgcn_readlane((int)lane_rh.shift, q);
+        rh.stride = (uint32_t)__builtin_amdgcn_readlane((int)lane_rh.stride, q);
+        rh.signs = (uint32_t)__builtin_amdgcn_readlane((int)lane_rh.signs, q);
         uint32_t r = rh.shift;
         for (uint32_t i = 0; i < p.s; ++i) {
           const uint32_t rel = r - r0;
