@@ -772,6 +772,54 @@ def _random_cases(count, seed):
     return cases
 
 
+def _random_cases_wide(count, seed):
+    """A wider draw: high and tiny blocks, many wiring slots, block widths that are not whole
+    stages, a partly filled last block -- the combinations of the dispatcher's special modes."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    while len(cases) < count:
+        Br = int(rng.choice([1, 2, 4, 8, 16, 32, 64, 128, 256, 512, 6, 48]))
+        M = int(rng.choice([1, 2, 3, 4, 8, 16, 40, 64, 130]))
+        Bc = int(rng.choice([8, 40, 64, 72, 96, 125, 128, 200, 256, 500]))
+        kappa = int(rng.integers(1, min(M, 40) + 1))
+        s = int(rng.integers(1, min(Br, 32) + 1))
+        n = int(rng.choice([1, 3, 64, 100, 128, 130, 255, 256, 301]))
+        short = int(rng.choice([0, 0, 1, Bc // 2]))        # rows missing from the last block
+        d = M * Bc - min(short, Bc - 1)
+        if M * Bc * n > 2 ** 23 or M * Br * n > 2 ** 23:
+            continue
+        cases.append(((d, M * Br, Bc, Br, kappa, s), n, int(rng.integers(0, 2 ** 62))))
+    return cases
+
+
+@DTYPES
+def test_random_shapes_wide_draw_both_layouts(dtype):
+    """60 seeded draws; the column apply (packed, so lda = n is often not a multiple of 4) and the
+    rows apply (packed too: ldg = d) against the oracle, whatever kernels the dispatcher picks."""
+    seen = set()
+    for params, n, seed in _random_cases_wide(60, 77):
+        print("random wide", params, n, seed, dtype, flush=True)
+        g = torch.Generator(device=DEV).manual_seed(seed % (2 ** 31))
+        A = torch.randn((params[0], n), generator=g, device=DEV).to(dtype)
+        sk = B.Sketch(*params, seed=seed)
+        S = O.build_csc(O.Params(*params), seed)
+        ref = O.apply(S, host64(A))
+        out = sk.apply(A)
+        i = sk.info()
+        seen.add(("cols", i.last_variant, i.last_mode, sk.plan(n, dtype, address=A.data_ptr())["flags"]))
+        check(out, ref, dtype, f"{params} n={n}")
+        G = A.t().contiguous()
+        out_r = sk.apply_rows(G)
+        seen.add(("rows", sk.info().last_variant, sk.plan(n, dtype, rows=True, address=G.data_ptr())["flags"]))
+        check(out_r.t(), ref, dtype, f"rows {params} n={n}")
+        sk.close()
+    torch.cuda.synchronize()
+    flags = {f for key in seen if key[0] == "cols" for f in (key[3],)}
+    assert any(f & B.PLAN_ELEMENT_LOADS for f in flags) and any(f & B.PLAN_SLOT_GROUPS for f in flags) \
+        and any(f & B.PLAN_ROW_SLICES for f in flags), seen
+    assert ("cols", B.VARIANT_GENERIC, 0, 0) in seen
+
+
 @pytest.mark.parametrize("variant", [B.VARIANT_AUTO, B.VARIANT_GENERIC], ids=lambda v: VNAME[v])
 @DTYPES
 def test_random_shapes_match_oracle(dtype, variant):
