@@ -18,7 +18,8 @@ namespace fs {
 constexpr int kGenericLdsBytes = 64 * 1024;
 constexpr int kRowUnroll = 8;
 
-template <typename T, bool POW2>
+// ONEPASS: the whole block height fits the LDS tile (one row pass), so no update is filtered.
+template <typename T, bool POW2, bool ONEPASS>
 __global__ __launch_bounds__(256) void generic_kernel(SketchParams p, const T* __restrict__ A,
                                                       int64_t lda, int n, T* __restrict__ out,
                                                       int64_t ldo, int rows_per_pass) {
@@ -66,13 +67,14 @@ __global__ __launch_bounds__(256) void generic_kernel(SketchParams p, const T* _
         rh.signs = (uint32_t)__builtin_amdgcn_readlane((int)lane_rh.signs, src_lane);
         uint32_t r = rh.shift;
         for (uint32_t i = 0; i < p.s; ++i) {
-          const uint32_t rel = r - r0;
-          if (rel < R) {
+          const uint32_t rel = ONEPASS ? r : r - r0;
+          if (ONEPASS || rel < R) {
             const float x = ((rh.signs >> i) & 1u) ? -v[q] : v[q];
             sY[rel * tn + tid] += x;
           }
           r += rh.stride;
-          if (r >= p.Br) r -= p.Br;
+          if (POW2) r &= p.Br - 1;
+          else if (r >= p.Br) r -= p.Br;
         }
       }
     }
@@ -92,7 +94,7 @@ __global__ __launch_bounds__(256) void generic_kernel(SketchParams p, const T* _
 // LDS so that consecutive threads store consecutive elements of one output row.
 constexpr int kChunk = 32;
 
-template <typename T, bool POW2>
+template <typename T, bool POW2, bool ONEPASS>
 __global__ __launch_bounds__(128) void generic_rows_kernel(SketchParams p, const T* __restrict__ G,
                                                            int64_t ldg, int n, T* __restrict__ out,
                                                            int64_t ldo, int rows_per_pass) {
@@ -146,10 +148,11 @@ __global__ __launch_bounds__(128) void generic_rows_kernel(SketchParams p, const
         rh.signs = (uint32_t)__builtin_amdgcn_readlane((int)lane_rh.signs, q);
         uint32_t r = rh.shift;
         for (uint32_t i = 0; i < p.s; ++i) {
-          const uint32_t rel = r - r0;
-          if (rel < R) sY[rel * ld + tid] += ((rh.signs >> i) & 1u) ? -v : v;
+          const uint32_t rel = ONEPASS ? r : r - r0;
+          if (ONEPASS || rel < R) sY[rel * ld + tid] += ((rh.signs >> i) & 1u) ? -v : v;
           r += rh.stride;
-          if (r >= p.Br) r -= p.Br;
+          if (POW2) r &= p.Br - 1;
+          else if (r >= p.Br) r -= p.Br;
         }
       }
     }
@@ -173,8 +176,15 @@ hipError_t launch_generic_rows(const SketchParams& p, const void* G, int64_t ldg
   if (ex_tiles > 65535 || passes > 65535u) return hipErrorInvalidValue;
   dim3 grid(p.M, (unsigned)ex_tiles, passes), block(te);
   const size_t lds = (size_t)(kChunk + rows_per_pass) * ld * 4;
-#define FS_GO(T, P2) \
-  hipLaunchKernelGGL((generic_rows_kernel<T, P2>), grid, block, lds, st, p, (const T*)G, ldg, (int)n, (T*)out, ldo, rows_per_pass)
+#define FS_GO(T, P2)                                                                                         \
+  do {                                                                                                       \
+    if (passes == 1)                                                                                         \
+      hipLaunchKernelGGL((generic_rows_kernel<T, P2, true>), grid, block, lds, st, p, (const T*)G, ldg,      \
+                         (int)n, (T*)out, ldo, rows_per_pass);                                               \
+    else                                                                                                     \
+      hipLaunchKernelGGL((generic_rows_kernel<T, P2, false>), grid, block, lds, st, p, (const T*)G, ldg,     \
+                         (int)n, (T*)out, ldo, rows_per_pass);                                               \
+  } while (0)
   if (ev.start) (void)hipEventRecord(ev.start, st);
   if (dt == FS_F32)       { if (p.br_pow2) FS_GO(float, true); else FS_GO(float, false); }
   else if (dt == FS_BF16) { if (p.br_pow2) FS_GO(uint16_t, true); else FS_GO(uint16_t, false); }
@@ -197,8 +207,15 @@ hipError_t launch_generic(const SketchParams& p, const void* A, int64_t lda, int
   if (jt > 65535u || passes > 65535u) return hipErrorInvalidValue;
   dim3 grid(p.M, jt, passes), block(tn);
   const size_t lds = (size_t)rows_per_pass * tn * 4;
-#define FS_GO(T, P2) \
-  hipLaunchKernelGGL((generic_kernel<T, P2>), grid, block, lds, st, p, (const T*)A, lda, (int)n, (T*)out, ldo, rows_per_pass)
+#define FS_GO(T, P2)                                                                                        \
+  do {                                                                                                      \
+    if (passes == 1)                                                                                        \
+      hipLaunchKernelGGL((generic_kernel<T, P2, true>), grid, block, lds, st, p, (const T*)A, lda, (int)n,  \
+                         (T*)out, ldo, rows_per_pass);                                                      \
+    else                                                                                                    \
+      hipLaunchKernelGGL((generic_kernel<T, P2, false>), grid, block, lds, st, p, (const T*)A, lda, (int)n, \
+                         (T*)out, ldo, rows_per_pass);                                                      \
+  } while (0)
   if (ev.start) (void)hipEventRecord(ev.start, st);
   if (dt == FS_F32)       { if (p.br_pow2) FS_GO(float, true); else FS_GO(float, false); }
   else if (dt == FS_BF16) { if (p.br_pow2) FS_GO(uint16_t, true); else FS_GO(uint16_t, false); }
