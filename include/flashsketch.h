@@ -25,14 +25,16 @@
  *              are the vectors being sketched.
  *   Pointers   A, out, rows, signs, S_dense and workspaces are DEVICE pointers
  *              owned by the caller.  Handles and fs_info are HOST objects.
- *   Alignment  A and out must be aligned to their element size.  The fast
- *              kernels additionally want 16-byte aligned bases and
- *              lda*sizeof(elt) a multiple of 16; otherwise a slower generic
- *              kernel is used (never an error).  When n is not a multiple of
- *              4 the fast kernels load, and discard, up to 3 elements of a
- *              row's own padding (columns n .. lda-1, inside the aligned
- *              4-element group of the row's last valid element); their
- *              values, NaN included, never reach the result.
+ *   Alignment  A and out must be aligned to their element size.  The matrix-core
+ *              kernels load 4 columns per lane as one vector when A and lda are
+ *              aligned to 4 elements; otherwise they load element by element,
+ *              about half as fast (never an error).  With vector loads and n not
+ *              a multiple of 4, up to 3 elements of a row's own padding (columns
+ *              n .. lda-1, inside the aligned 4-element group of the row's last
+ *              valid element) are loaded and discarded; their values, NaN
+ *              included, never reach the result.  Element loads read nothing
+ *              beyond column n-1.  Stores to out are vectors when out and ldo are
+ *              aligned to 4 elements, else element by element.
  *   Streams    `stream` is a hipStream_t passed as void* (NULL = default
  *              stream).  Calls enqueue work and return; they never synchronise.
  *              A handle must not be used from two streams at the same time
