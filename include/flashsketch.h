@@ -97,7 +97,9 @@ typedef enum {
   FS_VARIANT_AUTO = 0,    /* pick by shape/dtype/alignment                          */
   FS_VARIANT_GENERIC = 1, /* one lane per column, LDS-private output tile, any Br   */
   FS_VARIANT_MFMA = 2     /* +-1 operand on the matrix cores: any power-of-two Br
-                             and any Bc, kappa <= 128,
+                             (other Br while its kappa slots, each padded to the next
+                             power of two rows, fit 128 tile rows, or padded Br <= 64),
+                             any Bc, kappa <= 128,
                              64*ceil(Bc/64)*lda*sizeof(elt) < 2^31; about twice as fast
                              when A and lda are aligned to 4 columns (vector loads)  */
 } fs_variant;

@@ -10,7 +10,10 @@ encodes what the kernels of this library prefer, in that order:
   2. Br in {128, 64, 32}: the output-stationary matrix-core path (A read kappa times);
   3. Br in {16, 8, 4, 2, 1} with kappa*Br > 128: input-stationary in groups of 128/Br wiring
      slots (A read once per group);
-  4. any Br dividing k (generic kernel).
+  4. any other Br dividing k, closest to 32 first.  The column-layout matrix-core kernel still
+     takes it input-stationary when Br padded to the next power of two keeps kappa slots within
+     128 tile rows (or Br <= 64 padded, in slot groups); otherwise the general kernel runs.  The
+     path named for such a Br is what fs_sketch_plan reports for a packed 256-column call.
 
 subject to the sketch's own constraints: Br | k, M = k/Br = ceil(d/Bc), kappa <= M, s <= Br.
 For a given Br, Bc is the smallest multiple of 64 with ceil(d/Bc) = M when there is one (whole
@@ -26,6 +29,23 @@ def _bc_for(d: int, M: int, multiple: int):
     bc = -(-d // M)                      # ceil(d / M): the smallest Bc with ceil(d/Bc) <= M
     bc = -(-bc // multiple) * multiple   # round up
     return bc if -(-d // bc) == M else None
+
+
+def _planned_path(d, k, bc, br, kappa, s) -> str:
+    """The path the library's dispatcher would take (host-only query; nothing is launched)."""
+    import torch
+
+    from . import binding as B
+    sk = B.Sketch(d, k, bc, br, kappa, s)
+    try:
+        p = sk.plan(256, torch.bfloat16)
+    finally:
+        sk.close()
+    if p["variant"] != B.VARIANT_MFMA:
+        return "generic"
+    if p["flags"] & B.PLAN_SLOT_GROUPS:
+        return "grouped"
+    return "out" if p["mode"] == 1 else "in"
 
 
 def suggest_blocks(d: int, k: int, kappa: int, s: int = 2):
@@ -56,7 +76,7 @@ def suggest_blocks(d: int, k: int, kappa: int, s: int = 2):
                     return bc, br, path
     for br in sorted((b for b in range(1, min(k, 65536) + 1) if k % b == 0), key=lambda b: abs(b - 32)):
         if ok(br):
-            bc = _bc_for(d, k // br, 1)
+            bc = _bc_for(d, k // br, 64) or _bc_for(d, k // br, 1)
             if bc is not None:
-                return bc, br, "generic"
+                return bc, br, _planned_path(d, k, bc, br, kappa, s)
     raise ValueError(f"no block grid for d={d}, k={k}, kappa={kappa}, s={s}")

@@ -78,7 +78,11 @@ Plan make_plan(const SketchParams& p, const void* A, int64_t lda, int64_t n, fs_
                bool have_orbit) {
   Plan pl;
   const size_t esz = dt == FS_F32 ? 4 : 2;
-  if (!p.br_pow2 || p.kappa > (uint32_t)MAX_KAPPA || n < 1) return pl;
+  if (p.kappa > (uint32_t)MAX_KAPPA || n < 1) return pl;
+  // Br not a power of two: input-stationary only, a slot padded to the next power of two rows
+  uint32_t brp = 1;
+  while (brp < p.Br) brp <<= 1;
+  if (!p.br_pow2 && brp > 128) return pl;
   const int64_t blk_stages = ((int64_t)p.Bc + KC - 1) / KC;  // the last one may be partly filled
   if ((uintptr_t)A % esz) return pl;
   pl.unal = (uintptr_t)A % (4 * esz) || (lda * esz) % (4 * esz);  // no 4-column vector loads
@@ -90,16 +94,16 @@ Plan make_plan(const SketchParams& p, const void* A, int64_t lda, int64_t n, fs_
 
   int mt_i = 0, nrg_i = 0, mt_o = 0, nrg_o = 0;
   // IN: the kappa*Br stacked rows sit in the smallest tile that holds them (rows above them idle)
-  const uint64_t rw = (uint64_t)p.kappa * p.Br;
+  const uint64_t rw = (uint64_t)p.kappa * brp;
   // OUT: blocks of 32, 64 or 128 rows, or 128-row slices of a higher (power-of-two) block
   const int nsub = p.Br > 128 ? (int)(p.Br / 128) : 1;
-  const bool can_out = tile_shape(p.Br > 128 ? 128 : p.Br, &mt_o, &nrg_o);
-  // More stacked rows than the highest tile and blocks too small for OUT: groups of 128/Br slots,
-  // each a work-group of its own that reads the input block again.
-  const bool grouped = rw > 128 && !can_out && p.Br < 32;
+  const bool can_out = p.br_pow2 && tile_shape(p.Br > 128 ? 128 : p.Br, &mt_o, &nrg_o);
+  // More stacked rows than the highest tile and blocks too small for OUT (or not a power of two):
+  // groups of 128/Br slots, each a work-group of its own that reads the input block again.
+  const bool grouped = rw > 128 && !can_out && brp <= 64;
   const bool can_in = (rw <= 128 || grouped) && tile_shape(rw <= 32 ? 32 : rw <= 64 ? 64 : 128, &mt_i, &nrg_i);
   if (!can_in && !can_out) return pl;
-  const int group_slots = grouped ? (int)(128 / p.Br) : (int)p.kappa;
+  const int group_slots = grouped ? (int)(128 / brp) : (int)p.kappa;
   const int groups = (int)((p.kappa + group_slots - 1) / group_slots);
 
   // IN-stationary row split: more work-groups fill the chip better, but every split adds kappa
@@ -138,7 +142,7 @@ Plan make_plan(const SketchParams& p, const void* A, int64_t lda, int64_t n, fs_
     // per CU, and a merge buffer that fits beside nothing else in LDS
     constexpr int R = 4;
     const size_t merge = (size_t)(p.kappa + R - 1) * p.Br * (WCOLS * 2) * 4;
-    if (have_orbit && !pl.unal && zs == 1 && rw == 64 && pl.nrg == 1 && pl.ncg == 2 && p.kappa > 1 &&
+    if (have_orbit && p.br_pow2 && !pl.unal && zs == 1 && rw == 64 && pl.nrg == 1 && pl.ncg == 2 && p.kappa > 1 &&
         p.M % R == 0 && (int64_t)(p.M / R) * col_tiles >= 256 && merge <= 100 * 1024) {
       pl.run = R;
       pl.planes = (int)((p.kappa + R - 2) / R) + 1;

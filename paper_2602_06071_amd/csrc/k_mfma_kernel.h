@@ -170,6 +170,19 @@ void mfma_kernel(MfmaArgs a) {
   const uint32_t row_lo = SUB ? slice * RWV : (uint32_t)rg * RWV;
   // `whole`: the slot lies entirely inside this wave's rows, so no nonzero is filtered out.
   auto scatter = [&](uint16_t* phi, uint32_t key, uint32_t u, uint32_t slot_row0, bool whole) {
+    if (!p.br_pow2) {
+      // (wave-uniform; IN only) Br not a power of two: a slot takes 2^log2_br >= Br tile rows, of
+      // which the first Br are used; the general row hash, and the wrap as a compare
+      const RowHash rg_ = row_hash_any(key, u, p.Br);
+      uint32_t rr = rg_.shift;
+      for (uint32_t i = 0; i < p.s; ++i) {
+        phi[__umul24(slot_row0 - row_lo + rr, (uint32_t)PHI_LD) + lane] =
+            (uint16_t)(((rg_.signs >> i) << 15) | Fmt<T>::one);
+        rr += rg_.stride;
+        if (rr >= p.Br) rr -= p.Br;
+      }
+      return;
+    }
     const RowHash rh = row_hash_pow2(key, u, p.Br);
     uint32_t r = rh.shift;
     // tile index of (row, lane) = row*72 + lane (24-bit multiply-add); the stored half-word is
@@ -617,8 +630,8 @@ void mfma_kernel(MfmaArgs a) {
         if (colq >= a.n) continue;
         float v[4] = {acc[mt][4 * q][i], acc[mt][4 * q + 1][i], acc[mt][4 * q + 2][i], acc[mt][4 * q + 3][i]};
         if (IN_STAT) {
-          const uint32_t slot = row_s >> lbr, r = row_s & (p.Br - 1);
-          if (slot >= kap) continue;  // fewer stacked rows than the tile is high: idle rows
+          const uint32_t slot = row_s >> lbr, r = row_s & ((1u << lbr) - 1u);
+          if (slot >= kap || r >= p.Br) continue;  // idle rows: above the stacked slots, or above Br in a slot
           const int64_t plane = (int64_t)z * p.kappa + slot0 + slot;
           float* dst = a.ws + (plane * p.k + (int64_t)s_blk[slot] * p.Br + r) * a.ldw + colq;
           *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);

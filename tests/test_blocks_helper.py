@@ -16,7 +16,8 @@ from paper_2602_06071_amd.blocks import suggest_blocks
     (16384, 1024, 8, 32, "out"),       # s = 32 needs Br >= 32: output-stationary
     (65536, 4096, 1, 8, "in"),
     (4000, 256, 2, 4, "in"),           # d not a multiple of the block: padded grid
-    (1000, 90, 3, 5, "generic"),       # k has no power-of-two block
+    (1000, 90, 3, 5, "in"),            # k = 90: Br = 30, three slots of 32 tile rows
+    (5000, 7 * 97, 2, 8, "generic"),   # k = 679: Br = 97 padded to 128 rows, twice
     (49152, 768, 3, 4, "in"),          # kappa = 3: 96 stacked rows in a 128-row tile
     (16896, 528, 32, 8, "grouped"),    # k = 16 * 33, s = 8: no block of 32 rows or more, kappa*16 = 512
     (1000, 384, 2, 4, "in"),           # M = 12: no multiple of 64 gives 12 blocks, Bc = 84
@@ -29,7 +30,8 @@ def test_suggestions_are_valid_and_on_the_named_path(d, k, kappa, s, want):
     p.check()                                        # the oracle's statement of the constraints
     assert k % Br == 0 and math.ceil(d / Bc) == k // Br and kappa <= k // Br and s <= Br
     if path == "in":
-        assert kappa * Br <= 128 and Br & (Br - 1) == 0 and (Bc % 64 == 0 or Bc == -(-d // (k // Br)))
+        padded = 1 << (Br - 1).bit_length()
+        assert kappa * padded <= 128 and (Bc % 64 == 0 or Bc == -(-d // (k // Br)))
     if path == "grouped":
         assert Br in (1, 2, 4, 8, 16) and kappa * Br > 128 and (Bc % 64 == 0 or Bc == -(-d // (k // Br)))
     if path == "out":

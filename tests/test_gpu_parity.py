@@ -141,6 +141,11 @@ SMALL = [
     ((8192, 1024, 512, 64, 4, 8), 250, 1, 0),       # output-stationary, lda = 251
     ((16384, 1024, 2048, 128, 4, 8), 130, 1, 3),    # 128-row tiles, lda = 131
     ((4001, 256, 512, 32, 2, 4), 77, 0, 0),         # and a partly filled last block
+    # Br not a power of two: a slot takes the next power of two of tile rows (column layout)
+    ((512, 768, 64, 96, 1, 8), 130, 2, 0),          # Br = 96, kappa = 1: 96 of 128 rows
+    ((1024, 768, 64, 48, 2, 5), 256, 0, 0),         # Br = 48, kappa = 2: two slots of 64
+    ((1024, 768, 64, 48, 4, 5), 64, 0, 4),          # the same with kappa = 4: groups of two slots
+    ((4800, 600, 200, 25, 3, 25), 100, 0, 0),       # Br = 25 = s, Bc = 200
     # output blocks higher than the 128-row tile: 128-row slices
     ((4096, 1024, 1024, 256, 2, 8), 300, 0, 0),     # Br = 256
     ((8192, 4096, 1024, 512, 3, 32), 130, 2, 0),    # Br = 512, s = 32
@@ -299,9 +304,9 @@ def test_mfma_modes_are_the_intended_ones():
 
 
 def test_forced_variant_on_unsupported_shape_reports_unsupported():
-    sk = B.Sketch(1152, 72, 96, 6, 5, 3)  # Br not a power of two
+    sk = B.Sketch(256, 384, 64, 96, 2, 4)  # Br = 96 (not a power of two) with kappa = 2: 256 padded rows
     sk.set_variant(B.VARIANT_MFMA)
-    A = torch.zeros((1152, 8), device=DEV)
+    A = torch.zeros((256, 8), device=DEV)
     with pytest.raises(B.FlashSketchError) as e:
         sk.apply(A)
     assert e.value.status == 2
@@ -778,7 +783,7 @@ def _random_cases_wide(count, seed):
     rng = np.random.default_rng(seed)
     cases = []
     while len(cases) < count:
-        Br = int(rng.choice([1, 2, 4, 8, 16, 32, 64, 128, 256, 512, 6, 48]))
+        Br = int(rng.choice([1, 2, 4, 8, 16, 32, 64, 128, 256, 512, 6, 48, 96]))
         M = int(rng.choice([1, 2, 3, 4, 8, 16, 40, 64, 130]))
         Bc = int(rng.choice([8, 40, 64, 72, 96, 125, 128, 200, 256, 500]))
         kappa = int(rng.integers(1, min(M, 40) + 1))
@@ -844,7 +849,7 @@ def test_random_shapes_match_oracle(dtype, variant):
             assert np.array_equal(signs.cpu().numpy(), want_s)
     if variant == B.VARIANT_AUTO:
         assert {m for v, m in modes if v == B.VARIANT_MFMA} >= {1, 2}, modes  # both MFMA modes were hit
-        assert (B.VARIANT_GENERIC, 0) in modes
+        assert all(v == B.VARIANT_MFMA for v, m in modes), modes   # every draw has a matrix-core kernel
 
 
 # ------------------------------------------------ FlashBlockRow kind ------

@@ -48,7 +48,9 @@ def test_the_five_configurations_take_the_decompositions_they_were_designed_for(
     ((1000, 256, 125, 32, 2, 4), 300, {}, (MFMA, IN, None)),             # Bc = 125
     ((4096, 256, 512, 32, 2, 4), 301, {}, (MFMA, IN, EL | SP)),          # lda = 301
     ((4096, 256, 512, 32, 2, 4), 300, {"address": 258}, (MFMA, IN, EL | SP)),   # A not aligned to 4 columns
-    ((1152, 72, 96, 6, 5, 3), 65, {}, (GENERIC, 0, 0)),                  # Br = 6
+    ((1152, 72, 96, 6, 5, 3), 65, {}, (MFMA, IN, None)),                 # Br = 6: slots of 8 tile rows
+    ((1440, 180, 80, 10, 18, 10), 36, {}, (MFMA, IN, GR)),               # Br = 10: slots of 16, groups of 8
+    ((256, 384, 64, 96, 2, 4), 64, {}, (GENERIC, 0, 0)),                 # Br = 96, kappa = 2: 256 padded rows
     ((16640, 4160, 64, 16, 130, 1), 64, {}, (GENERIC, 0, 0)),            # kappa = 130
 ])
 def test_column_layout_dispatch(params, n, kw, want):
@@ -98,7 +100,7 @@ def test_plan_honours_the_forced_variant_and_reports_errors():
     assert L.fs_sketch_plan(h, a, 64, 0, 0, 0, C.byref(v), None, None, None) == 0 and v.value == GENERIC  # n = 0
     assert L.fs_sketch_plan(h, a, 64, 64, 0, 0, None, None, None, None) == 0               # every result optional
     sk.close()
-    odd = B.Sketch(1152, 72, 96, 6, 5, 3)
+    odd = B.Sketch(256, 384, 64, 96, 2, 4)   # Br = 96 with kappa = 2: no matrix-core kernel
     odd.set_variant(MFMA)
     with pytest.raises(B.FlashSketchError) as e:
         odd.plan(8, torch.float32)
