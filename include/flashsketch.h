@@ -156,7 +156,7 @@ fs_status fs_sketch_apply_ld(fs_sketch_t h, const void* A, int64_t lda, int64_t 
  * out (n x k, ld = ldo >= k) = G S^T, i.e. out[i, :] = S G[i, :] -- the transpose of what
  * fs_sketch_apply_ld computes on G^T.  FS_KIND_BLOCKPERM only.  Two kernels, chosen as for
  * fs_sketch_apply (fs_sketch_set_variant applies here too):
- *  - matrix cores: needs a power-of-two Br.  kappa*Br <= 128 is input-stationary (G is read
+ *  - matrix cores: Br a power of two (else see FS_VARIANT_MFMA).  kappa*Br <= 128 is input-stationary (G is read
  *    once; fastest when kappa*Br is exactly 32, 64 or 128, the heights of its tiles); beyond
  *    that Br >= 32 is output-stationary (G is read kappa times, mostly from L2; blocks higher
  *    than 128 rows in 128-row slices) and smaller Br input-stationary in groups of 128/Br
@@ -166,7 +166,8 @@ fs_status fs_sketch_apply_ld(fs_sketch_t h, const void* A, int64_t lda, int64_t 
  *    bytes (128-bit loads; otherwise four dword loads or, for an odd ldg of a 16-bit type,
  *    eight element loads per piece).  A row stride that is a large power of two maps the
  *    rows of a tile to one HBM channel: prefer ldg = d + 64 elements.
- *  - general: every other valid sketch (Br not a power of two, kappa > 128);
+ *  - general: every other valid sketch (kappa > 128; Br not a power of two with more than 128
+ *    padded rows);
  *    tiles are turned through LDS and accumulated without atomics, G is read kappa times.
  * Forcing FS_VARIANT_MFMA on a call the matrix-core kernel cannot take returns
  * FS_ERR_UNSUPPORTED (nothing is launched).

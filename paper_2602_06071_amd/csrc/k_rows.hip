@@ -251,6 +251,19 @@ void rows_kernel(RowsArgs a) {
     }
     const uint32_t u = (uint32_t)(z * T_stages + t) * KC + lane;
     if (u >= p.Bc) return;  // past the block
+    if (!p.br_pow2) {  // (wave-uniform) slots of 2^lbr >= Br rows; the general row hash, wrap by compare
+      for (uint32_t slot = part; slot < kap; slot += KSTEPS) {
+        const RowHash rh = row_hash_any(s_bk[slot], u, p.Br);
+        uint32_t r = rh.shift;
+        const uint32_t base = slot << lbr;
+        for (uint32_t i = 0; i < p.s; ++i) {
+          s_phi[__umul24(base + r, (uint32_t)PHI_LD) + lane] = (uint16_t)(((rh.signs >> i) << 15) | Fmt<T>::one);
+          r += rh.stride;
+          if (r >= p.Br) r -= p.Br;
+        }
+      }
+      return;
+    }
     for (uint32_t slot = part; slot < kap; slot += KSTEPS) {
       const RowHash rh = row_hash_pow2(s_bk[slot], u, p.Br);
       uint32_t r = rh.shift;
@@ -407,7 +420,10 @@ __global__ __launch_bounds__(256) void reduce_rows_kernel(const float* __restric
   if (idx >= (int64_t)n * q) return;
   const int64_t ex = idx / q;
   const uint32_t col0 = (uint32_t)(idx % q) * VEC;
-  const uint32_t bi = col0 >> lbr, r = col0 & (p.Br - 1);  // orbit position (or block) and row in block
+  // orbit position (or block) and row in block; lbr = log2 of the rows a slot takes in a record
+  // (Br, or the next power of two when Br is not one)
+  const uint32_t bi = p.br_pow2 ? col0 >> lbr : col0 / p.Br;
+  const uint32_t r = p.br_pow2 ? col0 & (p.Br - 1) : col0 - bi * p.Br;
   const uint32_t g = orbit ? orbit[bi] : bi;
   const int64_t z_stride = (int64_t)n * p.M * rw;
   const float* src = part + ex * (int64_t)p.M * rw + r;
@@ -429,7 +445,7 @@ __global__ __launch_bounds__(256) void reduce_rows_kernel(const float* __restric
       }
     }
   }
-  T* dst = out + ex * ldo + ((int64_t)g << lbr) + r;
+  T* dst = out + ex * ldo + (int64_t)g * p.Br + r;
 #pragma unroll
   for (int c = 0; c < VEC; ++c) s[c] *= p.scale;
   if constexpr (VEC == 4) {
@@ -460,10 +476,14 @@ struct RowsPlan {
 RowsPlan make_rows_plan(const SketchParams& p, const void* G, int64_t ldg, int64_t n, fs_dtype dt) {
   RowsPlan pl;
   const size_t esz = dt == FS_F32 ? 4 : 2;
-  if (!p.br_pow2 || p.kappa > (uint32_t)MAX_KAPPA || n < 1) return pl;
+  if (p.kappa > (uint32_t)MAX_KAPPA || n < 1) return pl;
   const int64_t blk_stages = ((int64_t)p.Bc + KC - 1) / KC;  // the last one may be partly filled
-  const uint64_t rw = (uint64_t)p.kappa * p.Br;
-  const bool br_tile = p.Br >= 32;  // a power of two: 32, 64, 128, or 128-row slices of a higher block
+  // Br not a power of two: input-stationary only, every slot padded to the next power of two
+  uint32_t brp = 1;
+  while (brp < p.Br) brp <<= 1;
+  if (!p.br_pow2 && brp > 128) return pl;
+  const uint64_t rw = (uint64_t)p.kappa * brp;
+  const bool br_tile = p.br_pow2 && p.Br >= 32;  // 32, 64, 128, or 128-row slices of a higher block
   const int out_mt = (int)(p.Br > 128 ? 128 : p.Br) / 32;
   const int out_nsub = p.Br > 128 ? (int)(p.Br / 128) : 1;
   if (p.kappa == 1 && br_tile) {  // nothing is re-read: output-stationary stores the result directly
@@ -473,9 +493,9 @@ RowsPlan make_rows_plan(const SketchParams& p, const void* G, int64_t ldg, int64
   } else if (rw <= 32) { pl.mt = 1; pl.et = 4; }   // the smallest tile that holds the stacked rows
   else if (rw <= 64) { pl.mt = 2; pl.et = 4; }
   else if (rw <= 128) { pl.mt = 4; pl.et = 4; }
-  else if (p.Br < 32) {  // more stacked rows than the highest tile, blocks too small for OUT:
+  else if (p.br_pow2 ? p.Br < 32 : brp <= 64) {  // more stacked rows than the highest tile, no OUT for them:
     pl.mt = 4; pl.et = 4;  // groups of 128/Br slots, G read once per group
-    pl.group_slots = (int)(128 / p.Br);
+    pl.group_slots = (int)(128 / brp);
     pl.groups = (int)((p.kappa + pl.group_slots - 1) / pl.group_slots);
   } else if (br_tile) {  // too many stacked rows: output-stationary
     pl.out_stat = true;

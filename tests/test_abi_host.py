@@ -131,7 +131,7 @@ def test_apply_argument_errors_before_any_hip_call():
     assert out.value >= one_set and out.value % one_set == 0                  # times the row split
     assert L.fs_sketch_rows_workspace_bytes(h, -1, 0, C.byref(out)) == 1
     sk.close()
-    big = B.Sketch(4096, 384, 64, 6, 4, 2)                                    # Br = 6: not a power of two
+    big = B.Sketch(4096, 6144, 64, 96, 2, 4)                                  # Br = 96, kappa = 2: 256 padded rows
     big.set_variant(B.VARIANT_MFMA)
-    assert L.fs_sketch_apply_rows(big._h, buf, 4096, 8, buf, 384, 0, None) == 2
+    assert L.fs_sketch_apply_rows(big._h, buf, 4096, 8, buf, 6144, 0, None) == 2
     big.close()

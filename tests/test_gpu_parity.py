@@ -644,10 +644,15 @@ ROWS = [
     ((4096, 1024, 1024, 256, 2, 8), 129, 0, 0),     # Br = 256
     ((8192, 4096, 1024, 512, 3, 32), 70, 2, 0),     # Br = 512, s = 32
     ((2048, 2048, 1024, 1024, 1, 16), 40, 0, 4),    # Br = 1024, kappa = 1
-    # shapes only the general kernel takes
+    # Br not a power of two: slots padded to the next power of two of tile rows
     ((1152, 72, 96, 6, 5, 3), 70, 1, 3),            # Br = 6, M = 12, odd row stride
-    ((1440, 180, 80, 10, 18, 10), 5, 0, 0),         # kappa = M, s = Br = 10
+    ((1440, 180, 80, 10, 18, 10), 5, 0, 0),         # kappa = M, s = Br = 10: slot groups
     ((1440, 180, 80, 10, 18, 10), 130, 2, 0),       # the same over two example tiles
+    ((1024, 768, 64, 48, 2, 5), 100, 0, 0),         # Br = 48: vector reduction, two slots of 64
+    ((512, 768, 64, 96, 1, 8), 64, 0, 4),           # Br = 96, kappa = 1
+    # shapes only the general kernel takes
+    ((256, 384, 64, 96, 2, 4), 70, 0, 0),           # Br = 96, kappa = 2: 256 padded rows
+    ((8320, 4160, 64, 32, 130, 1), 40, 0, 0),       # kappa = 130
 ]
 
 
@@ -703,8 +708,8 @@ def test_apply_rows_one_hot_rows_reproduce_columns_exactly():
 def test_apply_rows_forced_matrix_core_variant_reports_unsupported_shapes():
     """Shapes the matrix-core rows kernel cannot take run on the general one; forcing the
     matrix-core variant turns them into FS_ERR_UNSUPPORTED instead."""
-    for params in [(8192, 384, 128, 6, 4, 2),        # Br = 6: not a power of two
-                   (7680, 1200, 64, 10, 4, 2)]:      # Br = 10
+    for params in [(256, 384, 64, 96, 2, 4),         # Br = 96, kappa = 2: 256 padded rows
+                   (8320, 4160, 64, 32, 130, 1)]:    # kappa = 130
         G = torch.zeros((4, params[0]), device=DEV, dtype=torch.bfloat16)
         sk = B.Sketch(*params, seed=0)
         sk.apply_rows(G)

@@ -74,7 +74,8 @@ def test_column_layout_dispatch(params, n, kw, want):
     ((8192, 2048, 64, 16, 16, 2), 33, torch.float32, {}, (MFMA, IN, GR)),
     ((1000, 256, 125, 32, 2, 4), 70, torch.bfloat16, {}, (MFMA, IN, EL)),      # blocks start at odd entries
     ((1000, 256, 125, 32, 2, 4), 70, torch.float32, {}, (MFMA, IN, EL)),       # 500-byte blocks: dword loads
-    ((1152, 72, 96, 6, 5, 3), 70, torch.float32, {}, (GENERIC, 0, 0)),
+    ((1152, 72, 96, 6, 5, 3), 70, torch.float32, {}, (MFMA, IN, 0)),          # Br = 6: slots of 8 tile rows
+    ((256, 384, 64, 96, 2, 4), 70, torch.float32, {}, (GENERIC, 0, 0)),       # 256 padded rows
 ])
 def test_rows_layout_dispatch(params, n, dtype, kw, want):
     p = plan(params, n, dtype, rows=True, **kw)
