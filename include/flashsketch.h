@@ -156,8 +156,9 @@ fs_status fs_sketch_apply_ld(fs_sketch_t h, const void* A, int64_t lda, int64_t 
  * out (n x k, ld = ldo >= k) = G S^T, i.e. out[i, :] = S G[i, :] -- the transpose of what
  * fs_sketch_apply_ld computes on G^T.  FS_KIND_BLOCKPERM only.  Two kernels, chosen as for
  * fs_sketch_apply (fs_sketch_set_variant applies here too):
- *  - matrix cores: Br a power of two (else see FS_VARIANT_MFMA).  kappa*Br <= 128 is input-stationary (G is read
- *    once; fastest when kappa*Br is exactly 32, 64 or 128, the heights of its tiles); beyond
+ *  - matrix cores: Br a power of two (else see FS_VARIANT_MFMA).  kappa*Br <= 128 is
+ *    input-stationary (G is read once; fastest when kappa*Br is exactly 32, 64 or 128, the
+ *    heights of its tiles); beyond
  *    that Br >= 32 is output-stationary (G is read kappa times, mostly from L2; blocks higher
  *    than 128 rows in 128-row slices) and smaller Br input-stationary in groups of 128/Br
  *    wiring slots (G is read once per group).  Also needs 130*ldg*sizeof(elt) < 2^31 (input-stationary: 34*ldg*sizeof(elt));
