@@ -146,6 +146,7 @@ SMALL = [
     ((1024, 768, 64, 48, 2, 5), 256, 0, 0),         # Br = 48, kappa = 2: two slots of 64
     ((1024, 768, 64, 48, 4, 5), 64, 0, 4),          # the same with kappa = 4: groups of two slots
     ((4800, 600, 200, 25, 3, 25), 100, 0, 0),       # Br = 25 = s, Bc = 200
+    ((8192, 48, 1024, 6, 4, 2), 64, 0, 0),          # Br = 6 with few, long blocks: split rows
     # output blocks higher than the 128-row tile: 128-row slices
     ((4096, 1024, 1024, 256, 2, 8), 300, 0, 0),     # Br = 256
     ((8192, 4096, 1024, 512, 3, 32), 130, 2, 0),    # Br = 512, s = 32
@@ -650,6 +651,7 @@ ROWS = [
     ((1440, 180, 80, 10, 18, 10), 130, 2, 0),       # the same over two example tiles
     ((1024, 768, 64, 48, 2, 5), 100, 0, 0),         # Br = 48: vector reduction, two slots of 64
     ((512, 768, 64, 96, 1, 8), 64, 0, 4),           # Br = 96, kappa = 1
+    ((8192, 48, 1024, 6, 4, 2), 64, 0, 0),          # Br = 6 with few, long blocks: split rows
     # shapes only the general kernel takes
     ((256, 384, 64, 96, 2, 4), 70, 0, 0),           # Br = 96, kappa = 2: 256 padded rows
     ((8320, 4160, 64, 32, 130, 1), 40, 0, 0),       # kappa = 130
