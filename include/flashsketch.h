@@ -99,7 +99,7 @@ typedef enum {
   FS_VARIANT_MFMA = 2     /* +-1 operand on the matrix cores: any power-of-two Br
                              (other Br while its kappa slots, each padded to the next
                              power of two rows, fit 128 tile rows, or padded Br <= 64),
-                             any Bc, kappa <= 128,
+                             any Bc, kappa <= 128 (more when Br <= 64),
                              64*ceil(Bc/64)*lda*sizeof(elt) < 2^31; about twice as fast
                              when A and lda are aligned to 4 columns (vector loads)  */
 } fs_variant;
@@ -167,8 +167,8 @@ fs_status fs_sketch_apply_ld(fs_sketch_t h, const void* A, int64_t lda, int64_t 
  *    bytes (128-bit loads; otherwise four dword loads or, for an odd ldg of a 16-bit type,
  *    eight element loads per piece).  A row stride that is a large power of two maps the
  *    rows of a tile to one HBM channel: prefer ldg = d + 64 elements.
- *  - general: every other valid sketch (kappa > 128; Br not a power of two with more than 128
- *    padded rows);
+ *  - general: every other valid sketch (more than 128 padded rows of blocks whose padded
+ *    height is 128 or more, with Br not a power of two or kappa > 128);
  *    tiles are turned through LDS and accumulated without atomics, G is read kappa times.
  * Forcing FS_VARIANT_MFMA on a call the matrix-core kernel cannot take returns
  * FS_ERR_UNSUPPORTED (nothing is launched).

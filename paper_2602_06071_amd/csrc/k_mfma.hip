@@ -78,7 +78,7 @@ Plan make_plan(const SketchParams& p, const void* A, int64_t lda, int64_t n, fs_
                bool have_orbit) {
   Plan pl;
   const size_t esz = dt == FS_F32 ? 4 : 2;
-  if (p.kappa > (uint32_t)MAX_KAPPA || n < 1) return pl;
+  if (n < 1) return pl;
   // Br not a power of two: input-stationary only, a slot padded to the next power of two rows
   uint32_t brp = 1;
   while (brp < p.Br) brp <<= 1;
@@ -97,7 +97,9 @@ Plan make_plan(const SketchParams& p, const void* A, int64_t lda, int64_t n, fs_
   const uint64_t rw = (uint64_t)p.kappa * brp;
   // OUT: blocks of 32, 64 or 128 rows, or 128-row slices of a higher (power-of-two) block
   const int nsub = p.Br > 128 ? (int)(p.Br / 128) : 1;
-  const bool can_out = p.br_pow2 && tile_shape(p.Br > 128 ? 128 : p.Br, &mt_o, &nrg_o);
+  // (its slot tables hold all kappa neighbours: at most MAX_KAPPA; the IN modes table one group)
+  const bool can_out = p.br_pow2 && p.kappa <= (uint32_t)MAX_KAPPA &&
+                       tile_shape(p.Br > 128 ? 128 : p.Br, &mt_o, &nrg_o);
   // More stacked rows than the highest tile and blocks too small for OUT (or not a power of two):
   // groups of 128/Br slots, each a work-group of its own that reads the input block again.
   const bool grouped = rw > 128 && !can_out && brp <= 64;

@@ -476,14 +476,15 @@ struct RowsPlan {
 RowsPlan make_rows_plan(const SketchParams& p, const void* G, int64_t ldg, int64_t n, fs_dtype dt) {
   RowsPlan pl;
   const size_t esz = dt == FS_F32 ? 4 : 2;
-  if (p.kappa > (uint32_t)MAX_KAPPA || n < 1) return pl;
+  if (n < 1) return pl;
   const int64_t blk_stages = ((int64_t)p.Bc + KC - 1) / KC;  // the last one may be partly filled
   // Br not a power of two: input-stationary only, every slot padded to the next power of two
   uint32_t brp = 1;
   while (brp < p.Br) brp <<= 1;
   if (!p.br_pow2 && brp > 128) return pl;
   const uint64_t rw = (uint64_t)p.kappa * brp;
-  const bool br_tile = p.br_pow2 && p.Br >= 32;  // 32, 64, 128, or 128-row slices of a higher block
+  // 32, 64, 128, or 128-row slices of a higher block (OUT tables all kappa neighbours: at most MAX_KAPPA)
+  const bool br_tile = p.br_pow2 && p.Br >= 32 && p.kappa <= (uint32_t)MAX_KAPPA;
   const int out_mt = (int)(p.Br > 128 ? 128 : p.Br) / 32;
   const int out_nsub = p.Br > 128 ? (int)(p.Br / 128) : 1;
   if (p.kappa == 1 && br_tile) {  // nothing is re-read: output-stationary stores the result directly
@@ -493,14 +494,14 @@ RowsPlan make_rows_plan(const SketchParams& p, const void* G, int64_t ldg, int64
   } else if (rw <= 32) { pl.mt = 1; pl.et = 4; }   // the smallest tile that holds the stacked rows
   else if (rw <= 64) { pl.mt = 2; pl.et = 4; }
   else if (rw <= 128) { pl.mt = 4; pl.et = 4; }
-  else if (p.br_pow2 ? p.Br < 32 : brp <= 64) {  // more stacked rows than the highest tile, no OUT for them:
-    pl.mt = 4; pl.et = 4;  // groups of 128/Br slots, G read once per group
-    pl.group_slots = (int)(128 / brp);
-    pl.groups = (int)((p.kappa + pl.group_slots - 1) / pl.group_slots);
-  } else if (br_tile) {  // too many stacked rows: output-stationary
+  else if (br_tile) {  // too many stacked rows: output-stationary
     pl.out_stat = true;
     pl.mt = out_mt; pl.nsub = out_nsub;
     pl.et = 4;
+  } else if (brp <= 64) {  // ... and no OUT for them (small blocks, Br not a power of two, kappa > 128):
+    pl.mt = 4; pl.et = 4;  // groups of 128/Br slots, G read once per group
+    pl.group_slots = (int)(128 / brp);
+    pl.groups = (int)((p.kappa + pl.group_slots - 1) / pl.group_slots);
   } else return pl;
   if ((uintptr_t)G % esz) return pl;
   // what every piece address G + example*ldg + block*Bc + 64*stage (in bytes) is a multiple of

@@ -141,6 +141,8 @@ SMALL = [
     ((8192, 1024, 512, 64, 4, 8), 250, 1, 0),       # output-stationary, lda = 251
     ((16384, 1024, 2048, 128, 4, 8), 130, 1, 3),    # 128-row tiles, lda = 131
     ((4001, 256, 512, 32, 2, 4), 77, 0, 0),         # and a partly filled last block
+    ((16640, 4160, 64, 16, 130, 1), 64, 0, 0),      # kappa = 130 > 128: 17 slot groups
+    ((8320, 4160, 64, 32, 130, 1), 40, 0, 0),       # the same with 32-row blocks: groups of four
     # Br not a power of two: a slot takes the next power of two of tile rows (column layout)
     ((512, 768, 64, 96, 1, 8), 130, 2, 0),          # Br = 96, kappa = 1: 96 of 128 rows
     ((1024, 768, 64, 48, 2, 5), 256, 0, 0),         # Br = 48, kappa = 2: two slots of 64
@@ -652,9 +654,10 @@ ROWS = [
     ((1024, 768, 64, 48, 2, 5), 100, 0, 0),         # Br = 48: vector reduction, two slots of 64
     ((512, 768, 64, 96, 1, 8), 64, 0, 4),           # Br = 96, kappa = 1
     ((8192, 48, 1024, 6, 4, 2), 64, 0, 0),          # Br = 6 with few, long blocks: split rows
+    ((8320, 4160, 64, 32, 130, 1), 40, 0, 0),       # kappa = 130 > 128: groups of four 32-row slots
     # shapes only the general kernel takes
     ((256, 384, 64, 96, 2, 4), 70, 0, 0),           # Br = 96, kappa = 2: 256 padded rows
-    ((8320, 4160, 64, 32, 130, 1), 40, 0, 0),       # kappa = 130
+    ((8320, 16640, 64, 128, 130, 1), 40, 0, 0),     # kappa = 130 with Br = 128
 ]
 
 
@@ -711,7 +714,7 @@ def test_apply_rows_forced_matrix_core_variant_reports_unsupported_shapes():
     """Shapes the matrix-core rows kernel cannot take run on the general one; forcing the
     matrix-core variant turns them into FS_ERR_UNSUPPORTED instead."""
     for params in [(256, 384, 64, 96, 2, 4),         # Br = 96, kappa = 2: 256 padded rows
-                   (8320, 4160, 64, 32, 130, 1)]:    # kappa = 130
+                   (8320, 16640, 64, 128, 130, 1)]:  # kappa = 130 with Br = 128
         G = torch.zeros((4, params[0]), device=DEV, dtype=torch.bfloat16)
         sk = B.Sketch(*params, seed=0)
         sk.apply_rows(G)

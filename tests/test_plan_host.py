@@ -51,7 +51,8 @@ def test_the_five_configurations_take_the_decompositions_they_were_designed_for(
     ((1152, 72, 96, 6, 5, 3), 65, {}, (MFMA, IN, None)),                 # Br = 6: slots of 8 tile rows
     ((1440, 180, 80, 10, 18, 10), 36, {}, (MFMA, IN, GR)),               # Br = 10: slots of 16, groups of 8
     ((256, 384, 64, 96, 2, 4), 64, {}, (GENERIC, 0, 0)),                 # Br = 96, kappa = 2: 256 padded rows
-    ((16640, 4160, 64, 16, 130, 1), 64, {}, (GENERIC, 0, 0)),            # kappa = 130
+    ((16640, 4160, 64, 16, 130, 1), 64, {}, (MFMA, IN, GR)),             # kappa = 130: 17 groups of 8 slots
+    ((8320, 16640, 64, 128, 130, 1), 64, {}, (GENERIC, 0, 0)),           # kappa = 130 with Br = 128
 ])
 def test_column_layout_dispatch(params, n, kw, want):
     p = plan(params, n, torch.bfloat16, **kw)
