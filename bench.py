@@ -25,8 +25,12 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
 # HBM bytes per launch of the dominant kernel on the default workload, from the rocprofv3
-# FETCH_SIZE / WRITE_SIZE runs summarised in profiles/blockperm_mfma_grad_bf16_chunk256.md
-MEASURED_TRAFFIC = {("grad", "mfma"): (2_097_533 + 22_528) * 1024}
+# FETCH_SIZE / WRITE_SIZE runs summarised in profiles/blockperm_mfma_grad_bf16_chunk256.md, with
+# the kernel instantiation they were measured on (fs_info.last_kernel): reported only while the
+# library still launches that instantiation for the workload, else null.
+MEASURED_TRAFFIC = {
+    "grad": ("mfma_kernel<bf16,2,1,2,in,4,4,1,-,->+reduce_planes", (2_097_533 + 22_528) * 1024),
+}
 
 
 def parse():
@@ -70,28 +74,73 @@ def time_workload(torch, B, cfg, A, variant, steps, warmup, kind=None, sketch_pa
     run_steps = functools.partial(globals()["run_steps"], rows=rows)
     run_steps(sk, A, out, cfg, warmup)
     torch.cuda.synchronize()
-    # HIP-event brackets around the dominant kernel on the last two timed steps only: every
-    # bracket costs ~2 us of queue time, so bracketing all launches would slow the timed region
-    # (the host runs far ahead of the GPU, so creating the events mid-loop stalls nothing)
-    n_brk = min(steps, 2)
+    # HIP-event brackets on the last four timed steps only: every recorded event costs a few
+    # microseconds of queue time, so bracketing all launches would slow the timed region.  Two
+    # steps bracket the whole apply (one pair around all its kernels, nothing in between), the last
+    # two the dominant kernel alone.  (The host runs far ahead of the GPU, so creating the events
+    # mid-loop stalls nothing.)
+    n_brk = min(steps // 2, 2)
+    n_l = len(chunks_of(cfg))
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    run_steps(sk, A, out, cfg, steps - n_brk)
-    sk.profile_begin(n_brk * len(chunks_of(cfg)))
-    run_steps(sk, A, out, cfg, n_brk)
+    run_steps(sk, A, out, cfg, steps - 2 * n_brk)
+    apply_ms = []
+    if n_brk:
+        sk.profile_begin(n_brk * n_l, B.PROFILE_APPLY)
+        run_steps(sk, A, out, cfg, n_brk)
+        apply_ms = sk.profile_end(whole=True)[1]     # (waits for those steps)
+        sk.profile_begin(n_brk * n_l, B.PROFILE_KERNEL)
+        run_steps(sk, A, out, cfg, n_brk)
+    else:
+        sk.profile_begin(steps * n_l)
+        run_steps(sk, A, out, cfg, steps)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    kernel_ms = sk.profile_end()
-    used = sk.info().last_variant
+    kernel_ms, both = sk.profile_end(whole=True)
+    apply_ms = apply_ms or both
+    info = sk.info()
     sk.close()
-    return (t1 - t0) / steps, kernel_ms, used, out
+    return Timing((t1 - t0) / steps, kernel_ms, apply_ms, info.last_variant, info.last_kernel.decode()), out
 
 
-def cpu_baseline(torch, cfg, A, budget_s=12.0, slice_cols=32):
-    """The float64 oracle, as it stands, on a bounded sample of the same workload:
-    the CSC product S @ A[:, cols] over leading column slices until ~budget_s of CPU
-    time is spent (each slice is widened to float64 on the host first)."""
+@dataclasses.dataclass
+class Timing:
+    sec_per_step: float      # wall clock
+    kernel_ms: list          # HIP events around the dominant kernel of each bracketed apply
+    apply_ms: list           # HIP events around everything each bracketed apply enqueued
+    variant: int
+    kernel: str              # fs_info.last_kernel
+
+    @property
+    def kernel_s(self):
+        return sum(self.kernel_ms) / len(self.kernel_ms) / 1e3
+
+    @property
+    def apply_s(self):
+        return sum(self.apply_ms) / len(self.apply_ms) / 1e3
+
+
+_POOL_STATE = {}
+
+
+def _pool_leg(j):
+    """One worker's share of the all-core leg: the oracle's product on its own column slice."""
     from oracle import blockperm as O
+    t0 = time.perf_counter()
+    Y = O.apply(_POOL_STATE["S"], _POOL_STATE["slices"][j])
+    return time.perf_counter() - t0, float(abs(Y).sum())
+
+
+def cpu_baseline(torch, cfg, A, budget_s=10.0, slice_cols=32):
+    """The float64 oracle, as it stands, on a bounded sample of the same workload, on the box's
+    own host cores.  Leg 1, one core: the CSC product S @ A[:, cols] over leading column slices
+    until ~budget_s of CPU time is spent (each slice is widened to float64 on the host first).
+    Leg 2, all cores the process may run on (os.sched_getaffinity): one slice of the same width
+    per core, each in a forked worker that runs the same single-threaded product (columns are
+    independent, so sharding them is all there is to a parallel oracle); wall clock of the slowest.
+    `value` is the all-core figure when that leg ran, else the one-core figure."""
+    from oracle import blockperm as O
+    import numpy as np
     t0 = time.perf_counter()
     S = O.build_csc(O.Params(*cfg.params), cfg.sketch_seed)
     t_build = time.perf_counter() - t0
@@ -103,15 +152,44 @@ def cpu_baseline(torch, cfg, A, budget_s=12.0, slice_cols=32):
         outs.append(O.apply(S, A_host))
         t_apply += time.perf_counter() - t0
         cols = c1
-    import numpy as np
     Y = np.concatenate(outs, axis=1)
-    gbps = cfg.d * cols * cfg.elt / t_apply / 1e9
-    return {
-        "value": gbps, "unit": "GB/s", "cores": 1, "kind": "oracle",
+    one = cfg.d * cols * cfg.elt / t_apply / 1e9
+    box_cores = len(os.sched_getaffinity(0))
+    res = {
+        "value": one, "unit": "GB/s", "cores": 1, "kind": "oracle",
         "sample": f"first {cols} of {cfg.n} columns of the same A (all {cfg.d} rows), float64 CSC product "
-                  f"{t_apply:.2f} s; building S as CSC took {t_build:.2f} s more and is not counted",
+                  f"{t_apply:.2f} s on one core; building S as CSC took {t_build:.2f} s more and is not counted",
         "cols_per_s": cols / t_apply,
-    }, Y, cols
+        "one_core": {"value": one, "cols_per_s": cols / t_apply, "seconds": t_apply, "columns": cols},
+        "host_cores_available": box_cores,
+    }
+    # all-core leg: up to 64 columns per core (2 GiB of float64 each at d = 4 M), fewer when there
+    # are not that many columns
+    try:
+        import multiprocessing as mp
+        per_core = max(1, min(64, cfg.n // max(1, box_cores)))
+        workers = min(box_cores, cfg.n // per_core)
+        if workers >= 2:
+            _POOL_STATE["S"] = S
+            _POOL_STATE["slices"] = [A[:, j * per_core:(j + 1) * per_core].to("cpu").to(torch.float64).numpy()
+                                     for j in range(workers)]
+            ctx = mp.get_context("fork")  # the workers only run NumPy / SciPy code on inherited host arrays
+            with ctx.Pool(workers) as pool:
+                pool.map(_pool_leg, range(workers), chunksize=1)  # spin the workers up (untimed)
+                t0 = time.perf_counter()
+                legs = pool.map_async(_pool_leg, range(workers), chunksize=1).get(timeout=180)
+                wall = time.perf_counter() - t0
+            allc = cfg.d * per_core * workers * cfg.elt / wall / 1e9
+            res.update({
+                "value": allc, "cores": workers, "cols_per_s": per_core * workers / wall,
+                "sample": res["sample"] + f"; all-core leg: {workers} forked workers x {per_core} columns each of the "
+                          f"same A, {wall:.2f} s wall (slowest worker {max(t for t, _ in legs):.2f} s)",
+                "all_cores": {"value": allc, "cores": workers, "seconds": wall, "columns": per_core * workers},
+            })
+            _POOL_STATE.clear()
+    except Exception as e:  # the one-core leg stands on its own
+        res["all_cores"] = {"error": f"{type(e).__name__}: {e}"}
+    return res, Y, cols
 
 
 def main():
@@ -138,15 +216,22 @@ def main():
         del A
         A = Gbuf[:, :cfg.d]
         torch.cuda.synchronize()
-    sec_per_step, kernel_ms, used, out = time_workload(torch, B, cfg, A, args.variant, args.steps, args.warmup,
-                                                       rows=rows)
+    tm, out = time_workload(torch, B, cfg, A, args.variant, args.steps, args.warmup, rows=rows)
+    sec_per_step, used = tm.sec_per_step, tm.variant
     n_launch = len(chunks_of(cfg))
     cols_per_launch = cfg.n // n_launch
     # algorithmic bytes of one launch: read its columns of A once, write its columns of SA once
     alg_bytes = cols_per_launch * (cfg.d * cfg.elt + cfg.k * cfg.elt)
-    avg_kernel_s = sum(kernel_ms) / len(kernel_ms) / 1e3
-    achieved = alg_bytes / avg_kernel_s / 1e9
+    a_bytes_launch = cols_per_launch * cfg.d * cfg.elt
+    # The roofline figure divides by the time of EVERYTHING one apply enqueues (the kernel that
+    # streams A and, where the output is written by a second kernel, that one too), so that the
+    # bytes counted and the time counted belong together; the dominant kernel's own duration is
+    # reported beside it (it is the one a rocprofv3 kernel trace shows).
+    achieved = alg_bytes / tm.apply_s / 1e9
     value = cfg.a_bytes / sec_per_step / 1e9
+    traffic = None
+    if not rows and cfg.name in MEASURED_TRAFFIC and MEASURED_TRAFFIC[cfg.name][0] == tm.kernel:
+        traffic = MEASURED_TRAFFIC[cfg.name][1]
 
     rec = {
         "metric": "sketch-apply GB/s of A streamed",
@@ -168,8 +253,13 @@ def main():
         "roofline": {
             "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBPS,
-            "traffic": None if rows else MEASURED_TRAFFIC.get((cfg.name, {1: "generic", 2: "mfma"}.get(used))),
-            "kernel_ms_avg": avg_kernel_s * 1e3, "launches_timed": len(kernel_ms),
+            "traffic": traffic,
+            "kernel": tm.kernel,
+            "basis": "algorithmic bytes of one launch / HIP-event time of the whole apply (all its kernels)",
+            "apply_ms_avg": tm.apply_s * 1e3,
+            "kernel_ms_avg": tm.kernel_s * 1e3,
+            "frac_dominant_kernel_reading_A": a_bytes_launch / tm.kernel_s / 1e9 / HBM_PEAK_GBPS,
+            "launches_timed": len(tm.kernel_ms),
             "algorithmic_bytes_per_launch": alg_bytes,
         },
     }
@@ -184,6 +274,8 @@ def main():
 
     if not args.no_extra and not rows:
         rec["extra"] = extra_measurements(torch, B, W, dev, cfg.name, with_oracle=not args.no_cpu)
+        if cfg.name == "grad":
+            rec["extra"].update(grad_side_measurements(torch, B, cfg, A, out))
         rec["extra"]["rows_layout"] = rows_layout_measurement(torch, B, cfg, A, out)
     print(json.dumps(rec))
 
@@ -195,13 +287,18 @@ def extra_measurements(torch, B, W, dev, skip, with_oracle):
     res = {}
 
     def one(cfg, A, **kw):
+        """kernel_ms: the dominant kernel; apply_ms: everything the apply enqueues (zero-fills, plane
+        reductions, conversions included); GBps_A and roofline_frac are computed from apply_ms."""
         try:
-            _, ms, used, _ = time_workload(torch, B, cfg, A, "auto", 5, 2, **kw)
+            tm, _ = time_workload(torch, B, cfg, A, "auto", 5, 2, **kw)
         except B.FlashSketchError as e:
             return {"error": str(e)}
-        t = sum(ms) / len(ms) / 1e3
-        return {"kernel_ms": t * 1e3, "GBps_A": cfg.a_bytes / len(chunks_of(cfg)) / t / 1e9,
-                "variant": used}
+        n_l = len(chunks_of(cfg))
+        alg = (cfg.a_bytes + cfg.k * cfg.n * cfg.elt) / n_l
+        return {"kernel_ms": tm.kernel_s * 1e3, "apply_ms": tm.apply_s * 1e3,
+                "GBps_A": cfg.a_bytes / n_l / tm.apply_s / 1e9,
+                "roofline_frac": alg / tm.apply_s / 1e9 / HBM_PEAK_GBPS,
+                "variant": tm.variant, "kernel": tm.kernel}
 
     def cold(cfg, A, reps=5):
         """Kernel time of single applies, each after 2 GiB of unrelated writes have gone through the
@@ -209,15 +306,18 @@ def extra_measurements(torch, B, W, dev, skip, with_oracle):
         sk = B.Sketch(*cfg.params, seed=cfg.sketch_seed)
         out = sk.apply(A)
         junk = torch.empty(1 << 29, device=dev, dtype=torch.float32)
-        ms = []
+        ms, ms_all = [], []
         for i in range(reps):
             junk.fill_(float(i))
             sk.profile_begin(1)
             sk.apply(A, out)
-            ms += sk.profile_end()
+            k_ms, a_ms = sk.profile_end(whole=True)
+            ms += k_ms
+            ms_all += a_ms
         sk.close()
-        t = sum(ms) / len(ms) / 1e3
-        return {"kernel_ms": t * 1e3, "GBps_A": cfg.a_bytes / t / 1e9}
+        t = sum(ms_all) / len(ms_all) / 1e3
+        return {"kernel_ms": sum(ms) / len(ms), "apply_ms": t * 1e3, "GBps_A": cfg.a_bytes / t / 1e9,
+                "roofline_frac": (cfg.a_bytes + cfg.k * cfg.n * cfg.elt) / t / 1e9 / HBM_PEAK_GBPS}
 
     for name in ("tiny", "tall"):
         if name != skip:
@@ -246,6 +346,53 @@ def extra_measurements(torch, B, W, dev, skip, with_oracle):
         for n in W.WIDE_NS:
             res[f"wide_n{n}"] = one(dataclasses.replace(base, n=n), A[:, :n].contiguous())
         del A
+    return res
+
+
+def grad_side_measurements(torch, B, cfg, A, out, steps=10):
+    """Two more views of the gradient workload.  (1) The prior-art plain-SJLT scatter at the same
+    k on one 256-column chunk of the same A, at s nonzeros per column (equal s) and at kappa*s
+    (equal nonzeros per column of S), whole apply (zero-fill, atomics, conversion).  (2) The same
+    step on four separate packed d x 256 buffers (lda = 256), as a pipeline that hands over one
+    chunk at a time would hold them, instead of column views of one d x 1024 matrix."""
+    res = {}
+    w = cfg.chunk
+    chunk_cfg = dataclasses.replace(cfg, n=w, chunk=0)
+    for s_nz in (cfg.s, cfg.s * cfg.kappa):
+        try:
+            tm, _ = time_workload(torch, B, chunk_cfg, A[:, :w], "auto", 3, 1, kind=B.KIND_SJLT_SCATTER,
+                                  sketch_params=(cfg.d, cfg.k, cfg.d, cfg.k, 1, s_nz))
+            res[f"grad_chunk_plain_sjlt_scatter_s{s_nz}"] = {
+                "kernel_ms": tm.kernel_s * 1e3, "apply_ms": tm.apply_s * 1e3,
+                "GBps_A": chunk_cfg.a_bytes / tm.apply_s / 1e9}
+        except B.FlashSketchError as e:
+            res[f"grad_chunk_plain_sjlt_scatter_s{s_nz}"] = {"error": str(e)}
+    try:
+        bufs = [A[:, c:c + w].contiguous() for c in range(0, cfg.n, w)]
+        o = torch.empty_like(out)
+        sk = B.Sketch(*cfg.params, seed=cfg.sketch_seed)
+
+        def step():
+            for j, buf in enumerate(bufs):
+                sk.apply(buf, o[:, j * w:(j + 1) * w])
+        step(); step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        t = (time.perf_counter() - t0) / steps
+        sk.profile_begin(len(bufs))
+        step()
+        k_ms, a_ms = sk.profile_end(whole=True)
+        res["grad_packed_chunks_lda256"] = {
+            "ms_per_step": t * 1e3, "GBps_A": cfg.a_bytes / t / 1e9, "pct_hbm_peak": 100.0 * cfg.a_bytes / t / 1e9 / HBM_PEAK_GBPS,
+            "kernel_ms": sum(k_ms) / len(k_ms), "apply_ms": sum(a_ms) / len(a_ms),
+            "bit_identical_to_column_views": bool(torch.equal(o, out))}
+        sk.close()
+        del bufs, o
+    except B.FlashSketchError as e:
+        res["grad_packed_chunks_lda256"] = {"error": str(e)}
     return res
 
 

@@ -120,6 +120,10 @@ typedef struct {
                           partial planes, 3 the same with orbit runs merged in LDS */
   int32_t last_hip_error; /* hipError_t of the last failed HIP call, else 0 */
   uint64_t workspace_bytes; /* size of the workspace currently attached     */
+  char last_kernel[64];     /* NUL-terminated name of the kernel the most recent apply launched,
+                               with its compile-time variant (matrix-core kernels: the template
+                               arguments in order), so that a stored profile can be matched to
+                               what ran; "" before the first apply                  */
 } fs_info;
 
 /* Create a BLOCKPERM handle.  Pure host work (no HIP call, usable without a GPU).
@@ -136,17 +140,21 @@ fs_status fs_sketch_create(fs_sketch_t* out, int64_t d, int64_t k, int32_t Bc, i
 fs_status fs_sketch_create_kind(fs_sketch_t* out, fs_kind kind, int64_t d, int64_t k, int32_t Bc,
                                 int32_t Br, int32_t kappa, int32_t s, uint64_t seed);
 
-/* out (k x n, ld = n) = S * A (d x n, ld = lda), both of type `dtype`.
+/* Y = S A of the paper's problem statement (Section 3, "Notation"), computed as Alg. 1 defines
+ * it block by block (Section 5.1): out (k x n, ld = n) = S * A (d x n, ld = lda), both of type
+ * `dtype`.
  * n == 0 is FS_OK and launches nothing.  Errors: NULL handle/A/out, n < 0,
  * lda < n, unknown dtype.  May grow the handle's workspace with hipMalloc on
  * first use unless one was attached with fs_sketch_set_workspace.  The first
- * matrix-core apply of a handle also uploads a table of 8*M bytes (the orbit
- * of the wiring map) with a synchronous copy; later applies only enqueue
- * kernels (call apply once before capturing it into a HIP graph). */
+ * matrix-core apply of a handle also allocates a table of 8*M bytes (the orbit
+ * of the wiring map) and enqueues the small kernel that fills it, unless fs_sketch_prepare
+ * has done so; no call ever copies from the host or synchronises.  Later applies only enqueue
+ * kernels (call prepare, or apply once, before capturing applies into a HIP graph). */
 fs_status fs_sketch_apply(fs_sketch_t h, const void* A, int64_t lda, int64_t n, void* out,
                           fs_dtype dtype, void* stream);
 
-/* Same with an explicit output leading dimension (column-chunk views). */
+/* Same with an explicit output leading dimension (column-chunk views: the 256-column
+ * chunks a gradient-compression pipeline hands over, Appendix F). */
 fs_status fs_sketch_apply_ld(fs_sketch_t h, const void* A, int64_t lda, int64_t n, void* out,
                              int64_t ldo, fs_dtype dtype, void* stream);
 
@@ -212,14 +220,29 @@ fs_status fs_sketch_export(fs_sketch_t h, int32_t* rows, int8_t* signs, void* st
 /* GAUSS_DENSE only: copy the k x d fp32 matrix (row-major, ld = d) to S_dense. */
 fs_status fs_sketch_export_dense(fs_sketch_t h, float* S_dense, void* stream);
 
+/* Allocates the handle's device tables (today: the orbit of the wiring map f of Appendix E,
+ * 8*M bytes, for 4 <= M <= 2^20) on the current device and enqueues on `stream` the kernel that
+ * fills them.  Optional: the first apply does the same.  After it, applies of a handle with an
+ * attached workspace neither allocate nor synchronise.  Later applies must be ordered after
+ * this call's work (same stream, or an event).  FS_OK and nothing done for other kinds. */
+fs_status fs_sketch_prepare(fs_sketch_t h, void* stream);
+
+/* The integers that define S for this handle (Section 3 "Notation" for d, k; Section 4 for
+ * M, Bc, Br, kappa, s; Appendix E for the wiring a, b), the scale of Alg. 1's last step, and
+ * what the most recent apply launched. */
 fs_status fs_sketch_info(fs_sketch_t h, fs_info* out);
 
-/* Bytes of device workspace an apply of n columns of `dtype` needs with the
- * handle's current variant setting (0 if none). */
+/* Bytes of device workspace an apply of n columns of `dtype` needs at most with the
+ * handle's current variant setting (0 if none).  The workspace holds the fp32 partial results
+ * of the cross-block accumulation (Section 5.3: each output tile is owned by one work-group and
+ * summed without global atomics) when the work is split by INPUT block: kappa (times a row
+ * split) planes of k x n floats, fewer when consecutive blocks of the wiring's orbit are merged
+ * on chip.  For FS_KIND_SJLT_SCATTER with 16-bit types: the k x n fp32 accumulator. */
 fs_status fs_sketch_workspace_bytes(fs_sketch_t h, int64_t n, fs_dtype dtype, size_t* bytes);
 
-/* Attach a caller-owned device workspace (256-byte aligned); the handle then
- * never allocates in apply and fails with FS_ERR_ALLOC if it is too small.
+/* Attach a caller-owned device workspace (256-byte aligned); applies then never grow a
+ * workspace and fail with FS_ERR_ALLOC if it is too small (after fs_sketch_prepare they
+ * allocate nothing at all).  Its contents need not be kept between calls.
  * (NULL, 0) detaches it and returns to the internal, lazily grown one. */
 fs_status fs_sketch_set_workspace(fs_sketch_t h, void* dev_ptr, size_t bytes);
 
@@ -227,15 +250,21 @@ fs_status fs_sketch_set_workspace(fs_sketch_t h, void* dev_ptr, size_t bytes);
  * FS_ERR_UNSUPPORTED at apply time if the forced variant cannot run the shape. */
 fs_status fs_sketch_set_variant(fs_sketch_t h, fs_variant v);
 
-/* Kernel timing for benchmarks.  After profile_begin, each apply brackets its
- * dominant kernel (the one that streams A) with a HIP event pair recorded on the
- * apply's stream, up to max_launches pairs.  profile_end synchronises those
- * events, writes the elapsed milliseconds of each bracketed launch to the HOST
- * array ms (capacity max_launches), the number of launches to *count, and
- * releases the events.  Errors: NULL arguments, max_launches < 1, begin while
- * already profiling, end without begin. */
-fs_status fs_sketch_profile_begin(fs_sketch_t h, int32_t max_launches);
-fs_status fs_sketch_profile_end(fs_sketch_t h, float* ms, int32_t* count);
+/* Kernel timing for benchmarks.  After profile_begin, each apply records HIP events on its
+ * stream, up to max_launches applies: with FS_PROFILE_KERNEL in `scope` one pair around its
+ * dominant kernel (the one that streams A), with FS_PROFILE_APPLY one pair around everything
+ * the apply enqueues (zero-fills, table builds, the dominant kernel, plane reductions,
+ * conversions).  Every recorded event costs a few microseconds on the stream, so with both
+ * scopes the inner pair lengthens what the outer pair measures: ask for one scope at a time
+ * when that matters.  profile_end synchronises the events and writes, per bracketed apply, the
+ * elapsed milliseconds of the dominant kernel to the HOST array ms and of the whole apply to
+ * the HOST array ms_apply (each of capacity max_launches; ms_apply may be NULL; a scope that was
+ * not asked for reads 0), the number of applies to *count, and releases the events.  Errors:
+ * NULL handle, ms or count, max_launches < 1, unknown scope, begin while already profiling, end
+ * without begin. */
+typedef enum { FS_PROFILE_KERNEL = 1, FS_PROFILE_APPLY = 2 } fs_profile_scope;
+fs_status fs_sketch_profile_begin(fs_sketch_t h, int32_t max_launches, int32_t scope);
+fs_status fs_sketch_profile_end(fs_sketch_t h, float* ms, float* ms_apply, int32_t* count);
 
 /* Frees the handle and any device memory it owns (not caller workspaces).  Like every call
  * that frees device memory it must not run while a stream is being captured into a HIP graph

@@ -22,8 +22,9 @@ SYMBOLS = [
     "fs_sketch_export", "fs_sketch_export_dense", "fs_sketch_info", "fs_sketch_workspace_bytes",
     "fs_sketch_set_workspace", "fs_sketch_set_variant", "fs_sketch_destroy", "fs_status_string",
     "fs_sketch_profile_begin", "fs_sketch_profile_end",
-    "fs_sketch_apply_rows", "fs_sketch_rows_workspace_bytes", "fs_sketch_plan",
+    "fs_sketch_apply_rows", "fs_sketch_rows_workspace_bytes", "fs_sketch_plan", "fs_sketch_prepare",
 ]
+PROFILE_KERNEL, PROFILE_APPLY = 1, 2
 PLAN_ELEMENT_LOADS, PLAN_ROW_SLICES, PLAN_SLOT_GROUPS, PLAN_SPLIT = 1, 2, 4, 8
 
 
@@ -43,6 +44,7 @@ class fs_info(C.Structure):
         ("kind", C.c_int32), ("variant", C.c_int32), ("last_variant", C.c_int32), ("last_mode", C.c_int32),
         ("last_hip_error", C.c_int32),
         ("workspace_bytes", C.c_uint64),
+        ("last_kernel", C.c_char * 64),
     ]
 
 
@@ -68,8 +70,9 @@ def _load() -> C.CDLL:
     L.fs_sketch_set_workspace.argtypes = [vp, vp, C.c_size_t]
     L.fs_sketch_set_variant.argtypes = [vp, C.c_int]
     L.fs_sketch_destroy.argtypes = [vp]
-    L.fs_sketch_profile_begin.argtypes = [vp, i32]
-    L.fs_sketch_profile_end.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(i32)]
+    L.fs_sketch_profile_begin.argtypes = [vp, i32, i32]
+    L.fs_sketch_profile_end.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(i32)]
+    L.fs_sketch_prepare.argtypes = [vp, vp]
     for name in SYMBOLS:
         getattr(L, name).restype = C.c_int
     L.fs_status_string.argtypes = [C.c_int]
@@ -175,16 +178,24 @@ class Sketch:
                    "fs_sketch_set_workspace")
         self._ws_keepalive = buf
 
-    def profile_begin(self, max_launches: int) -> None:
+    def profile_begin(self, max_launches: int, scope: int = PROFILE_KERNEL | PROFILE_APPLY) -> None:
         self._prof_cap = max_launches
-        _check(lib.fs_sketch_profile_begin(self._h, max_launches), "fs_sketch_profile_begin")
+        _check(lib.fs_sketch_profile_begin(self._h, max_launches, scope), "fs_sketch_profile_begin")
 
-    def profile_end(self) -> list[float]:
-        """Milliseconds of each bracketed dominant-kernel launch since profile_begin."""
+    def profile_end(self, whole: bool = False):
+        """Milliseconds of each bracketed dominant-kernel launch since profile_begin; with
+        `whole`, also of each whole apply (everything it enqueued): (kernel_ms, apply_ms)."""
         ms = (C.c_float * self._prof_cap)()
+        ms_apply = (C.c_float * self._prof_cap)()
         cnt = C.c_int32()
-        _check(lib.fs_sketch_profile_end(self._h, ms, C.byref(cnt)), "fs_sketch_profile_end")
-        return [float(ms[i]) for i in range(cnt.value)]
+        _check(lib.fs_sketch_profile_end(self._h, ms, ms_apply, C.byref(cnt)), "fs_sketch_profile_end")
+        kernel = [float(ms[i]) for i in range(cnt.value)]
+        if whole:
+            return kernel, [float(ms_apply[i]) for i in range(cnt.value)]
+        return kernel
+
+    def prepare(self, stream=None) -> None:
+        _check(lib.fs_sketch_prepare(self._h, _stream_ptr(stream)), "fs_sketch_prepare")
 
     def apply(self, A: torch.Tensor, out: torch.Tensor | None = None, stream=None) -> torch.Tensor:
         """out = S @ A for a 2-D row-major view A (unit column stride)."""

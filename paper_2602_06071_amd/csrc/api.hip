@@ -2,12 +2,22 @@
 // dispatch and workspace management.  No arithmetic of the sketch apply itself
 // lives here; it is all in the k_*.hip kernels.
 #include <math.h>
+#include <stdio.h>
+#include <string.h>
 #include <new>
 
 #include "handle.h"
 #include "spec.h"
 
+fs_status fs::hip_fail(fs_sketch_t h, hipError_t e) {
+  if (h) h->last_hip_error = (int)e;
+  (void)hipGetLastError();  // clear the sticky launch error
+  return FS_ERR_HIP;
+}
+
 namespace {
+
+using fs::hip_fail;
 
 uint32_t radical(uint32_t m) {
   uint32_t r = 1;
@@ -52,15 +62,11 @@ bool is_pow2(uint32_t x) { return x && !(x & (x - 1)); }
 
 bool valid_dtype(fs_dtype dt) { return dt == FS_F32 || dt == FS_BF16 || dt == FS_F16; }
 
-fs_status hip_fail(fs_sketch_t h, hipError_t e) {
-  if (h) h->last_hip_error = (int)e;
-  (void)hipGetLastError();  // clear the sticky launch error
-  return FS_ERR_HIP;
-}
-
-// Bytes of workspace the variant that would run needs.
+// Bytes of workspace the variant that would run needs.  exact_orbit < 0: an upper bound that
+// holds whether or not the orbit table will be there; 0 / 1: the size of exactly this call,
+// without / with the table.
 fs_status needed_workspace(fs_sketch_t h, const void* A, int64_t lda, int64_t n, const void* out,
-                           int64_t ldo, fs_dtype dt, int* variant_out, size_t* bytes) {
+                           int64_t ldo, fs_dtype dt, int* variant_out, size_t* bytes, int exact_orbit = -1) {
   *bytes = 0;
   *variant_out = FS_VARIANT_GENERIC;
   if (h->kind == FS_KIND_SJLT_SCATTER) {
@@ -76,6 +82,10 @@ fs_status needed_workspace(fs_sketch_t h, const void* A, int64_t lda, int64_t n,
   if (v == FS_VARIANT_MFMA) {
     if (!can) return FS_ERR_UNSUPPORTED;
     *bytes = fs::mfma_workspace_bytes(h->p, n, dt);
+    if (exact_orbit >= 0) {
+      int mode = 0, flags = 0;
+      if (!fs::mfma_describe(h->p, A, lda, n, dt, exact_orbit != 0, &mode, &flags, bytes)) return FS_ERR_UNSUPPORTED;
+    }
   }
   *variant_out = v;
   return FS_OK;
@@ -96,24 +106,39 @@ fs_status ensure_workspace(fs_sketch_t h, size_t need) {
   return FS_OK;
 }
 
-// pos2blk[q] = f^q(0), blk2pos = its inverse; uploaded once per handle.
-fs_status ensure_orbit(fs_sketch_t h) {
+// pos2blk[q] = f^q(0), blk2pos = its inverse: allocated once per handle and filled by a small
+// kernel enqueued on `st` (no copy, no synchronisation).
+fs_status ensure_orbit(fs_sketch_t h, hipStream_t st) {
   if (h->orbit || !fs::mfma_wants_orbit(h->p)) return FS_OK;
-  const uint32_t M = h->p.M;
-  std::vector<uint32_t> tab(2 * (size_t)M);
-  uint32_t x = 0;
-  for (uint32_t q = 0; q < M; ++q) {
-    tab[q] = x;
-    tab[M + x] = q;
-    x = fs::wire_next(x, h->p.a, h->p.b, M);
-  }
   void* dev = nullptr;
-  hipError_t e = hipMalloc(&dev, tab.size() * sizeof(uint32_t));
+  hipError_t e = hipMalloc(&dev, 2 * (size_t)h->p.M * sizeof(uint32_t));
   if (e != hipSuccess) { hip_fail(h, e); return FS_ERR_ALLOC; }
-  e = hipMemcpy(dev, tab.data(), tab.size() * sizeof(uint32_t), hipMemcpyHostToDevice);
+  e = fs::launch_orbit(h->p, (uint32_t*)dev, st);
   if (e != hipSuccess) { (void)hipFree(dev); return hip_fail(h, e); }
   h->orbit = (uint32_t*)dev;
   return FS_OK;
+}
+
+// The next unused set of profiling events (all null when not profiling).  `begin` is recorded
+// here, before anything the apply enqueues; the caller records `end` after its last launch.
+struct ProfSet {
+  fs::EventPair kernel;
+  hipEvent_t end = nullptr;
+};
+ProfSet next_events(fs_sketch_t h, hipStream_t st) {
+  ProfSet ps;
+  if (h->profiling && h->prof_used < (int)h->prof_begin.size()) {
+    const int i = h->prof_used++;
+    if (h->prof_scope & FS_PROFILE_KERNEL) {
+      ps.kernel.start = h->prof_start[i];
+      ps.kernel.stop = h->prof_stop[i];
+    }
+    if (h->prof_scope & FS_PROFILE_APPLY) {
+      ps.end = h->prof_end[i];
+      (void)hipEventRecord(h->prof_begin[i], st);
+    }
+  }
+  return ps;
 }
 
 }  // namespace
@@ -148,7 +173,8 @@ fs_status fs_sketch_create_kind(fs_sketch_t* out, fs_kind kind, int64_t d, int64
     const int64_t M = k / Br;
     if (M > (1 << 24) || kappa > M) return FS_ERR_INVALID_ARG;
     if (s > Br || s > 32 || Br > 65536) return FS_ERR_INVALID_ARG;
-    if (kind == FS_KIND_SJLT_SCATTER && (M != 1 || kappa != 1)) return FS_ERR_INVALID_ARG;
+    // (the scatter kernel walks exactly Bc rows of A: a padded block, Bc > d, is not accepted)
+    if (kind == FS_KIND_SJLT_SCATTER && (M != 1 || kappa != 1 || Bc != d)) return FS_ERR_INVALID_ARG;
   }
   fs_sketch_s* h = new (std::nothrow) fs_sketch_s();
   if (!h) return FS_ERR_ALLOC;
@@ -168,10 +194,11 @@ fs_status fs_sketch_create_kind(fs_sketch_t* out, fs_kind kind, int64_t d, int64
   h->last_variant = 0;
   h->last_mode = 0;
   h->last_hip_error = 0;
+  h->last_kernel[0] = 0;
   h->device = -1;
   h->ws = nullptr; h->ws_bytes = 0; h->ws_owned = true;
   h->dense = nullptr;
-  h->profiling = false; h->prof_used = 0;
+  h->profiling = false; h->prof_used = 0; h->prof_scope = 0;
   h->orbit = nullptr;
 
   if (kind == FS_KIND_GAUSS_DENSE) {
@@ -197,36 +224,43 @@ fs_status fs_sketch_create(fs_sketch_t* out, int64_t d, int64_t k, int32_t Bc, i
 }
 
 static void release_events(fs_sketch_t h) {
-  for (hipEvent_t e : h->prof_start) (void)hipEventDestroy(e);
-  for (hipEvent_t e : h->prof_stop) (void)hipEventDestroy(e);
-  h->prof_start.clear(); h->prof_stop.clear();
+  for (auto* v : {&h->prof_begin, &h->prof_start, &h->prof_stop, &h->prof_end}) {
+    for (hipEvent_t e : *v) (void)hipEventDestroy(e);
+    v->clear();
+  }
   h->profiling = false; h->prof_used = 0;
 }
 
-fs_status fs_sketch_profile_begin(fs_sketch_t h, int32_t max_launches) {
+fs_status fs_sketch_profile_begin(fs_sketch_t h, int32_t max_launches, int32_t scope) {
   if (!h || max_launches < 1 || max_launches > (1 << 20) || h->profiling) return FS_ERR_INVALID_ARG;
+  if (scope < 1 || scope > (FS_PROFILE_KERNEL | FS_PROFILE_APPLY)) return FS_ERR_INVALID_ARG;
+  h->prof_scope = scope;
   for (int i = 0; i < max_launches; ++i) {
-    hipEvent_t a = nullptr, b = nullptr;
-    hipError_t e = hipEventCreate(&a);
-    if (e == hipSuccess) e = hipEventCreate(&b);
-    if (e != hipSuccess) {
-      if (a) (void)hipEventDestroy(a);
-      release_events(h);
-      return hip_fail(h, e);
+    for (auto* v : {&h->prof_begin, &h->prof_start, &h->prof_stop, &h->prof_end}) {
+      hipEvent_t ev = nullptr;
+      const hipError_t e = hipEventCreate(&ev);
+      if (e != hipSuccess) {
+        release_events(h);
+        return hip_fail(h, e);
+      }
+      v->push_back(ev);
     }
-    h->prof_start.push_back(a); h->prof_stop.push_back(b);
   }
   h->profiling = true; h->prof_used = 0;
   return FS_OK;
 }
 
-fs_status fs_sketch_profile_end(fs_sketch_t h, float* ms, int32_t* count) {
+fs_status fs_sketch_profile_end(fs_sketch_t h, float* ms, float* ms_apply, int32_t* count) {
   if (!h || !ms || !count || !h->profiling) return FS_ERR_INVALID_ARG;
   fs_status rc = FS_OK;
   *count = h->prof_used;
+  const bool k = h->prof_scope & FS_PROFILE_KERNEL, a = h->prof_scope & FS_PROFILE_APPLY;
   for (int i = 0; i < h->prof_used; ++i) {
-    hipError_t e = hipEventSynchronize(h->prof_stop[i]);
-    if (e == hipSuccess) e = hipEventElapsedTime(&ms[i], h->prof_start[i], h->prof_stop[i]);
+    hipError_t e = hipEventSynchronize(a ? h->prof_end[i] : h->prof_stop[i]);
+    ms[i] = 0.f;
+    if (ms_apply) ms_apply[i] = 0.f;
+    if (e == hipSuccess && k) e = hipEventElapsedTime(&ms[i], h->prof_start[i], h->prof_stop[i]);
+    if (e == hipSuccess && a && ms_apply) e = hipEventElapsedTime(&ms_apply[i], h->prof_begin[i], h->prof_end[i]);
     if (e != hipSuccess) { rc = hip_fail(h, e); *count = i; break; }
   }
   release_events(h);
@@ -256,6 +290,7 @@ fs_status fs_sketch_info(fs_sketch_t h, fs_info* o) {
   o->kind = h->kind; o->variant = h->variant; o->last_variant = h->last_variant; o->last_mode = h->last_mode;
   o->last_hip_error = h->last_hip_error;
   o->workspace_bytes = h->ws_bytes;
+  memcpy(o->last_kernel, h->last_kernel, sizeof(o->last_kernel));
   return FS_OK;
 }
 
@@ -294,8 +329,11 @@ fs_status fs_sketch_set_workspace(fs_sketch_t h, void* dev_ptr, size_t bytes) {
   return FS_OK;
 }
 
-fs_status fs_sketch_apply_ld(fs_sketch_t h, const void* A, int64_t lda, int64_t n, void* out,
-                             int64_t ldo, fs_dtype dt, void* stream) {
+}  // extern "C"
+
+// The apply of the column layout (declared in handle.h).
+fs_status fs::apply_cols(fs_sketch_t h, const void* A, int64_t lda, int64_t n, void* out, int64_t ldo,
+                         fs_dtype dt, void* stream, const fs::ScratchSource& src) {
   if (!h || n < 0 || !valid_dtype(dt)) return FS_ERR_INVALID_ARG;
   if (n == 0) return FS_OK;
   if (!A || !out || lda < n || ldo < n) return FS_ERR_INVALID_ARG;
@@ -304,40 +342,79 @@ fs_status fs_sketch_apply_ld(fs_sketch_t h, const void* A, int64_t lda, int64_t 
   if ((uintptr_t)A % esz || (uintptr_t)out % esz) return FS_ERR_INVALID_ARG;
   hipStream_t st = (hipStream_t)stream;
 
+  // whether the kernels will get the orbit table of the wiring (it shapes their plan)
+  const bool with_orbit = h->kind == FS_KIND_BLOCKPERM && fs::mfma_wants_orbit(h->p) &&
+                          (!src.external || 2 * (size_t)h->p.M * sizeof(uint32_t) <= src.orbit_bytes);
   int variant;
   size_t need;
-  fs_status rc = needed_workspace(h, A, lda, n, out, ldo, dt, &variant, &need);
+  fs_status rc = needed_workspace(h, A, lda, n, out, ldo, dt, &variant, &need, with_orbit ? 1 : 0);
   if (rc != FS_OK) return rc;
-  rc = ensure_workspace(h, need);
-  if (rc != FS_OK) return rc;
-  if (variant == FS_VARIANT_MFMA) {
-    rc = ensure_orbit(h);
+  void* ws = nullptr;
+  const uint32_t* orbit = nullptr;
+  if (src.external && need > src.plane_bytes) return FS_ERR_ALLOC;  // beyond the supplied memory: nothing is launched
+  if (!src.external) {
+    rc = ensure_workspace(h, need);
     if (rc != FS_OK) return rc;
   }
-
-  fs::EventPair ev;
-  if (h->profiling && h->prof_used < (int)h->prof_start.size()) {
-    ev.start = h->prof_start[h->prof_used];
-    ev.stop = h->prof_stop[h->prof_used];
-    ++h->prof_used;
+  const ProfSet prof = next_events(h, st);
+  const fs::EventPair ev = prof.kernel;
+  if (src.external) {
+    ws = src.planes;
+    // such memory is shared between handles: the table of this handle's wiring is rebuilt on every
+    // call (a wiring too long for the table's room runs without one: the kernels then skip the
+    // orbit-ordered modes)
+    if (variant == FS_VARIANT_MFMA && with_orbit) {
+      const hipError_t e = fs::launch_orbit(h->p, src.orbit, st);
+      if (e != hipSuccess) return hip_fail(h, e);
+      orbit = src.orbit;
+    }
+  } else {
+    if (variant == FS_VARIANT_MFMA) {
+      rc = ensure_orbit(h, st);
+      if (rc != FS_OK) return rc;
+    }
+    ws = h->ws;
+    orbit = h->orbit;
   }
+
   hipError_t e;
   int mode = 0;
+  const char* what = "";
   if (h->kind == FS_KIND_SJLT_SCATTER) {
-    e = fs::launch_scatter(h->p, A, lda, n, out, ldo, dt, h->ws, st, ev);
+    e = fs::launch_scatter(h->p, A, lda, n, out, ldo, dt, ws, st, ev);
+    what = "scatter_kernel";
   } else if (h->kind == FS_KIND_GAUSS_DENSE) {
     e = fs::launch_gauss(h->dense, h->p.k, h->p.d, A, lda, n, out, ldo, dt, st, ev);
+    what = "gauss_kernel";
   } else if (h->kind == FS_KIND_BLOCKROW) {
     e = fs::launch_blockrow(h->p, A, lda, n, out, ldo, dt, st, ev);
+    what = "blockrow_kernel";
   } else if (variant == FS_VARIANT_MFMA) {
-    e = fs::launch_mfma(h->p, A, lda, n, out, ldo, dt, h->ws, h->orbit, st, ev, &mode);
+    e = fs::launch_mfma(h->p, A, lda, n, out, ldo, dt, ws, orbit, st, ev, &mode, h->last_kernel,
+                        sizeof(h->last_kernel));
   } else {
     e = fs::launch_generic(h->p, A, lda, n, out, ldo, dt, st, ev);
+    what = "generic_kernel";
   }
+  if (what[0]) snprintf(h->last_kernel, sizeof(h->last_kernel), "%s", what);
+  if (prof.end) (void)hipEventRecord(prof.end, st);
   h->last_variant = variant;
   h->last_mode = mode;
   if (e != hipSuccess) return hip_fail(h, e);
   return FS_OK;
+}
+
+extern "C" {
+
+fs_status fs_sketch_apply_ld(fs_sketch_t h, const void* A, int64_t lda, int64_t n, void* out,
+                             int64_t ldo, fs_dtype dt, void* stream) {
+  return fs::apply_cols(h, A, lda, n, out, ldo, dt, stream, fs::ScratchSource{});
+}
+
+fs_status fs_sketch_prepare(fs_sketch_t h, void* stream) {
+  if (!h) return FS_ERR_INVALID_ARG;
+  if (h->kind != FS_KIND_BLOCKPERM) return FS_OK;
+  return ensure_orbit(h, (hipStream_t)stream);
 }
 
 fs_status fs_sketch_apply_rows(fs_sketch_t h, const void* G, int64_t ldg, int64_t n, void* out,
@@ -355,22 +432,22 @@ fs_status fs_sketch_apply_rows(fs_sketch_t h, const void* G, int64_t ldg, int64_
   hipStream_t st = (hipStream_t)stream;
   fs_status rc = use_mfma ? ensure_workspace(h, fs::rows_workspace_bytes(h->p, G, ldg, n, dt)) : FS_OK;
   if (rc != FS_OK) return rc;
-  fs::EventPair ev;
-  if (h->profiling && h->prof_used < (int)h->prof_start.size()) {
-    ev.start = h->prof_start[h->prof_used];
-    ev.stop = h->prof_stop[h->prof_used];
-    ++h->prof_used;
-  }
+  const ProfSet prof = next_events(h, st);
+  const fs::EventPair ev = prof.kernel;
   if (!use_mfma) {
     const hipError_t e = fs::launch_generic_rows(h->p, G, ldg, n, out, ldo, dt, st, ev);
+    if (prof.end) (void)hipEventRecord(prof.end, st);
+    snprintf(h->last_kernel, sizeof(h->last_kernel), "generic_rows_kernel");
     h->last_variant = FS_VARIANT_GENERIC;
     h->last_mode = 0;
     if (e != hipSuccess) return hip_fail(h, e);
     return FS_OK;
   }
-  rc = ensure_orbit(h);  // the gather-reduction walks the wiring through this table
+  rc = ensure_orbit(h, st);  // the gather-reduction walks the wiring through this table
   if (rc != FS_OK) return rc;
   const hipError_t e = fs::launch_rows(h->p, G, ldg, n, out, ldo, dt, h->ws, h->orbit, st, ev);
+  if (prof.end) (void)hipEventRecord(prof.end, st);
+  snprintf(h->last_kernel, sizeof(h->last_kernel), "rows_kernel");
   h->last_variant = FS_VARIANT_MFMA;
   h->last_mode = 2;
   if (e != hipSuccess) return hip_fail(h, e);

@@ -25,15 +25,18 @@ struct fs_sketch_s {
   int last_variant;
   int last_mode;
   int last_hip_error;
+  char last_kernel[64];  // which kernel instantiation the most recent apply launched
   int device;  // device that owns ws / dense (-1: none yet)
   // internal or caller-owned workspace
   void* ws;
   size_t ws_bytes;
   bool ws_owned;
-  // optional event pairs around the dominant kernel of each apply
+  // optional events of each apply: begin / end around everything it enqueues, start / stop
+  // around its dominant kernel
   bool profiling;
   int prof_used;
-  std::vector<hipEvent_t> prof_start, prof_stop;
+  int prof_scope;  // FS_PROFILE_KERNEL | FS_PROFILE_APPLY
+  std::vector<hipEvent_t> prof_begin, prof_start, prof_stop, prof_end;
   // orbit order of the blocks under the wiring map (2*M words, device), built on first use
   uint32_t* orbit;
   // GAUSS_DENSE: the k x d matrix in its fp32 and bf16 forms (one allocation)
@@ -47,10 +50,30 @@ struct EventPair {
   hipEvent_t start = nullptr, stop = nullptr;
 };
 
+// Where the kernels of one column-layout apply find their scratch memory (partial planes or the
+// scatter accumulator, and the orbit table of the wiring).  Default: the handle's own or attached
+// workspace and its own table.  external: memory supplied for this call only -- `planes`
+// (256-byte aligned, plane_bytes long) and room for an orbit table that is rebuilt on every call
+// (orbit_bytes; a longer wiring runs without a table); nothing is then allocated.
+struct ScratchSource {
+  bool external = false;
+  void* planes = nullptr;
+  size_t plane_bytes = 0;
+  uint32_t* orbit = nullptr;
+  size_t orbit_bytes = 0;
+};
+// Argument checks, variant choice and launches of fs_sketch_apply_ld, on `src`'s memory.
+fs_status apply_cols(fs_sketch_t h, const void* A, int64_t lda, int64_t n, void* out, int64_t ldo,
+                     fs_dtype dt, void* stream, const ScratchSource& src);
+// Records a failed HIP call in the handle, clears the sticky error, returns FS_ERR_HIP.
+fs_status hip_fail(fs_sketch_t h, hipError_t e);
+
 // Each launcher validates nothing: api.hip has already checked every argument
 // and that the shape fits the kernel.  They return the launch's hipError_t.
 
 hipError_t launch_export(const SketchParams& p, int32_t* rows, int8_t* signs, hipStream_t st);
+// Fills tab (2*M words, device) with the orbit of the wiring map from block 0 and its inverse.
+hipError_t launch_orbit(const SketchParams& p, uint32_t* tab, hipStream_t st);
 
 // One lane per column, LDS-private output tile.
 hipError_t launch_generic(const SketchParams& p, const void* A, int64_t lda, int64_t n, void* out,
@@ -71,7 +94,7 @@ bool mfma_describe(const SketchParams& p, const void* A, int64_t lda, int64_t n,
                    bool have_orbit, int* mode, int* flags, size_t* workspace);
 hipError_t launch_mfma(const SketchParams& p, const void* A, int64_t lda, int64_t n, void* out,
                        int64_t ldo, fs_dtype dt, void* ws, const uint32_t* orbit, hipStream_t st,
-                       EventPair ev, int* mode);
+                       EventPair ev, int* mode, char* desc, size_t desc_cap);
 
 // Matrix-core path for inputs held examples-as-rows: G is n x d (ld = ldg), out is n x k.
 bool rows_supported(const SketchParams& p, const void* G, int64_t ldg, int64_t n, fs_dtype dt);

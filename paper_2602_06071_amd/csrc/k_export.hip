@@ -28,6 +28,32 @@ __global__ __launch_bounds__(256) void export_kernel(SketchParams p, int32_t* __
   }
 }
 
+// Orbit table of the wiring map: tab[q] = f^q(0) for q in [0, M), tab[M + f^q(0)] = q.
+// f^q is itself affine, x -> (A_q x + B_q) mod M, and powers compose as
+// (A, B) o (A', B') = (A A', A B' + B), so thread q reaches f^q(0) = B_q by binary
+// exponentiation (M <= 2^24: every product fits 64 bits).  f has full period (Appendix E,
+// "Full-cycle affine construction"), so the M values are distinct and both halves are
+// written exactly once.
+__global__ __launch_bounds__(256) void orbit_kernel(uint32_t* __restrict__ tab, uint32_t M, uint32_t a,
+                                                    uint32_t b) {
+  const uint32_t q = blockIdx.x * 256 + threadIdx.x;
+  if (q >= M) return;
+  uint64_t ra = 1, rb = 0;   // f^0
+  uint64_t pa = a, pb = b;   // f^(2^i)
+  for (uint32_t e = q; e; e >>= 1) {
+    if (e & 1u) { rb = (pa * rb + pb) % M; ra = (pa * ra) % M; }
+    pb = (pa * pb + pb) % M;
+    pa = (pa * pa) % M;
+  }
+  tab[q] = (uint32_t)rb;
+  tab[M + (uint32_t)rb] = q;
+}
+
+hipError_t launch_orbit(const SketchParams& p, uint32_t* tab, hipStream_t st) {
+  hipLaunchKernelGGL(orbit_kernel, dim3((p.M + 255) / 256), dim3(256), 0, st, tab, p.M, p.a, p.b);
+  return hipGetLastError();
+}
+
 hipError_t launch_export(const SketchParams& p, int32_t* rows, int8_t* signs, hipStream_t st) {
   const int64_t total = p.d * p.kappa;
   const int64_t blocks = (total + 255) / 256;

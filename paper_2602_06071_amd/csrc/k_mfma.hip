@@ -40,6 +40,8 @@
 //
 // Inputs must be finite: a dense product multiplies every element by the zeros of
 // Phi as well, so an Inf/NaN in A spreads to all rows of the blocks that read it.
+#include <stdio.h>
+
 #include "k_mfma_kernel.h"
 
 namespace fs {
@@ -205,10 +207,15 @@ size_t mfma_workspace_bytes(const SketchParams& p, int64_t n, fs_dtype dt) {
 
 hipError_t launch_mfma(const SketchParams& p, const void* A, int64_t lda, int64_t n, void* out,
                        int64_t ldo, fs_dtype dt, void* ws, const uint32_t* orbit, hipStream_t st,
-                       EventPair ev, int* mode) {
+                       EventPair ev, int* mode, char* desc, size_t desc_cap) {
   const Plan pl = make_plan(p, A, lda, n, dt, orbit != nullptr);
   if (!pl.ok) return hipErrorInvalidValue;
   *mode = !pl.in_stat ? 1 : pl.run > 1 ? 3 : 2;
+  if (desc && desc_cap)  // the template arguments of the instantiation launched below, in order
+    snprintf(desc, desc_cap, "mfma_kernel<%s,%d,%d,%d,%s,%d,%d,%d,%s,%s>%s",
+             dt == FS_F32 ? "f32" : dt == FS_BF16 ? "bf16" : "f16", pl.mt, pl.nrg, pl.ncg,
+             pl.in_stat ? "in" : "out", pl.run, pl.cpl, pl.unal ? 1 : pl.pfx, pl.nsub > 1 ? "sub" : "-",
+             pl.unal ? "unal" : "-", pl.planes ? "+reduce_planes" : "");
   const size_t esz = dt == FS_F32 ? 4 : 2;
   MfmaArgs a;
   a.p = p; a.A = A; a.out = out; a.ws = (float*)ws;

@@ -701,9 +701,10 @@ __global__ __launch_bounds__(256) void reduce_planes_kernel(const float* __restr
   }
 }
 
-template <typename K>
-hipError_t go(K kernel, dim3 grid, unsigned threads, size_t lds, hipStream_t st, const MfmaArgs& a) {
-  static size_t raised = 64 * 1024;  // one per kernel instantiation: the limit set so far
+// One instantiation, and so one cached limit, per kernel (the kernel is a template argument).
+template <auto kernel>
+hipError_t go(dim3 grid, unsigned threads, size_t lds, hipStream_t st, const MfmaArgs& a) {
+  static size_t raised = 64 * 1024;  // the dynamic-LDS limit set for this kernel so far
   if (lds > raised) {  // above the default dynamic-LDS limit: raise it for this kernel
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -718,12 +719,12 @@ hipError_t go(K kernel, dim3 grid, unsigned threads, size_t lds, hipStream_t st,
 template <typename T, bool IN_STAT>
 hipError_t launch_shape_unal(const Plan& pl, const MfmaArgs& a, dim3 grid, hipStream_t st) {
 #define FS_GO(MT, NCG) \
-  return go(mfma_kernel<T, MT, 1, NCG, IN_STAT, 1, 4, 1, false, true>, grid, 64 * NCG, pl.lds, st, a)
+  return go<mfma_kernel<T, MT, 1, NCG, IN_STAT, 1, 4, 1, false, true>>(grid, 64 * NCG, pl.lds, st, a)
 #define FS_GO4(NCG)                                                                                      \
   do {                                                                                                   \
     if constexpr (!IN_STAT) {                                                                            \
       if (pl.nsub > 1)                                                                                   \
-        return go(mfma_kernel<T, 4, 1, NCG, false, 1, 4, 1, true, true>, grid, 64 * NCG, pl.lds, st, a); \
+        return go<mfma_kernel<T, 4, 1, NCG, false, 1, 4, 1, true, true>>(grid, 64 * NCG, pl.lds, st, a); \
     }                                                                                                    \
     FS_GO(4, NCG);                                                                                       \
   } while (0)
@@ -739,23 +740,23 @@ hipError_t launch_shape_unal(const Plan& pl, const MfmaArgs& a, dim3 grid, hipSt
 template <typename T, bool IN_STAT>
 hipError_t launch_shape(const Plan& pl, const MfmaArgs& a, dim3 grid, hipStream_t st) {
 #define FS_GO(MT, NRG, NCG, RUN) \
-  return go(mfma_kernel<T, MT, NRG, NCG, IN_STAT, RUN, 4>, grid, 64 * NRG * NCG * RUN, pl.lds, st, a)
+  return go<mfma_kernel<T, MT, NRG, NCG, IN_STAT, RUN, 4>>(grid, 64 * NRG * NCG * RUN, pl.lds, st, a)
 #define FS_GO4(NCG)                                                                            \
   do {                                                                                         \
     if constexpr (!IN_STAT) {                                                                  \
       if (pl.nsub > 1) {                                                                       \
         if constexpr (sizeof(T) == 2) {                                                        \
           if (pl.pfx == 2)                                                                     \
-            return go(mfma_kernel<T, 4, 1, NCG, false, 1, 4, 2, true>, grid, 64 * NCG, pl.lds, st, a); \
+            return go<mfma_kernel<T, 4, 1, NCG, false, 1, 4, 2, true>>(grid, 64 * NCG, pl.lds, st, a); \
         }                                                                                      \
-        return go(mfma_kernel<T, 4, 1, NCG, false, 1, 4, 1, true>, grid, 64 * NCG, pl.lds, st, a);     \
+        return go<mfma_kernel<T, 4, 1, NCG, false, 1, 4, 1, true>>(grid, 64 * NCG, pl.lds, st, a);     \
       }                                                                                        \
     }                                                                                          \
     if constexpr (sizeof(T) == 2) {                                                            \
       if (pl.pfx == 2)                                                                         \
-        return go(mfma_kernel<T, 4, 1, NCG, IN_STAT, 1, 4, 2>, grid, 64 * NCG, pl.lds, st, a); \
+        return go<mfma_kernel<T, 4, 1, NCG, IN_STAT, 1, 4, 2>>(grid, 64 * NCG, pl.lds, st, a); \
     }                                                                                          \
-    return go(mfma_kernel<T, 4, 1, NCG, IN_STAT, 1, 4, 1>, grid, 64 * NCG, pl.lds, st, a);     \
+    return go<mfma_kernel<T, 4, 1, NCG, IN_STAT, 1, 4, 1>>(grid, 64 * NCG, pl.lds, st, a);     \
   } while (0)
   if constexpr (IN_STAT) {
     if (pl.run == 4) FS_GO(2, 1, 2, 4);

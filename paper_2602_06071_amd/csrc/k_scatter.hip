@@ -26,7 +26,7 @@ __global__ __launch_bounds__(256) void scatter_kernel(SketchParams p, const T* _
   if (col >= n) return;
   const uint32_t bk = block_key(p.key1, 0u, 0u, 1u);
   const uint32_t u_beg = blockIdx.x * (uint32_t)kScatterRows;
-  const uint32_t u_end = min(u_beg + (uint32_t)kScatterRows, p.Bc);
+  const uint32_t u_end = min(u_beg + (uint32_t)kScatterRows, (uint32_t)min((int64_t)p.Bc, p.d));
   for (uint32_t u = u_beg; u < u_end; ++u) {
     const float v = Elt<T>::load(A + (int64_t)u * lda + col) * p.scale;
     const RowHash rh = POW2 ? row_hash_pow2(bk, u, p.Br) : row_hash_any(bk, u, p.Br);

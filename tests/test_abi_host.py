@@ -65,6 +65,8 @@ def test_create_null_out_and_bad_kind():
     assert st == 1
     st, _ = _create(4096, 256, 512, 32, 2, 4, 0, kind=B.KIND_SJLT_SCATTER)  # needs M = 1
     assert st == 1
+    st, _ = _create(1000, 64, 1024, 64, 1, 4, 0, kind=B.KIND_SJLT_SCATTER)  # Bc > d: a padded block
+    assert st == 1
     st, h = _create(4096, 256, 4096, 256, 1, 4, 0, kind=B.KIND_SJLT_SCATTER)
     assert st == 0
     assert B.lib.fs_sketch_destroy(h) == 0

@@ -494,8 +494,10 @@ def test_caller_workspace_and_too_small_workspace():
     sk = B.Sketch(*params, seed=1)
     need = sk.workspace_bytes(n, torch.bfloat16)
     assert need > 0
+    exact = sk.plan(n, torch.bfloat16)["workspace_bytes"]
+    assert 0 < exact <= need                # the query is an upper bound over alignments and modes
     ref = sk.apply(A)                       # internal, lazily grown workspace
-    assert sk.info().workspace_bytes >= need
+    assert sk.info().workspace_bytes >= exact
     ws = torch.empty(need + 256, dtype=torch.uint8, device=DEV)
     off = (-ws.data_ptr()) % 256
     sk.set_workspace(ws[off:off + need])
@@ -507,6 +509,34 @@ def test_caller_workspace_and_too_small_workspace():
         sk.apply(A)
     assert e.value.status == 3
     sk.set_workspace(None)
+    assert torch.equal(sk.apply(A), ref)
+
+
+def test_prepare_then_applies_on_a_caller_workspace_allocate_nothing():
+    """After fs_sketch_prepare (device tables) and fs_sketch_set_workspace, an apply only enqueues
+    kernels: device memory in use stays what it was, and the result equals the lazily set-up one."""
+    params, n = (65536, 8192, 64, 8, 8, 2), 256   # orbit-run mode: uses the table and partial planes
+    A = torch.randn((params[0], n), device=DEV).to(torch.bfloat16)
+    lazy = B.Sketch(*params, seed=4)
+    ref = lazy.apply(A)
+    assert lazy.info().last_mode == 3
+    sk = B.Sketch(*params, seed=4)
+    ws = torch.empty(sk.workspace_bytes(n, torch.bfloat16) + 256, dtype=torch.uint8, device=DEV)
+    off = (-ws.data_ptr()) % 256
+    sk.set_workspace(ws[off:])
+    sk.prepare()
+    out = torch.empty_like(ref)
+    torch.cuda.synchronize()
+    free0, _ = torch.cuda.mem_get_info()
+    for _ in range(3):
+        ws.fill_(0xFF)                      # the workspace need not survive between calls
+        sk.apply(A, out)
+    torch.cuda.synchronize()
+    free1, _ = torch.cuda.mem_get_info()
+    assert free1 == free0, "an apply allocated device memory"
+    assert sk.info().last_mode == 3
+    assert torch.equal(out, ref)
+    sk.prepare()                            # idempotent
     assert torch.equal(sk.apply(A), ref)
 
 
@@ -523,8 +553,10 @@ def test_apply_on_a_side_stream_and_profile_brackets():
         for _ in range(5):                  # two more applies than brackets: extra ones run unbracketed
             sk.apply(A, out, stream=side)
     side.synchronize()
-    ms = sk.profile_end()
+    ms, ms_apply = sk.profile_end(whole=True)
     assert len(ms) == 3 and all(0.0 < t < 50.0 for t in ms)
+    # the whole-apply bracket contains the dominant kernel's (tiny runs input-stationary: + a reduction)
+    assert len(ms_apply) == 3 and all(a >= t for a, t in zip(ms_apply, ms)) and all(a < 50.0 for a in ms_apply)
     assert torch.equal(out, ref)
     with pytest.raises(B.FlashSketchError):
         sk.profile_end()                    # not profiling any more
