@@ -158,6 +158,26 @@ fs_status fs_sketch_apply(fs_sketch_t h, const void* A, int64_t lda, int64_t n, 
 fs_status fs_sketch_apply_ld(fs_sketch_t h, const void* A, int64_t lda, int64_t n, void* out,
                              int64_t ldo, fs_dtype dtype, void* stream);
 
+/* fs_sketch_apply_ld for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels
+ * and bit-identical results; but the kernels' scratch memory (partial planes of the
+ * cross-block accumulation, the scatter baseline's fp32 accumulator, the orbit table of the
+ * wiring, rebuilt by a small kernel on every call) is a fixed device array inside the library,
+ * FS_STATIC_SCRATCH_BYTES for the planes plus 1 MiB for the table, which every GPU that runs
+ * the library holds until the process ends (the runtime places it there when the first call on
+ * that GPU looks up its address: make that call before a graph capture starts).  The call
+ * allocates and frees nothing, copies nothing from the host and never synchronises; the
+ * handle's own workspace is not touched.
+ * A call whose planes need more than FS_STATIC_SCRATCH_BYTES (see fs_sketch_plan) returns
+ * FS_ERR_ALLOC and launches nothing; a wiring with M > 2^17 runs without the orbit table
+ * (slower modes, same result up to summation order).  FS_KIND_GAUSS_DENSE works (its matrix was
+ * allocated by create).  All calls on one GPU share the one array, which keeps the last call's
+ * contents: calls that overlap in time on one GPU (two streams, two threads, two handles)
+ * race; order them on one stream or with events. */
+#define FS_STATIC_SCRATCH_BYTES (32u << 20)
+fs_status fs_sketch_apply_static(fs_sketch_t h, const void* A, int64_t lda, int64_t n, void* out,
+                                 int64_t ldo, fs_dtype dtype, void* stream);
+
 /* The same sketch for inputs held examples-as-rows: G is n x d row-major (ld = ldg >= d,
  * every row one vector to sketch, as a pipeline that compresses per-example gradients holds
  * them: Section 7, "End-to-end ML: GraSS for Data Attribution", and Appendix F) and

@@ -23,7 +23,9 @@ SYMBOLS = [
     "fs_sketch_set_workspace", "fs_sketch_set_variant", "fs_sketch_destroy", "fs_status_string",
     "fs_sketch_profile_begin", "fs_sketch_profile_end",
     "fs_sketch_apply_rows", "fs_sketch_rows_workspace_bytes", "fs_sketch_plan", "fs_sketch_prepare",
+    "fs_sketch_apply_static",
 ]
+STATIC_SCRATCH_BYTES = 32 << 20
 PROFILE_KERNEL, PROFILE_APPLY = 1, 2
 PLAN_ELEMENT_LOADS, PLAN_ROW_SLICES, PLAN_SLOT_GROUPS, PLAN_SPLIT = 1, 2, 4, 8
 
@@ -59,6 +61,7 @@ def _load() -> C.CDLL:
     L.fs_sketch_create_kind.argtypes = [C.POINTER(vp), C.c_int, i64, i64, i32, i32, i32, i32, u64]
     L.fs_sketch_apply.argtypes = [vp, vp, i64, i64, vp, C.c_int, vp]
     L.fs_sketch_apply_ld.argtypes = [vp, vp, i64, i64, vp, i64, C.c_int, vp]
+    L.fs_sketch_apply_static.argtypes = [vp, vp, i64, i64, vp, i64, C.c_int, vp]
     L.fs_sketch_apply_rows.argtypes = [vp, vp, i64, i64, vp, i64, C.c_int, vp]
     L.fs_sketch_rows_workspace_bytes.argtypes = [vp, i64, C.c_int, C.POINTER(C.c_size_t)]
     i32p = C.POINTER(C.c_int32)
@@ -209,6 +212,18 @@ class Sketch:
         _check(lib.fs_sketch_apply_ld(self._h, A.data_ptr(), A.stride(0), n, out.data_ptr(),
                                       out.stride(0), _dtype_code(A), _stream_ptr(stream)),
                "fs_sketch_apply_ld")
+        return out
+
+    def apply_static(self, A: torch.Tensor, out: torch.Tensor, stream=None) -> torch.Tensor:
+        """out = S @ A through fs_sketch_apply_static (no allocation: out must be given)."""
+        if A.dim() != 2 or A.shape[0] != self.d or A.stride(1) != 1 and A.shape[1] > 1:
+            raise ValueError("A must be d x n with contiguous rows")
+        n = A.shape[1]
+        if out.shape != (self.k, n) or out.dtype != A.dtype or (out.stride(1) != 1 and n > 1):
+            raise ValueError("out must be k x n, same dtype, contiguous rows")
+        _check(lib.fs_sketch_apply_static(self._h, A.data_ptr(), A.stride(0), n, out.data_ptr(),
+                                          out.stride(0), _dtype_code(A), _stream_ptr(stream)),
+               "fs_sketch_apply_static")
         return out
 
     def apply_rows(self, G: torch.Tensor, out: torch.Tensor | None = None, stream=None) -> torch.Tensor:
