@@ -96,6 +96,14 @@ hipError_t launch_mfma(const SketchParams& p, const void* A, int64_t lda, int64_
                        int64_t ldo, fs_dtype dt, void* ws, const uint32_t* orbit, hipStream_t st,
                        EventPair ev, int* mode, char* desc, size_t desc_cap);
 
+// Output-stationary matrix-core kernel with Phi tiles shared by a work-group (16-bit types, blocks
+// exactly 32, 64 or 128 rows high, no row splits): whether it takes the call, its dynamic LDS, and
+// its launch.  It stores the result itself: no workspace.
+bool outs_supported(const SketchParams& p, const void* A, int64_t lda, int64_t n, fs_dtype dt);
+hipError_t launch_outs(const SketchParams& p, const void* A, int64_t lda, int64_t n, void* out, int64_t ldo,
+                       fs_dtype dt, const uint32_t* orbit, hipStream_t st, EventPair ev, char* desc,
+                       size_t desc_cap);
+
 // Matrix-core path for inputs held examples-as-rows: G is n x d (ld = ldg), out is n x k.
 bool rows_supported(const SketchParams& p, const void* G, int64_t ldg, int64_t n, fs_dtype dt);
 bool rows_describe(const SketchParams& p, const void* G, int64_t ldg, int64_t n, fs_dtype dt, int* mode,

@@ -186,6 +186,80 @@ def test_apply_matches_oracle(case, dtype, variant):
     assert (diff <= tol * (np.abs(ref) + np.sqrt((ref ** 2).mean()))).all()
 
 
+# --------------------- output-stationary kernel with shared Phi tiles -----
+OUTS = [
+    # params (d,k,Bc,Br,kappa,s), n, lda pad, ldo pad, taken: 16-bit output-stationary shapes (k >= d/4
+    # keeps the dispatcher from splitting the rows of these small problems over grid.z)
+    ((8192, 2048, 512, 128, 4, 8), 520, 0, 0, True),     # wide-config block height: four column waves, ragged last tile
+    ((8192, 2048, 512, 128, 4, 8), 200, 0, 0, True),     # two column waves (128 < n <= 256)
+    ((8192, 2048, 512, 128, 4, 8), 1021, 3, 0, True),    # n not a multiple of 4: the last vector straddles n
+    ((4096, 1024, 256, 64, 4, 8), 532, 0, 3, True),      # 64-row blocks, output rows not vector aligned
+    ((4096, 1024, 128, 32, 8, 1), 260, 4, 0, True),      # 32-row blocks, s = 1, two stages per block
+    ((4096, 1024, 256, 64, 4, 12), 300, 4, 0, True),     # s = 12: a lane's share runs into the tail loop
+    ((4096, 2048, 256, 128, 2, 32), 300, 0, 0, True),    # s = 32
+    ((4096, 1024, 256, 64, 16, 3), 300, 0, 0, True),     # kappa = M, odd s
+    ((3900, 1024, 256, 64, 8, 8), 264, 0, 0, True),      # d not a multiple of Bc: a partly filled last block
+    ((3200, 1024, 100, 32, 8, 4), 300, 0, 0, True),      # Bc = 100: the second stage of a block is partly outside it
+    ((6144, 4096, 192, 128, 2, 4), 300, 0, 0, True),     # three stages per block, kappa = 2: six stages
+    ((16384, 8192, 256, 128, 2, 8), 260, 0, 0, True),    # M = 64: orbit renumbering over many blocks
+    ((4096, 1024, 256, 64, 4, 8), 530, 0, 0, False),     # rows not aligned to 4 columns: element loads
+    ((16384, 1024, 2048, 128, 4, 8), 520, 0, 0, False),  # few output tiles: rows split over grid.z
+    ((6144, 4096, 192, 128, 1, 4), 300, 0, 0, False),    # an odd number of stages
+    ((4096, 1024, 256, 64, 4, 8), 100, 0, 0, False),     # a single wave of columns
+]
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float16], ids=["bf16", "f16"])
+@pytest.mark.parametrize("case", OUTS, ids=lambda c: f"{c[0]}-n{c[1]}")
+def test_shared_phi_kernel_matches_oracle(case, dtype):
+    """The 16-bit output-stationary shapes (kappa*Br above one tile, blocks one tile high) run on the
+    kernel whose work-group shares its Phi tiles; element-wise parity, untouched padding, and
+    results that do not depend on where a column sits in the launch."""
+    params, n, pa, po, expect_outs = case
+    print("outs", params, n, dtype, flush=True)
+    seed = 8
+    d, k = params[0], params[1]
+    g = torch.Generator(device=DEV).manual_seed(n + d)
+    Abuf = torch.randn((d + 70, n + pa), generator=g, device=DEV).to(dtype)
+    Abuf[d:] = float("nan")
+    if pa:
+        Abuf[:, n:] = float("nan")
+    A = Abuf[:d, :n]
+    obuf = torch.full((k, n + po), float("nan"), device=DEV, dtype=dtype)
+    sk = B.Sketch(*params, seed=seed)
+    sk.apply(A, obuf[:, :n])
+    torch.cuda.synchronize()
+    i = sk.info()
+    assert i.last_kernel.decode().startswith("outs_kernel") == expect_outs, i.last_kernel
+    assert (i.last_variant, i.last_mode) == (B.VARIANT_MFMA, 1)
+    ref = O.apply(oracle_csc(params, seed), host64(A))
+    check(obuf[:, :n], ref, dtype, "shared-Phi kernel")
+    if po:
+        assert torch.isnan(obuf[:, n:].float()).all(), "wrote outside the n output columns"
+    diff = np.abs(host64(obuf[:, :n]) - ref)
+    assert (diff <= ETOL[dtype] * (np.abs(ref) + np.sqrt((ref ** 2).mean()))).all()
+    # column independence: an aligned 256-column sub-view (two column waves instead of four) gives
+    # the same bits for the shared columns
+    if expect_outs and n >= 516:
+        other = sk.apply(A[:, 260:516])
+        assert sk.info().last_kernel.decode().startswith("outs_kernel")
+        assert torch.equal(other, obuf[:, 260:516])
+
+
+def test_shared_phi_kernel_one_hot_columns_are_exact():
+    params = (8192, 2048, 512, 128, 4, 4)            # kappa*s = 16: the scale is a power of two
+    d = params[0]
+    rng = np.random.default_rng(2)
+    cols = np.unique(np.r_[0, d - 1, params[2] - 1, params[2], rng.integers(0, d, 400)])
+    A = torch.zeros((d, (len(cols) + 3) // 4 * 4), device=DEV, dtype=torch.bfloat16)[:, :len(cols)]  # rows aligned to 4 columns
+    A[torch.from_numpy(cols).to(DEV), torch.arange(len(cols), device=DEV)] = 1.0
+    sk = B.Sketch(*params, seed=0)
+    out = sk.apply(A)
+    torch.cuda.synchronize()
+    assert sk.info().last_kernel.decode().startswith("outs_kernel")
+    assert np.array_equal(host64(out), oracle_csc(params, 0)[:, cols].toarray())
+
+
 # ---------------------------------------------------------- one-hot -------
 @pytest.mark.parametrize("variant", VARIANTS, ids=lambda v: VNAME[v])
 @DTYPES
