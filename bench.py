@@ -63,7 +63,7 @@ def run_steps(sk, A, out, cfg, steps, rows=False):
                 sk.apply(A[:, c0:c1], out[:, c0:c1])
 
 
-def time_workload(torch, B, cfg, A, variant, steps, warmup, kind=None, sketch_params=None, rows=False):
+def time_workload(torch, B, cfg, A, variant, steps, warmup, kind=None, sketch_params=None, rows=False, brackets=2):
     """Wall-clock over `steps` steps plus HIP-event durations of the dominant kernel.
     rows: A is the n x d matrix of the examples-as-rows layout and out is n x k."""
     params = sketch_params or cfg.params
@@ -74,12 +74,12 @@ def time_workload(torch, B, cfg, A, variant, steps, warmup, kind=None, sketch_pa
     run_steps = functools.partial(globals()["run_steps"], rows=rows)
     run_steps(sk, A, out, cfg, warmup)
     torch.cuda.synchronize()
-    # HIP-event brackets on the last four timed steps only: every recorded event costs a few
-    # microseconds of queue time, so bracketing all launches would slow the timed region.  Two
-    # steps bracket the whole apply (one pair around all its kernels, nothing in between), the last
-    # two the dominant kernel alone.  (The host runs far ahead of the GPU, so creating the events
+    # HIP-event brackets on the last 2 x `brackets` timed steps only: every recorded event costs a
+    # few microseconds of queue time, so bracketing all launches would slow the timed region.
+    # `brackets` steps bracket the whole apply (one pair around all its kernels, nothing in
+    # between), the last `brackets` the dominant kernel alone.  (The host runs far ahead of the GPU, so creating the events
     # mid-loop stalls nothing.)
-    n_brk = min(steps // 2, 2)
+    n_brk = min(steps // 2, brackets)
     n_l = len(chunks_of(cfg))
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -290,7 +290,9 @@ def extra_measurements(torch, B, W, dev, skip, with_oracle):
         """kernel_ms: the dominant kernel; apply_ms: everything the apply enqueues (zero-fills, plane
         reductions, conversions included); GBps_A and roofline_frac are computed from apply_ms."""
         try:
-            tm, _ = time_workload(torch, B, cfg, A, "auto", 5, 2, **kw)
+            # (enough warm-up for the clocks to settle: the matrix-core-bound shapes run 10-15 %
+            # slower in their first few launches)
+            tm, _ = time_workload(torch, B, cfg, A, "auto", 24, 8, brackets=8, **kw)
         except B.FlashSketchError as e:
             return {"error": str(e)}
         n_l = len(chunks_of(cfg))

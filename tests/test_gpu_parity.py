@@ -440,13 +440,40 @@ def test_dense_gaussian_matches_oracle(k, d, n, pad, dtype):
 
 
 # ------------------------------------------------ full-size configs -------
-def _sampled_parity(cfg, A, out, ncols=12, seed=0):
-    """Oracle on a sample of columns of the full-size problem."""
+def _sampled_parity(cfg, A, out, seed=0):
+    """Oracle on a sample of columns of the full-size problem: one column, at a random place, from
+    every 128-column wave tile, plus both edges; the bar holds for the sample as a whole and,
+    with a factor for the smaller sample, for every sampled column on its own."""
     rng = np.random.default_rng(seed)
-    cols = np.unique(np.r_[0, cfg.n - 1, rng.integers(0, cfg.n, ncols)])
+    tiles = np.arange(0, cfg.n, 128)
+    cols = np.unique(np.r_[0, cfg.n - 1, np.minimum(tiles + rng.integers(0, 128, len(tiles)), cfg.n - 1)])
     idx = torch.from_numpy(cols).to(A.device)
     ref = O.apply(oracle_csc(cfg.params, cfg.sketch_seed), host64(A[:, idx]))
+    got = host64(out[:, idx])
+    per_col = np.linalg.norm(got - ref, axis=0) / np.linalg.norm(ref, axis=0)
+    assert per_col.max() <= 1.5 * TOL[cfg.dtype], f"{cfg.name}: column {cols[per_col.argmax()]} off by {per_col.max():.3e}"
     return check(out[:, idx], ref, cfg.dtype, f"{cfg.name} sampled columns")
+
+
+def _all_columns_against_the_general_kernel(sk, A, out):
+    """Every column of a full-size result against the general (one-lane-per-column, LDS) kernel, on
+    the device: two kernels that share only the hash recipe.  Both accumulate in fp32 in different
+    orders, so fp32 results agree to rounding of the sum and 16-bit results are equal except where
+    the sum falls next to a rounding boundary (then one unit in the last place)."""
+    sk.set_variant(B.VARIANT_GENERIC)
+    other = sk.apply(A)
+    sk.set_variant(B.VARIANT_AUTO)
+    torch.cuda.synchronize()
+    a, b = out.float(), other.float()
+    rms = float(b.pow(2).mean().sqrt())
+    if out.dtype == torch.float32:
+        assert float((a - b).abs().max()) <= 2e-5 * rms
+    else:
+        ulp = 2.0 ** -7 if out.dtype == torch.bfloat16 else 2.0 ** -10
+        differ = a != b
+        assert float(differ.float().mean()) < 2e-2
+        assert bool(((a - b).abs() <= ulp * b.abs() + 1e-30)[differ].all())
+    assert float((a - b).norm() / b.norm()) <= TOL[out.dtype]
 
 
 @pytest.mark.parametrize("name", ["tiny", "tall"])
@@ -471,16 +498,46 @@ def test_full_config_mid_sampled(kappa):
     out = sk.apply(A)
     torch.cuda.synchronize()
     _sampled_parity(cfg, A, out)
+    if kappa in (1, 4):
+        _all_columns_against_the_general_kernel(sk, A, out)
 
 
-def test_full_config_wide_sampled():
-    cfg = W.CONFIGS["wide"]
-    print("full wide", flush=True)
+@pytest.mark.parametrize("n", W.WIDE_NS)
+def test_full_config_wide_sampled(n):
+    """The bf16 width sweep at full d: n = 1024 and 2048 split the rows of a work-group over
+    grid.z (partial planes), 4096 and 8192 run the shared-Phi kernel."""
+    import dataclasses
+    cfg = dataclasses.replace(W.CONFIGS["wide"], n=n)
+    print("full wide n", n, flush=True)
     A = W.make_input(cfg, DEV)
     sk = B.Sketch(*cfg.params, seed=cfg.sketch_seed)
     out = sk.apply(A)
     torch.cuda.synchronize()
+    assert sk.info().last_kernel.decode().startswith("outs_kernel") == (n >= 4096), sk.info().last_kernel
     _sampled_parity(cfg, A, out)
+    if n in (1024, 8192):
+        _all_columns_against_the_general_kernel(sk, A, out)
+
+
+def test_baseline_kinds_at_the_mid_configurations_full_d():
+    """The two reference points of the mid configuration at its full d = 16384, k = 1024 (fewer
+    columns, so that the oracles stay quick): the plain-SJLT scatter with s = 8 and the dense
+    Gaussian sketch."""
+    from oracle import gaussian as OG
+    cfg = W.CONFIGS["mid"]
+    n = 96
+    A = W.make_input(cfg, DEV, n=n)
+    sc = B.Sketch(cfg.d, cfg.k, cfg.d, cfg.k, 1, cfg.s, seed=cfg.sketch_seed, kind=B.KIND_SJLT_SCATTER)
+    out = sc.apply(A)
+    torch.cuda.synchronize()
+    ref = O.apply(O.build_csc(O.Params(cfg.d, cfg.k, cfg.d, cfg.k, 1, cfg.s), cfg.sketch_seed), host64(A))
+    check(out, ref, torch.float32, "plain SJLT scatter at mid's d")
+    ga = B.Sketch(cfg.d, cfg.k, cfg.d, cfg.k, 1, 1, seed=cfg.sketch_seed, kind=B.KIND_GAUSS_DENSE)
+    A4 = W.make_input(cfg, DEV, n=128)
+    out = ga.apply(A4)
+    torch.cuda.synchronize()
+    ref = OG.apply(OG.gaussian_matrix(cfg.k, cfg.d, cfg.sketch_seed), host64(A4))
+    check(out, ref, torch.float32, "dense Gaussian at mid's d")
 
 
 def test_full_config_grad_chunked_sampled():
@@ -495,7 +552,18 @@ def test_full_config_grad_chunked_sampled():
         sk.apply(A[:, c:c + cfg.chunk], out[:, c:c + cfg.chunk])
     torch.cuda.synchronize()
     print("  applied; oracle on sampled columns", flush=True)
-    _sampled_parity(cfg, A, out, ncols=6)
+    _sampled_parity(cfg, A, out)
+    # the same chunks as four separate packed d x 256 buffers (lda = 256), as a pipeline that hands
+    # over one chunk at a time holds them: the same bits
+    packed = torch.empty_like(out)
+    for c in range(0, cfg.n, cfg.chunk):
+        buf = A[:, c:c + cfg.chunk].contiguous()
+        sk.apply(buf, packed[:, c:c + cfg.chunk])
+        del buf
+    torch.cuda.synchronize()
+    assert torch.equal(packed, out)
+    # and every column of one chunk against the general kernel
+    _all_columns_against_the_general_kernel(sk, A[:, :cfg.chunk], out[:, :cfg.chunk].contiguous())
 
 
 def test_full_config_grad_rows_layout_sampled():
