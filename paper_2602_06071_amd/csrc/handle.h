@@ -104,6 +104,15 @@ hipError_t launch_outs(const SketchParams& p, const void* A, int64_t lda, int64_
                        fs_dtype dt, const uint32_t* orbit, hipStream_t st, EventPair ev, char* desc,
                        size_t desc_cap);
 
+// Matrix-core kernel that keeps several output blocks, consecutive on the orbit of the wiring, in one
+// wave's accumulators (blocks exactly 64 rows high, or 128 for fp32; the slot count divides kappa and
+// M; needs the orbit table): whether it takes the call, and its launch.  It stores the result
+// itself: no workspace.
+bool stacked_supported(const SketchParams& p, const void* A, int64_t lda, int64_t n, fs_dtype dt, bool have_orbit);
+hipError_t launch_stacked(const SketchParams& p, const void* A, int64_t lda, int64_t n, void* out, int64_t ldo,
+                          fs_dtype dt, const uint32_t* orbit, hipStream_t st, EventPair ev, char* desc,
+                          size_t desc_cap);
+
 // Matrix-core path for inputs held examples-as-rows: G is n x d (ld = ldg), out is n x k.
 bool rows_supported(const SketchParams& p, const void* G, int64_t ldg, int64_t n, fs_dtype dt);
 bool rows_describe(const SketchParams& p, const void* G, int64_t ldg, int64_t n, fs_dtype dt, int* mode,

@@ -171,9 +171,16 @@ Plan make_plan(const SketchParams& p, const void* A, int64_t lda, int64_t n, fs_
   // 16-bit output-stationary shapes without row splits or slices go to the kernel whose work-group
   // shares its Phi tiles (measured on the "wide" workload: 0.445 against 0.52 ms)
   pl.outs = !pl.in_stat && pl.zsplit == 1 && pl.nsub == 1 && !pl.unal && outs_supported(p, A, lda, n, dt);
+  // Shapes the kernel with several output blocks per wave takes go there (it loads A from L2
+  // (kappa+S-1)/S times per output block, not kappa times; measured on "mid": kappa = 4, 0.365
+  // against 0.395 ms, kappa = 8, 0.63 against 0.74 ms).  It stores the result itself.
+  if (stacked_supported(p, A, lda, n, dt, have_orbit)) {
+    pl.stacked = true; pl.unal = false; pl.outs = false; pl.in_stat = false; pl.run = 1; pl.planes = 0;
+    pl.zsplit = 1; pl.nsub = 1; pl.groups = 1;
+  }
   pl.lds = lds_bytes(pl.mt, pl.nrg, pl.ncg, pl.run,
                      pl.run > 1 ? (size_t)(p.kappa + pl.run - 1) * p.Br * 256 * 4 : 0);
-  pl.ok = pl.lds <= kLdsBudget;
+  pl.ok = pl.stacked || pl.lds <= kLdsBudget;
   return pl;
 }
 
@@ -214,6 +221,7 @@ hipError_t launch_mfma(const SketchParams& p, const void* A, int64_t lda, int64_
   const Plan pl = make_plan(p, A, lda, n, dt, orbit != nullptr);
   if (!pl.ok) return hipErrorInvalidValue;
   *mode = !pl.in_stat ? 1 : pl.run > 1 ? 3 : 2;
+  if (pl.stacked) return launch_stacked(p, A, lda, n, out, ldo, dt, orbit, st, ev, desc, desc_cap);
   if (pl.outs) return launch_outs(p, A, lda, n, out, ldo, dt, orbit, st, ev, desc, desc_cap);
   if (desc && desc_cap)  // the template arguments of the instantiation launched below, in order
     snprintf(desc, desc_cap, "mfma_kernel<%s,%d,%d,%d,%s,%d,%d,%d,%s,%s>%s",

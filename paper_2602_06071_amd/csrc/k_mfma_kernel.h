@@ -36,6 +36,7 @@ struct Plan {
   int groups = 1, group_slots = 0;  // IN: slot groups (A is read once per group)
   int nsub = 1;                     // OUT: 128-row slices of an output block
   bool unal = false;                // A or lda not aligned to 4 columns: element-wise loads
+  bool stacked = false;             // several output blocks per wave: the kernel of k_stacked.hip
   bool outs = false;                // OUT, 16-bit: the kernel of k_outs.hip (work-group-shared Phi tiles)
   int64_t ldw = 0;
   int planes = 0;

@@ -246,6 +246,84 @@ def test_shared_phi_kernel_matches_oracle(case, dtype):
         assert torch.equal(other, obuf[:, 260:516])
 
 
+# --------------------- several output blocks per wave ----------------------
+STACKED = [
+    # params (d,k,Bc,Br,kappa,s), n, lda pad, ldo pad, dtypes, taken.  The kernel wants at least 192
+    # work-groups of (4 or 2 output blocks) x 256 columns, so M and n are larger than elsewhere.
+    ((8192, 4096, 128, 64, 4, 8), 3584, 0, 0, "f32 bf16 f16", True),     # kappa = S = 4: one phase of one block, three of two
+    ((8192, 4096, 128, 64, 8, 8), 3070, 2, 3, "f32 bf16", True),         # kappa = 8; ragged last tile, padded rows, element stores
+    ((12750, 4096, 200, 64, 12, 5), 3074, 0, 0, "f32 f16", True),        # Bc = 200: a stage partly outside its block; d short of M*Bc; odd s
+    ((8192, 4096, 128, 64, 4, 1), 3072, 0, 0, "f32 bf16", True),         # s = 1
+    ((8192, 4096, 128, 64, 4, 20), 3072, 0, 0, "f32 bf16", True),        # s = 20: the tail loop over a row's nonzeros
+    ((2048, 1024, 128, 64, 16, 3), 12288, 0, 0, "f32", True),            # kappa = M: the window wraps round the orbit
+    ((16384, 8192, 256, 128, 6, 12), 2048, 0, 0, "f32", True),           # 128-row blocks: two slots; s = 12
+    ((16384, 8192, 256, 128, 2, 8), 2050, 0, 0, "f32", True),            # kappa = S = 2
+    ((16384, 8192, 256, 128, 2, 8), 2048, 0, 0, "bf16", False),          # 16-bit, 128 rows: one block per work-group is faster
+    ((8192, 4096, 128, 64, 6, 8), 3072, 0, 0, "f32", False),             # kappa not a multiple of the slot count
+    ((8192, 4096, 128, 64, 4, 8), 3071, 1, 0, "f32", False),             # odd n
+    ((8192, 4096, 128, 64, 4, 8), 2048, 0, 0, "f32", False),             # too few work-groups for the chip
+    ((12288, 4096, 192, 64, 4, 8), 3072, 0, 0, "f32", False),           # an odd number of stages per block
+]
+_DT = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}
+STACKED_RUNS = [(c, _DT[t]) for c in STACKED for t in c[4].split()]
+
+
+@pytest.mark.parametrize("case,dtype", STACKED_RUNS,
+                         ids=[f"{c[0]}-n{c[1]}-{str(t).split('.')[1]}" for c, t in STACKED_RUNS])
+def test_stacked_kernel_matches_oracle(case, dtype):
+    """Shapes with 64-row blocks (or 128-row, fp32) and kappa a multiple of the slot count run on the
+    kernel that keeps several consecutive output blocks of the wiring's orbit in one wave's
+    accumulators; element-wise parity, untouched padding."""
+    params, n, pa, po, _, expect = case
+    print("stacked", params, n, dtype, flush=True)
+    seed = 12
+    d, k = params[0], params[1]
+    g = torch.Generator(device=DEV).manual_seed(n + d)
+    Abuf = torch.randn((d + 70, n + pa), generator=g, device=DEV).to(dtype)
+    Abuf[d:] = float("nan")
+    if pa:
+        Abuf[:, n:] = float("nan")
+    A = Abuf[:d, :n]
+    obuf = torch.full((k, n + po), float("nan"), device=DEV, dtype=dtype)
+    sk = B.Sketch(*params, seed=seed)
+    plan = sk.plan(n, dtype, ld=A.stride(0), address=A.data_ptr())
+    sk.apply(A, obuf[:, :n])
+    torch.cuda.synchronize()
+    i = sk.info()
+    assert i.last_kernel.decode().startswith("stacked_kernel") == expect, i.last_kernel
+    assert (plan["variant"], plan["mode"]) == (i.last_variant, i.last_mode)
+    if expect:
+        assert (i.last_variant, i.last_mode, plan["workspace_bytes"]) == (B.VARIANT_MFMA, 1, 0)
+    ref = O.apply(oracle_csc(params, seed), host64(A))
+    check(obuf[:, :n], ref, dtype, "stacked kernel")
+    if po:
+        assert torch.isnan(obuf[:, n:].float()).all(), "wrote outside the n output columns"
+    diff = np.abs(host64(obuf[:, :n]) - ref)
+    assert (diff <= ETOL[dtype] * (np.abs(ref) + np.sqrt((ref ** 2).mean()))).all()
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16], ids=["f32", "bf16"])
+def test_stacked_kernel_one_hot_columns_are_exact_and_columns_independent(dtype):
+    params = (8192, 4096, 128, 64, 4, 4)             # kappa*s = 16: the scale is a power of two
+    d, n = params[0], 3584
+    rng = np.random.default_rng(5)
+    rows = np.r_[0, d - 1, params[2] - 1, params[2], rng.integers(0, d, n - 4)]
+    A = torch.zeros((d, n), device=DEV, dtype=dtype)
+    A[torch.from_numpy(rows).to(DEV), torch.arange(n, device=DEV)] = 1.0
+    sk = B.Sketch(*params, seed=0)
+    out = sk.apply(A)
+    torch.cuda.synchronize()
+    assert sk.info().last_kernel.decode().startswith("stacked_kernel")
+    assert np.array_equal(host64(out), oracle_csc(params, 0)[:, rows].toarray())
+    # a sub-view (other column tiles, other work-groups) gives the same bits for the shared columns
+    g = torch.Generator(device=DEV).manual_seed(1)
+    R = torch.randn((d, n), generator=g, device=DEV).to(dtype)
+    full = sk.apply(R)
+    part = sk.apply(R[:, 512:])
+    assert sk.info().last_kernel.decode().startswith("stacked_kernel")
+    assert torch.equal(part, full[:, 512:])
+
+
 def test_shared_phi_kernel_one_hot_columns_are_exact():
     params = (8192, 2048, 512, 128, 4, 4)            # kappa*s = 16: the scale is a power of two
     d = params[0]
