@@ -39,12 +39,14 @@ def parse():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="grad", choices=["tiny", "mid", "tall", "wide", "grad"])
+    ap.add_argument("--kappa", type=int, default=0, help="override the workload's kappa (profiling runs of mid and wide)")
     ap.add_argument("--variant", default="auto", choices=["auto", "generic", "mfma"])
     ap.add_argument("--layout", default="cols", choices=["cols", "rows"],
                     help="cols: A is d x n, vectors are columns (the default, the metric's workload); "
                          "rows: the same data held n x d, vectors are rows (fs_sketch_apply_rows)")
     ap.add_argument("--ld-pad", type=int, default=64, help="rows layout: row stride = d + this many elements")
     ap.add_argument("--no-extra", action="store_true", help="skip the side measurements")
+    ap.add_argument("--extras", default="", help="run only these side measurements (known: tall_cold)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     return ap.parse_args()
 
@@ -206,6 +208,9 @@ def main():
     torch.cuda.set_device(0)
     dev = "cuda:0"
     cfg = W.CONFIGS[args.workload]
+    if args.kappa:
+        import dataclasses
+        cfg = dataclasses.replace(cfg, kappa=args.kappa)
     A = W.make_input(cfg, dev)
     torch.cuda.synchronize()
 
@@ -273,14 +278,18 @@ def main():
         rec["rel_fro_err_vs_oracle_on_sample"] = err
 
     if not args.no_extra and not rows:
-        rec["extra"] = extra_measurements(torch, B, W, dev, cfg.name, with_oracle=not args.no_cpu)
+        only = set(args.extras.split(",")) if args.extras else None
+        rec["extra"] = extra_measurements(torch, B, W, dev, cfg.name, with_oracle=not args.no_cpu, only=only)
+        if only is not None:
+            print(json.dumps(rec))
+            return
         if cfg.name == "grad":
             rec["extra"].update(grad_side_measurements(torch, B, cfg, A, out))
         rec["extra"]["rows_layout"] = rows_layout_measurement(torch, B, cfg, A, out)
     print(json.dumps(rec))
 
 
-def extra_measurements(torch, B, W, dev, skip, with_oracle):
+def extra_measurements(torch, B, W, dev, skip, with_oracle, only=None):
     """Short side measurements on the other configurations (kernel time by HIP
     events, 5 launches each): the kappa sweep with the plain-SJLT scatter and
     dense-Gaussian reference points, the tall matrix, and the bf16 width sweep."""
@@ -302,15 +311,23 @@ def extra_measurements(torch, B, W, dev, skip, with_oracle):
                 "roofline_frac": alg / tm.apply_s / 1e9 / HBM_PEAK_GBPS,
                 "variant": tm.variant, "kernel": tm.kernel}
 
-    def cold(cfg, A, reps=5):
-        """Kernel time of single applies, each after 2 GiB of unrelated writes have gone through the
-        caches (L2 and the 256 MB Infinity Cache hold nothing of A or of the workspace)."""
+    def cold(cfg, A, flush, reps=5):
+        """Kernel time of single applies, each after 2 GiB of unrelated traffic has gone through the
+        caches, so that L2 and the 256 MB Infinity Cache hold nothing of A or of the workspace.
+        flush = "write": the 2 GiB are written (the caches are left full of DIRTY lines, which the
+        apply's own fetches then have to push out to HBM first); flush = "read": they are only read
+        (clean lines, dropped for free).  The difference between the two is the write-back, not the
+        kernel."""
         sk = B.Sketch(*cfg.params, seed=cfg.sketch_seed)
         out = sk.apply(A)
         junk = torch.empty(1 << 29, device=dev, dtype=torch.float32)
+        junk.fill_(1.0)
         ms, ms_all = [], []
         for i in range(reps):
-            junk.fill_(float(i))
+            if flush == "write":
+                junk.fill_(float(i))
+            else:
+                junk.sum()
             sk.profile_begin(1)
             sk.apply(A, out)
             k_ms, a_ms = sk.profile_end(whole=True)
@@ -318,16 +335,25 @@ def extra_measurements(torch, B, W, dev, skip, with_oracle):
             ms_all += a_ms
         sk.close()
         t = sum(ms_all) / len(ms_all) / 1e3
-        return {"kernel_ms": sum(ms) / len(ms), "apply_ms": t * 1e3, "GBps_A": cfg.a_bytes / t / 1e9,
+        return {"flush": "2 GiB of " + flush + "s", "kernel_ms": sum(ms) / len(ms), "apply_ms": t * 1e3,
+                "GBps_A": cfg.a_bytes / t / 1e9,
                 "roofline_frac": (cfg.a_bytes + cfg.k * cfg.n * cfg.elt) / t / 1e9 / HBM_PEAK_GBPS}
 
+    if only is not None:  # --extras tall_cold: just that pair (profiling runs)
+        assert only == {"tall_cold"}, "--extras knows: tall_cold"
+        cfg = W.CONFIGS["tall"]
+        A = W.make_input(cfg, dev)
+        res["tall_cold"] = cold(cfg, A, "write")
+        res["tall_cold_after_reads"] = cold(cfg, A, "read")
+        return res
     for name in ("tiny", "tall"):
         if name != skip:
             cfg = W.CONFIGS[name]
             A = W.make_input(cfg, dev)
             res[name] = one(cfg, A)
             if name == "tall":  # 256 MiB: about the size of the Infinity Cache, so also time it cold
-                res["tall_cold"] = cold(cfg, A)
+                res["tall_cold"] = cold(cfg, A, "write")
+                res["tall_cold_after_reads"] = cold(cfg, A, "read")
             del A
     if skip != "tall":
         res["tall_ose"] = tall_distortion(torch, B, W, dev, with_oracle)

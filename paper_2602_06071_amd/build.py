@@ -1,6 +1,10 @@
 """Builds libflashsketch.so for gfx950 with hipcc, in-tree, next to this file.
 
-    python -m paper_2602_06071_amd.build [--force]
+    python -m paper_2602_06071_amd.build [--force] [--define NAME]... [--output PATH]
+
+--define adds -DNAME to every compile (the kernels' FS_ABLATE_* switches); with --output the
+objects go to a folder next to PATH and the library to PATH, and the in-tree library is left alone
+(load such a library with FLASHSKETCH_LIB=PATH).
 
 Each csrc/*.hip file is compiled to an object of its own (so an edit recompiles
 one file) and the objects are linked into one shared library with the C ABI
@@ -42,7 +46,12 @@ def _stale(src: str, obj: str, headers: list[str]) -> bool:
     return any(os.path.getmtime(f) > t for f in [src, __file__] + headers)
 
 
-def build(force: bool = False, verbose: bool = True) -> str:
+def build(force: bool = False, verbose: bool = True, defines: tuple = (), output: str | None = None) -> str:
+    global OBJ, LIB
+    if output:
+        LIB = os.path.abspath(output)
+        OBJ = os.path.join(os.path.dirname(LIB), "_build")
+        force = True
     os.makedirs(OBJ, exist_ok=True)
     cc = hipcc()
     headers = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")]
@@ -57,7 +66,7 @@ def build(force: bool = False, verbose: bool = True) -> str:
 
     def compile_one(job):
         src, obj = job
-        cmd = [cc, *FLAGS, "-c", src, "-o", obj]
+        cmd = [cc, *FLAGS, *[f"-D{d}" for d in defines], "-c", src, "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         return src, r
 
@@ -84,4 +93,10 @@ def build(force: bool = False, verbose: bool = True) -> str:
 
 
 if __name__ == "__main__":
-    build(force="--force" in sys.argv)
+    import argparse
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--force", action="store_true")
+    ap.add_argument("--define", action="append", default=[])
+    ap.add_argument("--output")
+    a = ap.parse_args()
+    build(force=a.force, defines=tuple(a.define), output=a.output)

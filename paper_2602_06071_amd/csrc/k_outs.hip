@@ -21,6 +21,9 @@
 //
 // A goes HBM -> registers -> v_perm transpose -> MFMA B operand exactly as in mfma_kernel.
 // Inputs must be finite (a dense product also multiplies by the zeros of Phi).
+//
+// FS_ABLATE_LOADS / FS_ABLATE_FILL: compile-time switches for timing the kernel with the loads of A
+// (after the prologue) or the making of Phi taken out (wrong results; never defined in the shipped build).
 #include <stdio.h>
 
 #include <type_traits>
@@ -133,7 +136,13 @@ void outs_kernel(OutsArgs a) {
   uint32_t f_voff = voff0, f_us = 0, f_l = 0;
   const uint32_t spb = (uint32_t)a.spb;
   V ld[PFD][8];
+#ifdef FS_ABLATE_LOADS
+  bool loads_on = true;  // ablation build: only the prologue loads A, the ring keeps that data
+#endif
   auto issue = [&](V (&dst)[8]) {
+#ifdef FS_ABLATE_LOADS
+    if (loads_on)
+#endif
 #pragma unroll
     for (int j = 0; j < 8; ++j)
       dst[j] = __builtin_bit_cast(V, __builtin_amdgcn_raw_buffer_load_b64(f_rs, f_voff, soff[j], 0));
@@ -164,6 +173,9 @@ void outs_kernel(OutsArgs a) {
     pr = (pr + pstep) & (p.Br - 1);
   };
   auto fill = [&](uint16_t* tile, int part) {
+#ifdef FS_ABLATE_FILL
+    return;  // ablation build: Phi stays zero
+#endif
     if (part == 0) {
 #pragma unroll
       for (int i = 0; i < RWV * UPR / 64; ++i) {
@@ -233,7 +245,9 @@ void outs_kernel(OutsArgs a) {
 #pragma unroll
       for (int c = 0; c < 4; ++c)
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) acc[mt][c] = mfma<T>(pa[mt], op[c], acc[mt][c]);
+        for (int mt = 0; mt < MT; ++mt) {
+          acc[mt][c] = mfma<T>(pa[mt], op[c], acc[mt][c]);
+        }
       // spread the rest evenly between the MFMAs
 #pragma unroll
       for (int i = 0; i < 4 * MT; ++i) {
@@ -267,6 +281,9 @@ void outs_kernel(OutsArgs a) {
   fill(s_phi, 2);
   fill_stage_end();
   lds_barrier();
+#ifdef FS_ABLATE_LOADS
+  loads_on = false;
+#endif
   read_pa(s_phi, 0, pa2[0]);
   using P0 = std::integral_constant<int, 0>;
   using P1 = std::integral_constant<int, 1>;

@@ -51,6 +51,9 @@
 // blocks exactly 64 (S = 4) or 128 (S = 2, fp32 only: for 16-bit types the kernel with one block
 // per work-group is the faster one there) rows high.
 // Inputs must be finite (a dense product also multiplies by the zeros of Phi).
+//
+// FS_ABLATE_LOADS / FS_ABLATE_FILL: compile-time switches for timing the kernel with the loads of A
+// (after the prologue) or the making of Phi taken out (wrong results; never defined in the shipped build).
 #include <stdio.h>
 
 #include <type_traits>
@@ -199,9 +202,15 @@ void stacked_kernel(StackedArgs a) {
   };
   load_fetch_phase();
   V ld[PFD][8];
+#ifdef FS_ABLATE_LOADS
+  bool loads_on = true;  // ablation build: only the prologue loads A, the ring keeps that data
+#endif
   // the next sub-step of the sequence (no branches: a k-step stays one scheduling region)
   auto issue = [&](V (&dst)[8]) {
     const __amdgpu_buffer_rsrc_t rs = f_second ? f_rsy : f_rsx;
+#ifdef FS_ABLATE_LOADS
+    if (loads_on)
+#endif
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       if constexpr (F32)
@@ -261,6 +270,9 @@ void stacked_kernel(StackedArgs a) {
   // part 0 clears the K-slice and hashes, parts 1 to 4 write NPUT / 4 nonzeros each; part 6 (rarely
   // needed: s > 8) loops over the remaining nonzeros.
   auto fill = [&](uint16_t* tile, int part) {
+#ifdef FS_ABLATE_FILL
+    return;  // ablation build: Phi stays zero
+#endif
     if (part == 0) {
 #pragma unroll
       for (int u = 0; u < R * UPR / 64; ++u) {
@@ -442,6 +454,9 @@ void stacked_kernel(StackedArgs a) {
   for (int part = 0; part < 7; ++part) fill(s_phi, part);
   fill_stage_end();
   lds_barrier();
+#ifdef FS_ABLATE_LOADS
+  loads_on = false;
+#endif
 #pragma unroll
   for (int i = 0; i < S; ++i) read_slot(s_phi, 0, i, pa2[0]);
 
