@@ -16,12 +16,17 @@
 // directly, scaled, by the one wave that owns it: no partial planes, no second kernel, no
 // atomics, a fixed summation order.
 //
-//  * Phases.  The inputs are taken in kappa phases: phase ph takes the inputs whose orbit position
-//    is ph modulo kappa, in every work-group.  A work-group's window of kappa+S-1 positions holds
-//    one such input or two; one feeds all S slots, two feed the slots 0..m-1 and m..S-1.  So every
-//    phase is the same work in every work-group (each slot gets exactly one block), all readers
-//    of an input block read it in the same phase, stage by stage, and all but the first hit L2:
-//    HBM sees A once (measured: the same fetch size as the output-stationary kernel).
+//  * Phases.  The inputs are taken in kappa phases: a phase takes the inputs whose orbit position
+//    has one residue modulo kappa, the same residue in every work-group.  A work-group's window
+//    of kappa+S-1 positions holds one such input or two; one feeds all S slots, two feed the slots
+//    0..m-1 and m..S-1.  So every phase is the same matrix work in every work-group (each slot
+//    gets exactly one block), all readers of an input block read it in the same phase, stage by
+//    stage, and all but the first hit L2: with kappa = S HBM sees A once (measured: the same fetch
+//    size as the output-stationary kernel).  With kappa = 2S, 3S, .. there are kappa/S kinds of
+//    work-group whose two-block phases (a little slower: two loads, two splits per k-step) fall
+//    on different residues; the residues are taken in an order that alternates between the kinds,
+//    which keeps them within one such difference of each other (kappa = 2S: A is fetched 1.4
+//    times; in plain residue order 1.75 times).
 //  * A phase of two blocks walks both together: per k-step the 16 rows of the first block for its
 //    slots, then the same rows of the second for the others, against ONE Phi tile whose slot i
 //    was hashed with the block that feeds slot i.  Phi is made kappa times per output block, as in
@@ -129,11 +134,19 @@ void stacked_kernel(StackedArgs a) {
     jt = id / gridDim.x;
   }
   const uint32_t pos0 = grp * S;  // orbit position of slot 0
-  // Phase ph takes the inputs whose orbit position is ph modulo kappa.  The first of them in the
-  // window pos0+1 .. pos0+kappa+S-1 is input j (position pos0+1+j) with j < kappa; it feeds the
-  // slots 0..j.  If j <= S-2 the window holds a second one, input j+kappa, for the slots j+1..S-1.
+  // A phase takes the inputs whose orbit position has one residue modulo kappa.  The first of them
+  // in the window pos0+1 .. pos0+kappa+S-1 is input j (position pos0+1+j) with j < kappa; it feeds
+  // the slots 0..j.  If j <= S-2 the window holds a second one, input j+kappa, for the slots
+  // j+1..S-1.  Phase number ph takes the residue (ph % KS) S + ph / KS, KS = kappa / S: a group
+  // whose first position is t S modulo kappa has its two-block phases at the residues t S + 1 ..
+  // t S + S-1, and in this order they are the phases t + KS, t + 2 KS, ..: between the two-block
+  // phases of one kind of group come those of the others, so the kinds (their two-block phases
+  // take a little longer) never get more than one such difference apart, and stay close enough
+  // for the second reader of a block to find it in L2.
+  const uint32_t KS = p.kappa / (uint32_t)S;
   for (uint32_t ph = tid; ph < NPH; ph += NT) {
-    const uint32_t j = (ph + p.kappa - (pos0 + 1) % p.kappa) % p.kappa;
+    const uint32_t res = (ph % KS) * (uint32_t)S + ph / KS;
+    const uint32_t j = (res + p.kappa - (pos0 + 1) % p.kappa) % p.kappa;
     const bool two = j + 1 < (uint32_t)S;
     const uint32_t hx = a.pos2blk[(pos0 + 1 + j) % p.M];
     const uint32_t hy = two ? a.pos2blk[(pos0 + 1 + j + p.kappa) % p.M] : hx;
@@ -463,9 +476,9 @@ void stacked_kernel(StackedArgs a) {
   // ---- the walk over the phases and stages ------------------------------------------------------------
   using P0 = std::integral_constant<int, 0>;
   using P1 = std::integral_constant<int, 1>;
-  // With S | kappa the first input of phase 0 is input j0 >= S-1, so the phases come as: kappa - j0
-  // phases of one block, the S-1 phases of two blocks with 1, 2, .. S-1 slots on the first, then
-  // j0 - (S-1) more phases of one block.  (Straight-line code, one loop per shape and no choice
+  // With S | kappa a group of kind t (first position t S modulo kappa) has phases of one block
+  // except the phases t + i KS, i = 1 .. S-1, which have two with i slots on the first.  So the
+  // walk is a fixed sequence of loops.  (Straight-line code, one loop per shape and no choice
   // inside a loop: with a choice the register allocator gives the accumulators different homes in
   // the branches and moves them at every join.)
   auto run = [&](auto m_tag, uint32_t phases) __attribute__((always_inline)) {
@@ -480,14 +493,16 @@ void stacked_kernel(StackedArgs a) {
       }
     }
   };
-  const uint32_t j0 = (p.kappa - (pos0 + 1) % p.kappa) % p.kappa;
-  run(std::integral_constant<int, S>{}, p.kappa - j0);
+  const uint32_t kind = (pos0 / (uint32_t)S) % KS;
+  run(std::integral_constant<int, S>{}, KS + kind);
   run(std::integral_constant<int, 1>{}, 1);
   if constexpr (S >= 4) {
+    run(std::integral_constant<int, S>{}, KS - 1);
     run(std::integral_constant<int, 2>{}, 1);
+    run(std::integral_constant<int, S>{}, KS - 1);
     run(std::integral_constant<int, 3>{}, 1);
   }
-  run(std::integral_constant<int, S>{}, j0 - (uint32_t)(S - 1));
+  run(std::integral_constant<int, S>{}, KS - 1 - kind);
 
   // ---- epilogue: scale, convert, store the S blocks ---------------------------------------------------
   // accumulator register r of tile (i, mt, c) holds row mt*32 + 8*(r/4) + 4*kg + r%4 of the block
