@@ -222,7 +222,9 @@ typedef enum {
   FS_PLAN_ROW_SLICES = 2,    /* output blocks higher than 128 rows, served in 128-row slices   */
   FS_PLAN_SLOT_GROUPS = 4,   /* more than 128 stacked rows of small blocks: input read once
                                 per group of wiring slots                                      */
-  FS_PLAN_SPLIT = 8          /* the rows of a work-group's input are split over grid.z         */
+  FS_PLAN_SPLIT = 8,         /* the rows of a work-group's input are split over grid.z         */
+  FS_PLAN_STACKED = 16       /* output-stationary with several output blocks, consecutive on
+                                the orbit of the wiring, per wave (mode 1, no workspace)       */
 } fs_plan_flags;
 fs_status fs_sketch_plan(fs_sketch_t h, const void* A, int64_t ld, int64_t n, fs_dtype dtype,
                          int32_t rows, int32_t* variant, int32_t* mode, int32_t* flags,

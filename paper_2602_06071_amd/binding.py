@@ -27,7 +27,7 @@ SYMBOLS = [
 ]
 STATIC_SCRATCH_BYTES = 32 << 20
 PROFILE_KERNEL, PROFILE_APPLY = 1, 2
-PLAN_ELEMENT_LOADS, PLAN_ROW_SLICES, PLAN_SLOT_GROUPS, PLAN_SPLIT = 1, 2, 4, 8
+PLAN_ELEMENT_LOADS, PLAN_ROW_SLICES, PLAN_SLOT_GROUPS, PLAN_SPLIT, PLAN_STACKED = 1, 2, 4, 8, 16
 
 
 class FlashSketchError(RuntimeError):

@@ -198,7 +198,8 @@ bool mfma_describe(const SketchParams& p, const void* A, int64_t lda, int64_t n,
   if (!pl.ok) return false;
   *mode = !pl.in_stat ? 1 : pl.run > 1 ? 3 : 2;
   *flags = (pl.unal ? FS_PLAN_ELEMENT_LOADS : 0) | (pl.nsub > 1 ? FS_PLAN_ROW_SLICES : 0) |
-           (pl.groups > 1 ? FS_PLAN_SLOT_GROUPS : 0) | (pl.zsplit > 1 ? FS_PLAN_SPLIT : 0);
+           (pl.groups > 1 ? FS_PLAN_SLOT_GROUPS : 0) | (pl.zsplit > 1 ? FS_PLAN_SPLIT : 0) |
+           (pl.stacked ? FS_PLAN_STACKED : 0);
   *workspace = (size_t)pl.planes * (size_t)p.k * (size_t)pl.ldw * sizeof(float);
   return true;
 }

@@ -292,6 +292,7 @@ def test_stacked_kernel_matches_oracle(case, dtype):
     i = sk.info()
     assert i.last_kernel.decode().startswith("stacked_kernel") == expect, i.last_kernel
     assert (plan["variant"], plan["mode"]) == (i.last_variant, i.last_mode)
+    assert bool(plan["flags"] & B.PLAN_STACKED) == expect, plan
     if expect:
         assert (i.last_variant, i.last_mode, plan["workspace_bytes"]) == (B.VARIANT_MFMA, 1, 0)
     ref = O.apply(oracle_csc(params, seed), host64(A))

@@ -11,7 +11,7 @@ from paper_2602_06071_amd import workloads as W
 
 GENERIC, MFMA = B.VARIANT_GENERIC, B.VARIANT_MFMA
 OUT, IN, RUNS = 1, 2, 3
-EL, SL, GR, SP = B.PLAN_ELEMENT_LOADS, B.PLAN_ROW_SLICES, B.PLAN_SLOT_GROUPS, B.PLAN_SPLIT
+EL, SL, GR, SP, ST = B.PLAN_ELEMENT_LOADS, B.PLAN_ROW_SLICES, B.PLAN_SLOT_GROUPS, B.PLAN_SPLIT, B.PLAN_STACKED
 
 
 def plan(params, n, dtype, **kw):
@@ -29,11 +29,13 @@ def test_the_five_configurations_take_the_decompositions_they_were_designed_for(
         n = cfg.chunk or cfg.n
         p = plan(cfg.params, n, cfg.dtype, ld=cfg.n)
         assert (p["variant"], p["mode"], p["flags"]) == (MFMA, mode, flags), (name, p)
-    for kappa, mode in ((1, OUT), (2, OUT), (4, OUT), (8, OUT)):  # (kappa = 2: the planes would cost more than the re-read)
+    # mid: output-stationary throughout (kappa = 2: the planes would cost more than the re-read); from
+    # kappa = 4 on with four output blocks per wave
+    for kappa, flags in ((1, 0), (2, 0), (4, ST), (8, ST)):
         cfg = W.CONFIGS["mid"]
         params = cfg.params[:4] + (kappa,) + cfg.params[5:]
         p = plan(params, cfg.n, cfg.dtype)
-        assert (p["variant"], p["mode"]) == (MFMA, mode), (kappa, p)
+        assert (p["variant"], p["mode"], p["flags"], p["workspace_bytes"]) == (MFMA, OUT, flags, 0), (kappa, p)
     # the gradient chunk: three merged planes of 8192 x 256 floats
     assert plan(W.CONFIGS["grad"].params, 256, torch.bfloat16, ld=1024)["workspace_bytes"] == 3 * 8192 * 256 * 4
 
@@ -114,3 +116,23 @@ def test_plan_honours_the_forced_variant_and_reports_errors():
         sc.plan(100, torch.bfloat16, rows=True)
     assert e.value.status == 2
     sc.close()
+
+
+@pytest.mark.parametrize("params,n,dtype,kw,stacked", [
+    ((16384, 1024, 1024, 64, 4, 8), 16384, torch.float32, {}, True),      # mid
+    ((16384, 1024, 1024, 64, 4, 8), 16384, torch.bfloat16, {}, True),     # 64-row blocks: 16-bit too
+    ((16384, 2048, 1024, 128, 2, 8), 16384, torch.float32, {}, True),     # 128-row blocks, fp32: two per wave
+    ((65536, 4096, 2048, 128, 4, 8), 8192, torch.bfloat16, {}, False),    # wide: 16-bit 128-row blocks stay with one block per work-group
+    ((16384, 1024, 1024, 64, 6, 8), 16384, torch.float32, {}, False),     # kappa not a multiple of the 4 slots
+    ((16384, 1024, 1024, 64, 2, 8), 16384, torch.float32, {}, False),     # fewer permutations than slots
+    ((16384, 1024, 1024, 64, 4, 8), 16383, torch.float32, {"ld": 16384}, False),  # odd n
+    ((16384, 1024, 1024, 64, 4, 8), 16384, torch.float32, {"address": 260}, False),  # A not aligned to 2 columns
+    ((16384, 1024, 1024, 64, 4, 8), 8192, torch.float32, {}, False),      # 4 groups x 32 column tiles: too few work-groups
+    ((12288, 4096, 192, 64, 4, 8), 4096, torch.float32, {}, False),       # three 64-row stages per block
+    ((8192, 2048, 128, 32, 8, 8), 4096, torch.float32, {}, False),        # 32-row blocks
+])
+def test_the_kernel_with_several_output_blocks_per_wave_takes_the_shapes_it_says(params, n, dtype, kw, stacked):
+    p = plan(params, n, dtype, **kw)
+    assert bool(p["flags"] & ST) == stacked, p
+    if stacked:
+        assert (p["variant"], p["mode"], p["workspace_bytes"]) == (MFMA, OUT, 0), p

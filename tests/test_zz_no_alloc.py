@@ -29,6 +29,7 @@ CASES = [
     ((32768, 64, 4096, 8, 8, 2), torch.float16, 256, 64, 2),      # gradient-shaped blocks, row splits
     ((8192, 1024, 512, 64, 4, 8), torch.float32, 520, 130, 1),    # output-stationary: table only
     ((4096, 6144, 64, 96, 2, 4), torch.bfloat16, 65, 9, 0),       # general kernel: no scratch at all
+    ((8192, 4096, 128, 64, 4, 8), torch.float32, 3584, 3072, 1),  # four output blocks per wave: table only
 ]
 
 
