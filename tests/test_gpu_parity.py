@@ -789,6 +789,7 @@ def test_apply_on_a_side_stream_and_profile_brackets():
     ((8192, 1024, 512, 64, 4, 8), 512, 512),     # OUT-stationary, direct store
     ((8192, 2048, 64, 16, 16, 2), 512, 256),     # slot groups
     ((4096, 1024, 1024, 256, 2, 8), 512, 256),   # 128-row slices of a 256-row block, split stages
+    ((8192, 4096, 128, 64, 4, 8), 7168, 3584),   # four output blocks per wave
 ])
 def test_chunked_apply_replays_from_a_hip_graph(params, n, chunk):
     """The apply only enqueues kernels once a handle has run once (workspace and orbit table
