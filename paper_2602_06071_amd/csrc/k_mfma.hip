@@ -156,7 +156,12 @@ Plan make_plan(const SketchParams& p, const void* A, int64_t lda, int64_t n, fs_
     // fill the chip (small n), as long as the extra plane traffic stays below that of reading A
     const int total_stages = (int)((int64_t)p.kappa * blk_stages);
     int zo = 1;
-    while ((int64_t)p.M * col_tiles * nsub * zo < 512 && zo < 8 && total_stages % (zo * 2) == 0 &&
+    // (16-bit shapes of the kernel with work-group-shared Phi tiles, which has no row splits: once
+    // its work-groups of 512 columns cover five eighths of the CUs it beats the split form;
+    // measured on wide at n = 2560 and 3072: 0.20 against 0.25 and 0.26 ms, at n = 2048: 0.19 against 0.15 ms)
+    const bool keep_whole = nsub == 1 && !pl.unal && (int64_t)p.M * ((n + 511) / 512) >= 160 &&
+                            outs_supported(p, A, lda, n, dt);
+    while (!keep_whole && (int64_t)p.M * col_tiles * nsub * zo < 512 && zo < 8 && total_stages % (zo * 2) == 0 &&
            2.0 * (zo * 2) * (double)p.k * 4.0 / ((double)p.d * esz) <= 1.0)
       zo *= 2;
     pl.mt = mt_o; pl.nrg = nrg_o; pl.zsplit = zo; pl.nsub = nsub;

@@ -572,8 +572,9 @@ bool stacked_supported(const SketchParams& p, const void* A, int64_t lda, int64_
   if (spb * KC * lda * (int64_t)esz >= ((int64_t)1 << 31)) return false;
   const int64_t col_tiles = (n + 255) / 256;
   if (col_tiles > 65535) return false;
-  // enough work-groups for the chip: one per CU (they hold 4 SIMDs with one wave each)
-  return (int64_t)(p.M / S) * col_tiles >= 192;
+  // enough work-groups (they hold a CU each: 4 SIMDs with one wave each) to beat the kernels that
+  // split rows instead; measured cross-over on the mid shape: half the CUs
+  return (int64_t)(p.M / S) * col_tiles >= 128;
 }
 
 hipError_t launch_stacked(const SketchParams& p, const void* A, int64_t lda, int64_t n, void* out, int64_t ldo,

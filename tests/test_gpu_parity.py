@@ -248,7 +248,7 @@ def test_shared_phi_kernel_matches_oracle(case, dtype):
 
 # --------------------- several output blocks per wave ----------------------
 STACKED = [
-    # params (d,k,Bc,Br,kappa,s), n, lda pad, ldo pad, dtypes, taken.  The kernel wants at least 192
+    # params (d,k,Bc,Br,kappa,s), n, lda pad, ldo pad, dtypes, taken.  The kernel wants at least 128
     # work-groups of (4 or 2 output blocks) x 256 columns, so M and n are larger than elsewhere.
     ((8192, 4096, 128, 64, 4, 8), 3584, 0, 0, "f32 bf16 f16", True),     # kappa = S = 4: one phase of one block, three of two
     ((8192, 4096, 128, 64, 8, 8), 3070, 2, 3, "f32 bf16", True),         # kappa = 8; ragged last tile, padded rows, element stores
@@ -261,7 +261,8 @@ STACKED = [
     ((16384, 8192, 256, 128, 2, 8), 2048, 0, 0, "bf16", False),          # 16-bit, 128 rows: one block per work-group is faster
     ((8192, 4096, 128, 64, 6, 8), 3072, 0, 0, "f32", False),             # kappa not a multiple of the slot count
     ((8192, 4096, 128, 64, 4, 8), 3071, 1, 0, "f32", False),             # odd n
-    ((8192, 4096, 128, 64, 4, 8), 2048, 0, 0, "f32", False),             # too few work-groups for the chip
+    ((8192, 4096, 128, 64, 4, 8), 1792, 0, 0, "f32", False),             # too few work-groups for the chip
+    ((8192, 4096, 128, 64, 4, 8), 2048, 0, 0, "f32", True),              # exactly the 128 it asks for
     ((12288, 4096, 192, 64, 4, 8), 3072, 0, 0, "f32", False),           # an odd number of stages per block
 ]
 _DT = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}

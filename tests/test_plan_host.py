@@ -127,7 +127,8 @@ def test_plan_honours_the_forced_variant_and_reports_errors():
     ((16384, 1024, 1024, 64, 2, 8), 16384, torch.float32, {}, False),     # fewer permutations than slots
     ((16384, 1024, 1024, 64, 4, 8), 16383, torch.float32, {"ld": 16384}, False),  # odd n
     ((16384, 1024, 1024, 64, 4, 8), 16384, torch.float32, {"address": 260}, False),  # A not aligned to 2 columns
-    ((16384, 1024, 1024, 64, 4, 8), 8192, torch.float32, {}, False),      # 4 groups x 32 column tiles: too few work-groups
+    ((16384, 1024, 1024, 64, 4, 8), 8192, torch.float32, {}, True),       # 4 groups x 32 column tiles: the 128 work-groups it asks for
+    ((16384, 1024, 1024, 64, 4, 8), 7936, torch.float32, {}, False),      # 4 x 31: too few
     ((12288, 4096, 192, 64, 4, 8), 4096, torch.float32, {}, False),       # three 64-row stages per block
     ((8192, 2048, 128, 32, 8, 8), 4096, torch.float32, {}, False),        # 32-row blocks
 ])
