@@ -97,12 +97,13 @@ hipError_t launch_mfma(const SketchParams& p, const void* A, int64_t lda, int64_
                        EventPair ev, int* mode, char* desc, size_t desc_cap);
 
 // Output-stationary matrix-core kernel with Phi tiles shared by a work-group (16-bit types, blocks
-// exactly 32, 64 or 128 rows high, no row splits): whether it takes the call, its dynamic LDS, and
-// its launch.  It stores the result itself: no workspace.
-bool outs_supported(const SketchParams& p, const void* A, int64_t lda, int64_t n, fs_dtype dt);
+// exactly 32, 64 or 128 rows high): whether it takes the call with a given row split, and its
+// launch.  Without a row split it stores the result itself; with one, work-group z writes plane z
+// of the workspace and the caller runs the plane reduction.
+bool outs_supported(const SketchParams& p, const void* A, int64_t lda, int64_t n, fs_dtype dt, int zsplit);
 hipError_t launch_outs(const SketchParams& p, const void* A, int64_t lda, int64_t n, void* out, int64_t ldo,
-                       fs_dtype dt, const uint32_t* orbit, hipStream_t st, EventPair ev, char* desc,
-                       size_t desc_cap);
+                       fs_dtype dt, const uint32_t* orbit, int zsplit, float* ws, int64_t ldw, hipStream_t st,
+                       EventPair ev, char* desc, size_t desc_cap);
 
 // Matrix-core kernel that keeps several output blocks, consecutive on the orbit of the wiring, in one
 // wave's accumulators (blocks exactly 64 rows high, or 128 for fp32; the slot count divides kappa and

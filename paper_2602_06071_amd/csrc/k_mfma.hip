@@ -156,12 +156,17 @@ Plan make_plan(const SketchParams& p, const void* A, int64_t lda, int64_t n, fs_
     // fill the chip (small n), as long as the extra plane traffic stays below that of reading A
     const int total_stages = (int)((int64_t)p.kappa * blk_stages);
     int zo = 1;
-    // (16-bit shapes of the kernel with work-group-shared Phi tiles, which has no row splits: once
-    // its work-groups of 512 columns cover five eighths of the CUs it beats the split form;
-    // measured on wide at n = 2560 and 3072: 0.20 against 0.25 and 0.26 ms, at n = 2048: 0.19 against 0.15 ms)
-    const bool keep_whole = nsub == 1 && !pl.unal && (int64_t)p.M * ((n + 511) / 512) >= 160 &&
-                            outs_supported(p, A, lda, n, dt);
-    while (!keep_whole && (int64_t)p.M * col_tiles * nsub * zo < 512 && zo < 8 && total_stages % (zo * 2) == 0 &&
+    // 16-bit shapes of the kernel with work-group-shared Phi tiles: its work-groups cover 512
+    // columns and hold a CU each, so it wants a row split that brings their number to between
+    // five eighths of the CUs and all of them (measured on wide: n = 2560 and 3072 whole, 0.20 ms
+    // against 0.25 and 0.26 ms split; n = 1536 in 2 splits, n = 1024 in 4)
+    const int64_t shared_wgs = (int64_t)p.M * ((n + 511) / 512);
+    const bool shared_phi = nsub == 1 && !pl.unal && outs_supported(p, A, lda, n, dt, 1);
+    auto enough = [&](int z) {
+      return shared_phi ? shared_wgs * z >= 160 : (int64_t)p.M * col_tiles * nsub * z >= 512;
+    };
+    // (the split must divide the stages; the shared-Phi kernel wants an even number per work-group)
+    while (!enough(zo) && zo < 8 && total_stages % (zo * 2 * (shared_phi ? 2 : 1)) == 0 &&
            2.0 * (zo * 2) * (double)p.k * 4.0 / ((double)p.d * esz) <= 1.0)
       zo *= 2;
     pl.mt = mt_o; pl.nrg = nrg_o; pl.zsplit = zo; pl.nsub = nsub;
@@ -175,7 +180,7 @@ Plan make_plan(const SketchParams& p, const void* A, int64_t lda, int64_t n, fs_
   if (pl.mt == 4 && dt != FS_F32 && pl.stages % 2 == 0 && !pl.unal) pl.pfx = 2;
   // 16-bit output-stationary shapes without row splits or slices go to the kernel whose work-group
   // shares its Phi tiles (measured on the "wide" workload: 0.445 against 0.52 ms)
-  pl.outs = !pl.in_stat && pl.zsplit == 1 && pl.nsub == 1 && !pl.unal && outs_supported(p, A, lda, n, dt);
+  pl.outs = !pl.in_stat && pl.nsub == 1 && !pl.unal && outs_supported(p, A, lda, n, dt, pl.zsplit);
   // Shapes the kernel with several output blocks per wave takes go there (it loads A from L2
   // (kappa+S-1)/S times per output block, not kappa times; measured on "mid": kappa = 4, 0.365
   // against 0.395 ms, kappa = 8, 0.63 against 0.74 ms).  It stores the result itself.
@@ -221,6 +226,29 @@ size_t mfma_workspace_bytes(const SketchParams& p, int64_t n, fs_dtype dt) {
   return (size_t)pl.planes * (size_t)p.k * (size_t)pl.ldw * sizeof(float);
 }
 
+// The fixed-order sum of the partial planes into the output, scaled and converted.
+static hipError_t launch_reduce(const SketchParams& p, const Plan& pl, int64_t n, void* out, int64_t ldo,
+                                fs_dtype dt, float* ws, const uint32_t* orbit, hipStream_t st) {
+  const size_t esz = dt == FS_F32 ? 4 : 2;
+  const int out_vec = ((uintptr_t)out % (4 * esz) == 0 && (ldo * esz) % (4 * esz) == 0) ? 1 : 0;
+  const int64_t work = p.k * (pl.ldw / 4);
+  const unsigned blocks = (unsigned)((work + 255) / 256);
+  const uint32_t* blk2pos = orbit ? orbit + p.M : nullptr;
+  if (dt == FS_BF16)
+    hipLaunchKernelGGL(reduce_planes_kernel<uint16_t>, dim3(blocks), dim3(256), 0, st, ws, pl.planes,
+                       p.k, pl.ldw, (int)n, (uint16_t*)out, ldo, p.scale, out_vec, pl.run, blk2pos,
+                       p.Br, p.kappa);
+  else if (dt == FS_F16)
+    hipLaunchKernelGGL(reduce_planes_kernel<f16>, dim3(blocks), dim3(256), 0, st, ws, pl.planes,
+                       p.k, pl.ldw, (int)n, (f16*)out, ldo, p.scale, out_vec, pl.run, blk2pos,
+                       p.Br, p.kappa);
+  else
+    hipLaunchKernelGGL(reduce_planes_kernel<float>, dim3(blocks), dim3(256), 0, st, ws, pl.planes,
+                       p.k, pl.ldw, (int)n, (float*)out, ldo, p.scale, out_vec, pl.run, blk2pos,
+                       p.Br, p.kappa);
+  return hipGetLastError();
+}
+
 hipError_t launch_mfma(const SketchParams& p, const void* A, int64_t lda, int64_t n, void* out,
                        int64_t ldo, fs_dtype dt, void* ws, const uint32_t* orbit, hipStream_t st,
                        EventPair ev, int* mode, char* desc, size_t desc_cap) {
@@ -228,7 +256,12 @@ hipError_t launch_mfma(const SketchParams& p, const void* A, int64_t lda, int64_
   if (!pl.ok) return hipErrorInvalidValue;
   *mode = !pl.in_stat ? 1 : pl.run > 1 ? 3 : 2;
   if (pl.stacked) return launch_stacked(p, A, lda, n, out, ldo, dt, orbit, st, ev, desc, desc_cap);
-  if (pl.outs) return launch_outs(p, A, lda, n, out, ldo, dt, orbit, st, ev, desc, desc_cap);
+  hipError_t e;
+  if (pl.outs) {
+    e = launch_outs(p, A, lda, n, out, ldo, dt, orbit, pl.zsplit, (float*)ws, pl.ldw, st, ev, desc, desc_cap);
+    if (e != hipSuccess || pl.planes == 0) return e;
+    return launch_reduce(p, pl, n, out, ldo, dt, (float*)ws, orbit, st);
+  }
   if (desc && desc_cap)  // the template arguments of the instantiation launched below, in order
     snprintf(desc, desc_cap, "mfma_kernel<%s,%d,%d,%d,%s,%d,%d,%d,%s,%s>%s",
              dt == FS_F32 ? "f32" : dt == FS_BF16 ? "bf16" : "f16", pl.mt, pl.nrg, pl.ncg,
@@ -250,29 +283,13 @@ hipError_t launch_mfma(const SketchParams& p, const void* A, int64_t lda, int64_
   dim3 grid(p.M / pl.run, col_tiles * pl.nsub, pl.zsplit * pl.groups);
 
   if (ev.start) (void)hipEventRecord(ev.start, st);
-  hipError_t e;
   if (dt == FS_BF16) e = pl.unal ? launch_mfma_bf16_unal(pl, a, grid, st) : launch_mfma_bf16(pl, a, grid, st);
   else if (dt == FS_F16) e = pl.unal ? launch_mfma_f16_unal(pl, a, grid, st) : launch_mfma_f16(pl, a, grid, st);
   else e = pl.unal ? launch_mfma_f32_unal(pl, a, grid, st) : launch_mfma_f32(pl, a, grid, st);
   if (ev.stop) (void)hipEventRecord(ev.stop, st);
   if (e != hipSuccess || pl.planes == 0) return e;
 
-  const int64_t work = p.k * (pl.ldw / 4);
-  const unsigned blocks = (unsigned)((work + 255) / 256);
-  const uint32_t* blk2pos = orbit ? orbit + p.M : nullptr;
-  if (dt == FS_BF16)
-    hipLaunchKernelGGL(reduce_planes_kernel<uint16_t>, dim3(blocks), dim3(256), 0, st, a.ws, pl.planes,
-                       p.k, pl.ldw, (int)n, (uint16_t*)out, ldo, p.scale, a.out_vec, pl.run, blk2pos,
-                       p.Br, p.kappa);
-  else if (dt == FS_F16)
-    hipLaunchKernelGGL(reduce_planes_kernel<f16>, dim3(blocks), dim3(256), 0, st, a.ws, pl.planes,
-                       p.k, pl.ldw, (int)n, (f16*)out, ldo, p.scale, a.out_vec, pl.run, blk2pos,
-                       p.Br, p.kappa);
-  else
-    hipLaunchKernelGGL(reduce_planes_kernel<float>, dim3(blocks), dim3(256), 0, st, a.ws, pl.planes,
-                       p.k, pl.ldw, (int)n, (float*)out, ldo, p.scale, a.out_vec, pl.run, blk2pos,
-                       p.Br, p.kappa);
-  return hipGetLastError();
+  return launch_reduce(p, pl, n, out, ldo, dt, a.ws, orbit, st);
 }
 
 }  // namespace fs

@@ -46,6 +46,12 @@ struct OutsArgs {
   int n;
   int spb;      // stages per input block: ceil(Bc / KC)
   int out_vec;  // out rows allow 4-column vector stores
+  // row split: work-group z (grid.z) takes the stages [z*stages, (z+1)*stages) of the kappa*spb
+  // stages of its output block and, when there is more than one, stores its unscaled fp32 sums to
+  // plane z of ws (k x ldw floats each) for the fixed-order reduction kernel
+  int zsplit, stages;
+  float* ws;
+  int64_t ldw;
 };
 
 template <typename T, int MT, int NW>
@@ -132,9 +138,11 @@ void outs_kernel(OutsArgs a) {
 
   // ---- the three cursors -------------------------------------------------------------------
   // loads (PFS stages ahead of the MFMAs): descriptor of the block, lane offset, stage in block
-  __amdgpu_buffer_rsrc_t f_rs = make_rsrc(__builtin_amdgcn_readfirstlane(s_hblk[0]));
-  uint32_t f_voff = voff0, f_us = 0, f_l = 0;
   const uint32_t spb = (uint32_t)a.spb;
+  const uint32_t t0 = blockIdx.z * (uint32_t)a.stages;  // first stage of this work-group
+  uint32_t f_us = t0 % spb, f_l = t0 / spb;
+  uint32_t f_voff = voff0 + f_us * (uint32_t)KSTEPS * kstep_bytes;
+  __amdgpu_buffer_rsrc_t f_rs = make_rsrc(__builtin_amdgcn_readfirstlane(s_hblk[f_l]));
   V ld[PFD][8];
 #ifdef FS_ABLATE_LOADS
   bool loads_on = true;  // ablation build: only the prologue loads A, the ring keeps that data
@@ -156,7 +164,7 @@ void outs_kernel(OutsArgs a) {
     }
   };
   // Phi (one stage ahead): key of the block, stage in block
-  uint32_t p_key = __builtin_amdgcn_readfirstlane(s_key[0]), p_us = 0, p_l = 0;
+  uint32_t p_us = t0 % spb, p_l = t0 / spb, p_key = __builtin_amdgcn_readfirstlane(s_key[p_l]);
   const uint32_t sh_col = (uint32_t)(wave * KW + lane % KW), sh_j = (uint32_t)(lane / KW);
   // byte offsets inside a tile: this lane's K-column, and a pad column that no MFMA reads
   const uint32_t sh_colb = sh_col * 2u;
@@ -287,7 +295,7 @@ void outs_kernel(OutsArgs a) {
   read_pa(s_phi, 0, pa2[0]);
   using P0 = std::integral_constant<int, 0>;
   using P1 = std::integral_constant<int, 1>;
-  const int n_stages = (int)(p.kappa * spb);  // even, >= 4 (checked on the host)
+  const int n_stages = a.stages;  // even, >= 2 (checked on the host)
   for (int t = 0; t + 2 < n_stages; t += 2) {
     stage(P0{}, std::true_type{}, std::true_type{});
     stage(P1{}, std::true_type{}, std::true_type{});
@@ -303,6 +311,19 @@ void outs_kernel(OutsArgs a) {
   // accumulator register i of tile (mt, c) holds block row mt*32 + 8*(i/4) + 4*kg + i%4 of column
   // col0 + c
   if (col0 >= a.n) return;
+  if (a.zsplit > 1) {  // a partial sum: plane blockIdx.z (ldw is a multiple of 4 and col0 + 3 < ldw)
+    float* plane = a.ws + (int64_t)blockIdx.z * p.k * a.ldw;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const uint32_t row = (uint32_t)(mt * 32 + 8 * (i >> 2) + 4 * kg + (i & 3));
+        *reinterpret_cast<float4*>(plane + ((int64_t)blk * p.Br + row) * a.ldw + col0) =
+            make_float4(acc[mt][0][i], acc[mt][1][i], acc[mt][2][i], acc[mt][3][i]);
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
@@ -344,9 +365,9 @@ hipError_t launch_t(int nw, dim3 grid, size_t lds, hipStream_t st, const OutsArg
 }  // namespace
 
 // Shapes this kernel takes (the caller has already chosen the output-stationary decomposition
-// without row splits or slices): 16-bit type, Br = 32, 64 or 128, vector-aligned A, an even
+// without slices, and the row split): 16-bit type, Br = 32, 64 or 128, vector-aligned A, an even
 // number >= 4 of stages, more than one wave of columns, offsets that fit 32 bits.
-bool outs_supported(const SketchParams& p, const void* A, int64_t lda, int64_t n, fs_dtype dt) {
+bool outs_supported(const SketchParams& p, const void* A, int64_t lda, int64_t n, fs_dtype dt, int zsplit) {
   if (dt == FS_F32) return false;
   if (p.Br != 32 && p.Br != 64 && p.Br != 128) return false;
   if (p.kappa > (uint32_t)MAX_KAPPA || n <= WCOLS) return false;
@@ -354,6 +375,7 @@ bool outs_supported(const SketchParams& p, const void* A, int64_t lda, int64_t n
   const int64_t spb = ((int64_t)p.Bc + KC - 1) / KC;
   const int64_t T = spb * p.kappa;
   if (T < 4 || T % 2) return false;
+  if (zsplit < 1 || T % zsplit || (T / zsplit) % 2) return false;  // an even number of stages per work-group
   if ((16 * lda + n) * 2 >= ((int64_t)1 << 31)) return false;
   if (spb * KC * lda * 2 >= ((int64_t)1 << 31)) return false;
   const int nw = n > 2 * WCOLS ? 4 : 2;
@@ -362,21 +384,24 @@ bool outs_supported(const SketchParams& p, const void* A, int64_t lda, int64_t n
 }
 
 hipError_t launch_outs(const SketchParams& p, const void* A, int64_t lda, int64_t n, void* out, int64_t ldo,
-                       fs_dtype dt, const uint32_t* orbit, hipStream_t st, EventPair ev, char* desc,
-                       size_t desc_cap) {
+                       fs_dtype dt, const uint32_t* orbit, int zsplit, float* ws, int64_t ldw, hipStream_t st,
+                       EventPair ev, char* desc, size_t desc_cap) {
   OutsArgs a;
   a.p = p; a.A = A; a.out = out; a.pos2blk = orbit;
   a.lda = lda; a.ldo = ldo; a.n = (int)n;
   a.spb = (int)(((int64_t)p.Bc + KC - 1) / KC);
   a.out_vec = ((uintptr_t)out % 8 == 0 && (ldo * 2) % 8 == 0) ? 1 : 0;
+  a.zsplit = zsplit; a.stages = (int)((int64_t)a.spb * p.kappa / zsplit); a.ws = ws; a.ldw = ldw;
+  if (zsplit > 1 && (!ws || ldw % 4 || ldw < n)) return hipErrorInvalidValue;
   const int nw = n > 2 * WCOLS ? 4 : 2;
   const int mt = (int)p.Br / 32;
   const int tnw = WCOLS * nw;
   const unsigned col_tiles = (unsigned)((n + tnw - 1) / tnw);
   const size_t lds = 2 * MAX_KAPPA * 4 + 2 * (size_t)(32 * mt) * PHI_LD * 2;
-  dim3 grid(p.M, col_tiles, 1);
+  dim3 grid(p.M, col_tiles, zsplit);
   if (desc && desc_cap)
-    snprintf(desc, desc_cap, "outs_kernel<%s,%d,%d>", dt == FS_BF16 ? "bf16" : "f16", mt, nw);
+    snprintf(desc, desc_cap, "outs_kernel<%s,%d,%d>%s", dt == FS_BF16 ? "bf16" : "f16", mt, nw,
+             zsplit > 1 ? "+reduce_planes" : "");
   if (ev.start) (void)hipEventRecord(ev.start, st);
   hipError_t e;
 #define FS_T(T)                                                           \

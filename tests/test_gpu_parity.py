@@ -203,7 +203,8 @@ OUTS = [
     ((6144, 4096, 192, 128, 2, 4), 300, 0, 0, True),     # three stages per block, kappa = 2: six stages
     ((16384, 8192, 256, 128, 2, 8), 260, 0, 0, True),    # M = 64: orbit renumbering over many blocks
     ((4096, 1024, 256, 64, 4, 8), 530, 0, 0, False),     # rows not aligned to 4 columns: element loads
-    ((16384, 1024, 2048, 128, 4, 8), 520, 0, 0, False),  # few output tiles: rows split over grid.z
+    ((16384, 1024, 2048, 128, 4, 8), 520, 0, 0, True),   # few output tiles: rows split over grid.z, partial planes
+    ((8192, 512, 1024, 64, 8, 8), 300, 4, 3, True),      # the same with 64-row blocks, kappa = M, padded rows
     ((6144, 4096, 192, 128, 1, 4), 300, 0, 0, False),    # an odd number of stages
     ((4096, 1024, 256, 64, 4, 8), 100, 0, 0, False),     # a single wave of columns
 ]
@@ -584,8 +585,8 @@ def test_full_config_mid_sampled(kappa):
 
 @pytest.mark.parametrize("n", W.WIDE_NS)
 def test_full_config_wide_sampled(n):
-    """The bf16 width sweep at full d: n = 1024 and 2048 split the rows of a work-group over
-    grid.z (partial planes), 4096 and 8192 run the shared-Phi kernel."""
+    """The bf16 width sweep at full d on the shared-Phi kernel: n = 1024 and 2048 split the rows of
+    a work-group over grid.z (partial planes and the reduction), 4096 and 8192 store directly."""
     import dataclasses
     cfg = dataclasses.replace(W.CONFIGS["wide"], n=n)
     print("full wide n", n, flush=True)
@@ -593,7 +594,8 @@ def test_full_config_wide_sampled(n):
     sk = B.Sketch(*cfg.params, seed=cfg.sketch_seed)
     out = sk.apply(A)
     torch.cuda.synchronize()
-    assert sk.info().last_kernel.decode().startswith("outs_kernel") == (n >= 4096), sk.info().last_kernel
+    kernel = sk.info().last_kernel.decode()
+    assert kernel.startswith("outs_kernel") and kernel.endswith("+reduce_planes") == (n < 4096), kernel
     _sampled_parity(cfg, A, out)
     if n in (1024, 8192):
         _all_columns_against_the_general_kernel(sk, A, out)
