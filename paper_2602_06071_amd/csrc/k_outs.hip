@@ -19,6 +19,10 @@
 //    the k-step advances one VGPR offset, and the three cursors (loads PFS stages ahead, Phi one
 //    stage ahead, MFMAs) are counters stepped once per stage.
 //
+//  * Too few (output block, column tile) pairs for the chip: grid.z splits the kappa*spb stages of
+//    an output block, work-group z takes the stages [z*stages, (z+1)*stages) and stores unscaled
+//    fp32 sums to plane z; the fixed-order reduction kernel scales, converts and stores.
+//
 // A goes HBM -> registers -> v_perm transpose -> MFMA B operand exactly as in mfma_kernel.
 // Inputs must be finite (a dense product also multiplies by the zeros of Phi).
 //
