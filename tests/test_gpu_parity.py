@@ -1092,6 +1092,56 @@ def test_random_shapes_wide_draw_both_layouts(dtype):
     assert ("cols", B.VARIANT_GENERIC, 0, 0) in seen
 
 
+def _random_cases_many_work_groups(count, seed):
+    """Shapes with enough (block, column tile) pairs for the kernels that want a chip full of
+    work-groups: output-stationary with shared Phi tiles (whole and row-split), several output
+    blocks per wave."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    while len(cases) < count:
+        Br = int(rng.choice([32, 64, 64, 128, 128]))
+        M = int(rng.choice([4, 8, 16, 32, 64, 64, 128]))
+        Bc = int(rng.choice([128, 200, 256, 384, 512, 1000, 1024]))
+        kappa = min(int(rng.choice([2, 4, 4, 6, 8, 8, 12, 16])), M)
+        s = min(int(rng.choice([1, 2, 3, 8, 8, 12, 20, 32])), Br)
+        n = int(rng.choice([132, 256, 520, 1024, 1028, 1536, 2048, 2050, 3072, 4096, 4100, 6144]))
+        d = M * Bc - int(rng.choice([0, 0, 0, 7, Bc // 3]))
+        if d * n > 6e7:
+            n = max(130, int(6e7 // d) // 2 * 2)
+        cases.append(((d, M * Br, Bc, Br, kappa, s), n, int(rng.choice([0, 0, 2, 4, 3])), int(rng.integers(0, 2 ** 62))))
+    return cases
+
+
+@DTYPES
+def test_random_shapes_many_work_groups(dtype):
+    """70 seeded draws at sizes where the dispatcher picks the kernels built for full chips.  All
+    columns against the general kernel on the device (two implementations that share only the
+    hash recipe), 24 sampled columns against the oracle."""
+    kernels = set()
+    for params, n, pad, seed in _random_cases_many_work_groups(70, 4242):
+        print("random many", params, n, pad, seed, dtype, flush=True)
+        g = torch.Generator(device=DEV).manual_seed(seed % (2 ** 31))
+        A = torch.randn((params[0], n + pad), generator=g, device=DEV).to(dtype)[:, :n]
+        sk = B.Sketch(*params, seed=seed)
+        out = sk.apply(A)
+        kern = sk.info().last_kernel.decode()
+        kernels.add(kern.split("<")[0] + ("+reduce" if kern.endswith("+reduce_planes") else ""))
+        sk.set_variant(B.VARIANT_GENERIC)
+        other = sk.apply(A)
+        sk.set_variant(B.VARIANT_AUTO)
+        torch.cuda.synchronize()
+        a, b = out.float(), other.float()
+        assert float((a - b).norm() / b.norm()) <= TOL[dtype], (params, n, kern)
+        cols = np.unique(np.r_[0, n - 1, np.random.default_rng(seed % 1000).integers(0, n, 22)])
+        ref = O.apply(oracle_csc(params, seed), host64(A[:, torch.from_numpy(cols).to(DEV)]))
+        check(out[:, torch.from_numpy(cols).to(DEV)], ref, dtype, f"{params} n={n} {kern}")
+        sk.close()
+    want = {"stacked_kernel", "mfma_kernel", "mfma_kernel+reduce"}
+    if dtype != torch.float32:
+        want |= {"outs_kernel", "outs_kernel+reduce"}
+    assert want <= kernels, kernels
+
+
 @pytest.mark.parametrize("variant", [B.VARIANT_AUTO, B.VARIANT_GENERIC], ids=lambda v: VNAME[v])
 @DTYPES
 def test_random_shapes_match_oracle(dtype, variant):
