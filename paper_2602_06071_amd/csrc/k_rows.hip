@@ -430,21 +430,38 @@ __global__ __launch_bounds__(256) void reduce_rows_kernel(const float* __restric
   float s[VEC];
 #pragma unroll
   for (int c = 0; c < VEC; ++c) s[c] = 0.f;
-  uint32_t rec = bi;
-  for (uint32_t l = 0; l < p.kappa; ++l) {
-    if (orbit) rec = rec + 1 == p.M ? 0u : rec + 1;
-    else rec = wire_next(rec, p.a, p.b, p.M);
-    const uint32_t grp = l / group_slots;  // the set of records that holds slot l, and where in a record
-    const float* ph = src + (int64_t)grp * zsplit * z_stride + (int64_t)rec * rw + ((l - grp * group_slots) << lbr);
-    for (int zc = 0; zc < zsplit; ++zc) {
-      if constexpr (VEC == 4) {
-        const float4 v = *reinterpret_cast<const float4*>(ph + zc * z_stride);
-        s[0] += v.x; s[1] += v.y; s[2] += v.z; s[3] += v.w;
-      } else {
-        s[0] += ph[zc * z_stride];
+  // The kappa * zsplit addends in the order (slot l, row split z), four at a time: their loads are
+  // issued together, then added in that order.  (One load per pass of a loop made the kernel wait
+  // for memory once per addend.)
+  using Vec = std::conditional_t<VEC == 4, float4, float>;
+  const uint32_t total = p.kappa * (uint32_t)zsplit;
+  uint32_t rec = bi, l = 0, zc = 0, lg = 0, grp = 0;  // record of slot l; l = grp * group_slots + lg
+  rec = orbit ? (rec + 1 == p.M ? 0u : rec + 1) : wire_next(rec, p.a, p.b, p.M);
+  for (uint32_t t0 = 0; t0 < total; t0 += 4) {
+    Vec v[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      // (past the last addend the cursor stays on it: the load is valid and ignored)
+      const float* ph = src + ((int64_t)grp * zsplit + zc) * z_stride + (int64_t)rec * rw + (lg << lbr);
+      v[j] = *reinterpret_cast<const Vec*>(ph);
+      if (t0 + j + 1 < total) {
+        if (++zc == (uint32_t)zsplit) {
+          zc = 0;
+          ++l;
+          if (++lg == group_slots) { lg = 0; ++grp; }
+          rec = orbit ? (rec + 1 == p.M ? 0u : rec + 1) : wire_next(rec, p.a, p.b, p.M);
+        }
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (t0 + j < total) {
+        if constexpr (VEC == 4) { s[0] += v[j].x; s[1] += v[j].y; s[2] += v[j].z; s[3] += v[j].w; }
+        else s[0] += v[j];
       }
     }
   }
+  (void)l;
   T* dst = out + ex * ldo + (int64_t)g * p.Br + r;
 #pragma unroll
   for (int c = 0; c < VEC; ++c) s[c] *= p.scale;
