@@ -682,21 +682,23 @@ __global__ __launch_bounds__(256) void reduce_planes_kernel(const float* __restr
   if (run > 1) rho_k = (blk2pos[row / Br] % (uint32_t)run + kappa) % (uint32_t)run;
   const float* src = ws + row * ldw + col0;
   float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-  // Four planes at a time: their loads are issued together (from a clamped, always valid plane
-  // index; a plane that does not count is loaded and ignored), then added in index order.  One
-  // load per pass of a loop made this kernel wait for memory once per plane.
-  for (int p0 = 0; p0 < planes; p0 += 4) {
+  // The planes that count are planes 0 .. nvalid-1 (RUN > 1: once a plane is empty the later ones
+  // are too).  Four at a time: their loads are issued together, then added in index order; past
+  // the last one the load repeats it (a cache hit) and is ignored.  One load per pass of a loop
+  // made this kernel wait for memory once per plane.
+  int nvalid = planes;
+  if (run > 1) {
+    nvalid = 0;
+    while (nvalid < planes && (int)(nvalid * run + rho_k) - (int)kappa <= run - 2) ++nvalid;
+  }
+  for (int p0 = 0; p0 < nvalid; p0 += 4) {
     float4 v[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j)
-      v[j] = *reinterpret_cast<const float4*>(src + (int64_t)min(p0 + j, planes - 1) * k * ldw);
+      v[j] = *reinterpret_cast<const float4*>(src + (int64_t)min(p0 + j, nvalid - 1) * k * ldw);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int pl = p0 + j;
-      // (RUN > 1: once a plane is empty the later ones are too)
-      const bool on = pl < planes && !(run > 1 && (int)(pl * run + rho_k) - (int)kappa > run - 2);
-      if (on) { s.x += v[j].x; s.y += v[j].y; s.z += v[j].z; s.w += v[j].w; }
-    }
+    for (int j = 0; j < 4; ++j)
+      if (p0 + j < nvalid) { s.x += v[j].x; s.y += v[j].y; s.z += v[j].z; s.w += v[j].w; }
   }
   float v[4] = {s.x * scale, s.y * scale, s.z * scale, s.w * scale};
   T* dst = out + row * ldo + col0;
