@@ -421,6 +421,26 @@ def grad_side_measurements(torch, B, cfg, A, out, steps=10):
         del bufs, o
     except B.FlashSketchError as e:
         res["grad_packed_chunks_lda256"] = {"error": str(e)}
+    # (3) What a library reduction reads per second from one CONTIGUOUS 2 GiB chunk (torch.max over
+    # its int32 view: every byte read once, 8 bytes written): a reference point for the stream
+    # rate of this machine, next to the 512-of-every-2048-bytes view the apply reads.
+    try:
+        flat = A[:, :w].contiguous().view(torch.int32)
+        for _ in range(3):
+            flat.max()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        torch.cuda.synchronize()
+        ev[0].record()
+        for _ in range(8):
+            flat.max()
+        ev[1].record()
+        torch.cuda.synchronize()
+        ms = ev[0].elapsed_time(ev[1]) / 8
+        res["contiguous_chunk_read_by_torch_max"] = {"ms": ms, "GBps": chunk_cfg.a_bytes / ms / 1e6,
+                                                     "pct_hbm_peak": 100.0 * chunk_cfg.a_bytes / ms / 1e6 / HBM_PEAK_GBPS}
+        del flat
+    except RuntimeError as e:
+        res["contiguous_chunk_read_by_torch_max"] = {"error": str(e)}
     return res
 
 
